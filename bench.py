@@ -1,0 +1,164 @@
+#!/usr/bin/env python3
+"""Benchmark of the Fast-SNARF articulation hot path on one MI355X.
+
+One "step" = one pass of the whole path over one synthetic batch that is already resident in
+HBM: fs_precompute -> fs_init -> fs_solve (keeping J~ and iteration counts) -> fs_grad.
+Workload: the SMPL-scale single-pose configuration (24 bones, 64x64x16 weight grid,
+65,536 query points x 24 per-bone initial states, max 50 iterations, tol 1e-5).
+
+Prints ONE JSON line.  `value` = converged (point, init) root solves per second over the whole
+step.  `roofline` describes the Broyden solve kernel (the dominant one), timed with events on
+the stream it runs on.  `cpu_baseline` is the CPU oracle timed on this machine's host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# algorithmic fp32 operation counts of the method (one fused multiply-add = 2), from the arithmetic
+# the solver is defined by: one field evaluation and residual, one Broyden update, one step
+FLOP_EVAL = 237      # locate 12, corner weights 19, 8x12 tri-linear blend 180, T x 18, g 3, |g|^2 5
+FLOP_UPDATE = 63     # dg 3, v = J~^T dx 15, u = dx - J~ dg 18, v.dg 5, divide 1, u/den 3, rank-one 18
+FLOP_STEP = 18       # dx = -J~ g 15, x + dx 3
+PEAK_FP32_TFLOPS = 157.3
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="workload configuration 1..5 (default 2: SMPL-scale)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-grad", action="store_true", help="leave fs_grad out of the step")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (lanes are independent; see DESIGN.md for how the "
+              "path would shard); rerun with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2211_15601_amd import binding, workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    binding.load()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    w = wl.make_config(args.config)
+    N, K = w.N, w.K
+    ctx = binding.Context(w.dims, w.n_bones, w.lo, w.hi, n_poses=w.n_poses, tol=w.tol, div_thresh=w.div_thresh,
+                          max_iters=w.max_iters, init_mode=w.init_mode, grad_mode=binding.FS_GRAD_BROYDEN_J,
+                          corr_dims=w.corr_dims)
+    up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    W, B, xq = up(w.W), up(w.B), up(w.xq)
+    pose = up(w.pose) if w.n_poses > 1 else None
+    gxc = up(w.upstream_grads())
+    f32, u8 = torch.float32, torch.uint8
+    x0 = torch.empty((K, 3, N), dtype=f32, device=dev)
+    J0 = torch.empty((K, 9, N), dtype=f32, device=dev)
+    v0 = torch.empty((K, N), dtype=u8, device=dev)
+    xc = torch.empty((K, 3, N), dtype=f32, device=dev)
+    Jo = torch.empty((K, 9, N), dtype=f32, device=dev)
+    cv = torch.empty((K, N), dtype=u8, device=dev)
+    it = torch.empty((K, N), dtype=u8, device=dev)
+    gW = torch.empty(w.W.shape, dtype=f32, device=dev)
+    gB = torch.empty(w.B.shape, dtype=f32, device=dev)
+    gxq = torch.empty((3, N), dtype=f32, device=dev)
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    marks = []
+
+    def step(record):
+        e = [ev() for _ in range(5)] if record else None
+        if record: e[0].record()
+        ctx.precompute(W, B)
+        if record: e[1].record()
+        ctx.init(xq, pose, N, x0, J0, v0)
+        if record: e[2].record()
+        ctx.solve(xq, pose, N, K, x0, J0, v0, xc, cv, Jo, it)
+        if record: e[3].record()
+        if not args.no_grad:
+            ctx.grad(W, xc, Jo, cv, gxc, pose, N, K, gW, gB, gxq)
+        if record: e[4].record()
+        if record: marks.append(e)
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    phases = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(4)] for e in marks])   # ms
+    pre_ms, init_ms, solve_ms, grad_ms = phases.mean(0)
+
+    conv = int(cv.sum().item())
+    valid = int(v0.sum().item())
+    steps_total = int(it.to(torch.int64)[v0 == 1].sum().item())
+    evals = steps_total + valid                       # field evaluations = active lane-iterations
+    flops = evals * FLOP_EVAL + steps_total * (FLOP_UPDATE + FLOP_STEP)
+    achieved = flops / (solve_ms * 1e-3) / 1e12
+
+    out = {
+        "metric": "converged (point, init) root solves/sec",
+        "value": conv / (ms_per_step * 1e-3),
+        "unit": "solves/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"config {args.config} ({w.name}): grid {w.dims[0]}x{w.dims[1]}x{w.dims[2]}, "
+                               f"{w.n_bones} bones, {w.n_poses} pose(s), {N} points x {K} inits, "
+                               f"max_iters {w.max_iters}, tol {w.tol}",
+                   "step": "fs_precompute + fs_init + fs_solve" + ("" if args.no_grad else " + fs_grad"),
+                   "pairs": N * K, "valid_pairs": valid, "converged_pairs": conv,
+                   "lane_iterations": evals},
+        "breakdown_ms": {"fs_precompute": float(pre_ms), "fs_init": float(init_ms), "fs_solve": float(solve_ms),
+                         "fs_grad": float(grad_ms)},
+        "solve_only": {"converged_solves_per_s": conv / (solve_ms * 1e-3),
+                       "lane_iterations_per_s": evals / (solve_ms * 1e-3)},
+        "roofline": {"kernel": "k_solve", "bound": "alu", "achieved": achieved, "peak": PEAK_FP32_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_TFLOPS, "traffic": None,
+                     "flop_per_launch": flops, "avg_launch_ms": float(solve_ms)},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        ncores = len(os.sched_getaffinity(0))
+        pz = w.pose if w.n_poses > 1 else None
+        best = None
+        for rep in range(2):
+            c0 = time.perf_counter()
+            T = oracle.precompute(w.dims, w.W, w.B, prec="f32")
+            if w.init_mode == 0:
+                a0, b0, c0v = oracle.init_bone(w.dims, w.lo, w.hi, T, w.B, w.xq, pose=pz, prec="f32")
+            else:
+                bb, cd = oracle.corr_build(w.dims, w.lo, w.hi, T, w.corr_dims, prec="f32")
+                a0, b0, c0v = oracle.init_voxel(w.dims, w.lo, w.hi, T, w.corr_dims, bb, cd, w.xq, pose=pz, prec="f32")
+            oxc, ocv, oJ, oit = oracle.solve(w.dims, w.lo, w.hi, T, w.xq, a0, b0, c0v, pose=pz, tol=w.tol,
+                                             div_thresh=w.div_thresh, max_iters=w.max_iters, prec="f32")
+            if not args.no_grad:
+                oracle.grad(w.dims, w.lo, w.hi, T, w.W, w.B, oxc, oJ, ocv, w.upstream_grads(), pose=pz, mode=0, prec="f32")
+            dt = time.perf_counter() - c0
+            best = dt if best is None else min(best, dt)
+        out["cpu_baseline"] = {"value": int(ocv.sum()) / best, "unit": "solves/s", "cores": ncores, "kind": "oracle",
+                               "sample": "the whole workload of this run, same step (strict-fp32 oracle, best of 2 passes)",
+                               "seconds": best}
+        out["parity_spot_check"] = {"conv_equal": bool((ocv == cv.cpu().numpy()).all())}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,160 @@
+"""Thin ctypes binding of the C-ABI library (include/fastsnarf.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels.  PyTorch supplies
+device memory (`tensor.data_ptr()`) and the current HIP stream.  There is no CPU fallback: if the
+library has not been built, `load()` raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "csrc", "libfastsnarf.so")
+
+FS_OK, FS_E_ARG, FS_E_SHAPE, FS_E_STATE, FS_E_ALLOC, FS_E_DEVICE, FS_E_UNSUPPORTED = range(7)
+STATUS_NAMES = ["FS_OK", "FS_E_ARG", "FS_E_SHAPE", "FS_E_STATE", "FS_E_ALLOC", "FS_E_DEVICE", "FS_E_UNSUPPORTED"]
+FS_INIT_BONE, FS_INIT_VOXEL = 0, 1
+FS_GRAD_BROYDEN_J, FS_GRAD_EXACT_J = 0, 1
+
+EXPORTS = ["fs_create", "fs_destroy", "fs_set_params", "fs_precompute", "fs_init", "fs_solve", "fs_grad",
+           "fs_get_transforms", "fs_get_corr", "fs_last_error", "fs_version"]
+
+
+class GridDesc(ctypes.Structure):
+    _fields_ = [("nx", ctypes.c_int32), ("ny", ctypes.c_int32), ("nz", ctypes.c_int32),
+                ("n_bones", ctypes.c_int32), ("n_poses", ctypes.c_int32),
+                ("lo", ctypes.c_float * 3), ("hi", ctypes.c_float * 3)]
+
+
+class Params(ctypes.Structure):
+    _fields_ = [("tol", ctypes.c_float), ("div_thresh", ctypes.c_float), ("max_iters", ctypes.c_int32),
+                ("init_mode", ctypes.c_int32), ("grad_mode", ctypes.c_int32),
+                ("corr_nx", ctypes.c_int32), ("corr_ny", ctypes.c_int32), ("corr_nz", ctypes.c_int32),
+                ("corr_k", ctypes.c_int32)]
+
+
+class FsError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"{STATUS_NAMES[status] if 0 <= status < 7 else status}: {msg}")
+        self.status = status
+
+
+_lib = None
+
+
+def load():
+    """dlopen the HIP library and declare its prototypes.  Raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} not found: build it with `python -m paper_2211_15601_amd.build` "
+                           "(there is no CPU fallback)")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+    L.fs_create.argtypes = [ctypes.POINTER(GridDesc), ctypes.POINTER(Params), vp, ctypes.POINTER(vp)]
+    L.fs_destroy.argtypes = [vp]
+    L.fs_set_params.argtypes = [vp, ctypes.POINTER(Params)]
+    L.fs_precompute.argtypes = [vp, vp, vp]
+    L.fs_init.argtypes = [vp, vp, vp, i64, vp, vp, vp]
+    L.fs_solve.argtypes = [vp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp]
+    L.fs_grad.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, vp, vp, vp]
+    L.fs_get_transforms.argtypes = [vp, vp]
+    L.fs_get_corr.argtypes = [vp, vp, vp]
+    L.fs_last_error.argtypes = [vp]
+    L.fs_last_error.restype = ctypes.c_char_p
+    L.fs_version.argtypes = []
+    L.fs_version.restype = ctypes.c_char_p
+    for name in EXPORTS[:9]:
+        getattr(L, name).restype = ctypes.c_int
+    _lib = L
+    return L
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+class Context:
+    """One fs_ctx.  Methods mirror the C entry points one to one and return the raw status when
+    `check=False`, else raise FsError on a non-OK status."""
+
+    def __init__(self, dims, n_bones, lo, hi, n_poses=1, tol=1e-5, div_thresh=10.0, max_iters=50,
+                 init_mode=FS_INIT_BONE, grad_mode=FS_GRAD_BROYDEN_J, corr_dims=(32, 32, 8, 3), stream=None):
+        L = load()
+        self._L = L
+        self.desc = GridDesc(int(dims[0]), int(dims[1]), int(dims[2]), int(n_bones), int(n_poses),
+                             (ctypes.c_float * 3)(*[float(v) for v in lo]),
+                             (ctypes.c_float * 3)(*[float(v) for v in hi]))
+        self.params = Params(float(tol), float(div_thresh), int(max_iters), int(init_mode), int(grad_mode),
+                             int(corr_dims[0]), int(corr_dims[1]), int(corr_dims[2]), int(corr_dims[3]))
+        if stream is None:
+            stream = torch.cuda.current_stream().cuda_stream
+        self.stream = int(stream)
+        h = ctypes.c_void_p()
+        st = L.fs_create(ctypes.byref(self.desc), ctypes.byref(self.params), ctypes.c_void_p(self.stream),
+                         ctypes.byref(h))
+        if st != FS_OK:
+            raise FsError(st, "fs_create failed")
+        self._h = h
+        self.K = int(n_bones) if init_mode == FS_INIT_BONE else int(corr_dims[3])
+        self.V = int(dims[0]) * int(dims[1]) * int(dims[2])
+
+    def _ret(self, st, check):
+        if check and st != FS_OK:
+            raise FsError(st, self.last_error())
+        return st
+
+    def last_error(self) -> str:
+        return self._L.fs_last_error(self._h).decode()
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h:
+            self._L.fs_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def set_params(self, tol=None, div_thresh=None, max_iters=None, grad_mode=None, check=True):
+        p = self.params
+        if tol is not None: p.tol = float(tol)
+        if div_thresh is not None: p.div_thresh = float(div_thresh)
+        if max_iters is not None: p.max_iters = int(max_iters)
+        if grad_mode is not None: p.grad_mode = int(grad_mode)
+        return self._ret(self._L.fs_set_params(self._h, ctypes.byref(p)), check)
+
+    def precompute(self, W, B, check=True):
+        return self._ret(self._L.fs_precompute(self._h, _ptr(W), _ptr(B)), check)
+
+    def init(self, xq, pose, N, x0, Jinv0, valid0, check=True):
+        return self._ret(self._L.fs_init(self._h, _ptr(xq), _ptr(pose), N, _ptr(x0), _ptr(Jinv0), _ptr(valid0)), check)
+
+    def solve(self, xq, pose, N, K, x0, Jinv0, valid0, xc, conv, Jinv=None, iters=None, check=True):
+        return self._ret(self._L.fs_solve(self._h, _ptr(xq), _ptr(pose), N, K, _ptr(x0), _ptr(Jinv0), _ptr(valid0),
+                                          _ptr(xc), _ptr(conv), _ptr(Jinv), _ptr(iters)), check)
+
+    def grad(self, W, xc, Jinv, conv, gxc, pose, N, K, gW, gB, gxq=None, check=True):
+        return self._ret(self._L.fs_grad(self._h, _ptr(W), _ptr(xc), _ptr(Jinv), _ptr(conv), _ptr(gxc), _ptr(pose),
+                                         N, K, _ptr(gW), _ptr(gB), _ptr(gxq)), check)
+
+    def get_transforms(self, T, check=True):
+        return self._ret(self._L.fs_get_transforms(self._h, _ptr(T)), check)
+
+    def get_corr(self, bbox, cand, check=True):
+        return self._ret(self._L.fs_get_corr(self._h, _ptr(bbox), _ptr(cand)), check)
+
+
+def version() -> str:
+    return load().fs_version().decode()

@@ -1,0 +1,366 @@
+// C ABI of the Fast-SNARF articulation library (see include/fastsnarf.h): argument checks,
+// context-owned device buffers and kernel launches.  gfx950 only.
+#include "../../include/fastsnarf.h"
+#include "fs_kernels.hpp"
+
+#include <hip/hip_runtime.h>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+using namespace fs;
+
+struct fs_ctx {
+    fs_grid_desc desc;
+    fs_params prm;
+    hipStream_t stream;
+    int device;
+    GridP G;
+    CorrP C;
+    bool have_T;
+    // device buffers owned by the context
+    float *T;          // [P][V][12]
+    float *Bdev;       // [P][nb][12] copy of the bone transforms of the last precompute
+    float *Binv;       // [P][nb][12]
+    uint8_t *Bok;      // [P][nb]
+    float *GT;         // [P][V][12] gradient w.r.t. the transform grid (allocated on first fs_grad)
+    // correspondence grid (voxel init)
+    float *Y;          // [P][V][3]
+    unsigned *bb_ord;  // [P][6]
+    float *bbox;       // [P][6]
+    int *cell_of;      // [P][V]
+    int *count;        // [P*ncell + 1] counts, then offsets
+    int *fill;         // [P*ncell]
+    int *order;        // [P][V]
+    int32_t *cand;     // [P][ncell][ck]
+    char err[256];
+};
+
+namespace {
+
+fs_status fail(fs_ctx *c, fs_status s, const char *fmt, ...)
+{
+    if (c) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(c->err, sizeof c->err, fmt, ap);
+        va_end(ap);
+    }
+    return s;
+}
+
+bool device_ptr_ok(const fs_ctx *c, const void *p, bool nullable)
+{
+    if (!p) return nullable;
+    if ((reinterpret_cast<uintptr_t>(p) & 15u) != 0) return false;
+    hipPointerAttribute_t a;
+    if (hipPointerGetAttributes(&a, p) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    if (a.type != hipMemoryTypeDevice && a.type != hipMemoryTypeManaged) return false;
+    return a.device == c->device;
+}
+
+#define FS_CHECK_PTR(ctx, p, nullable)                                                            \
+    do {                                                                                          \
+        if (!device_ptr_ok((ctx), (p), (nullable)))                                               \
+            return fail((ctx), FS_E_ARG, "%s: " #p " must be a 16-byte aligned device pointer%s", \
+                        __func__, (nullable) ? " or NULL" : "");                                  \
+    } while (0)
+
+fs_status launch_status(fs_ctx *c, const char *what)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(c, FS_E_DEVICE, "%s: %s", what, hipGetErrorString(e));
+    return FS_OK;
+}
+
+template <class Tp>
+bool dev_alloc(Tp **p, size_t count)
+{
+    *p = nullptr;
+    if (count == 0) return true;
+    if (hipMalloc(reinterpret_cast<void **>(p), count * sizeof(Tp)) != hipSuccess) {
+        (void)hipGetLastError();
+        *p = nullptr;
+        return false;
+    }
+    return true;
+}
+
+bool params_ok(const fs_params *p, char *why, size_t n)
+{
+    if (!(p->tol > 0.0f) || !(p->div_thresh > p->tol) || !std::isfinite(p->div_thresh)) {
+        snprintf(why, n, "need 0 < tol < div_thresh < inf");
+        return false;
+    }
+    if (p->max_iters < 0 || p->max_iters > 255) { snprintf(why, n, "max_iters must be in 0..255"); return false; }
+    if (p->grad_mode != FS_GRAD_BROYDEN_J && p->grad_mode != FS_GRAD_EXACT_J) {
+        snprintf(why, n, "bad grad_mode");
+        return false;
+    }
+    return true;
+}
+
+int grid1d(long long n, int block) { return (int)((n + block - 1) / block); }
+
+void free_all(fs_ctx *c)
+{
+    void *ptrs[] = {c->T, c->Bdev, c->Binv, c->Bok, c->GT, c->Y, c->bb_ord, c->bbox,
+                    c->cell_of, c->count, c->fill, c->order, c->cand};
+    for (void *p : ptrs)
+        if (p) (void)hipFree(p);
+}
+
+int lanes_K(const fs_ctx *c) { return c->prm.init_mode == FS_INIT_BONE ? c->desc.n_bones : c->prm.corr_k; }
+
+}  // namespace
+
+extern "C" {
+
+const char *fs_version(void) { return "fastsnarf-mi355x 0.1 (gfx950)"; }
+
+const char *fs_last_error(const fs_ctx *ctx) { return ctx ? ctx->err : "null context"; }
+
+fs_status fs_create(const fs_grid_desc *desc, const fs_params *params, void *hip_stream, fs_ctx **out)
+{
+    if (out) *out = nullptr;
+    if (!desc || !params || !out) return FS_E_ARG;
+    if (desc->nx < 2 || desc->ny < 2 || desc->nz < 2 || desc->n_bones < 1 || desc->n_bones > FS_MAX_BONES ||
+        desc->n_poses < 1 || desc->n_poses > FS_MAX_POSES)
+        return FS_E_SHAPE;
+    const long long V = (long long)desc->nx * desc->ny * desc->nz;
+    if (V * 12 >= (1ll << 31)) return FS_E_SHAPE;
+    if (desc->n_poses * desc->n_bones > 1024) return FS_E_UNSUPPORTED;   /* bone tables are staged in 48 KiB of LDS */
+    for (int a = 0; a < 3; ++a)
+        if (!(desc->hi[a] > desc->lo[a]) || !std::isfinite(desc->hi[a]) || !std::isfinite(desc->lo[a])) return FS_E_ARG;
+    char why[128];
+    if (!params_ok(params, why, sizeof why)) return FS_E_ARG;
+    if (params->init_mode != FS_INIT_BONE && params->init_mode != FS_INIT_VOXEL) return FS_E_ARG;
+    if (params->init_mode == FS_INIT_VOXEL) {
+        if (params->corr_nx < 1 || params->corr_ny < 1 || params->corr_nz < 1 || params->corr_k < 1 ||
+            params->corr_k > FS_MAX_CORR_K)
+            return FS_E_SHAPE;
+        if ((long long)params->corr_nx * params->corr_ny * params->corr_nz * desc->n_poses >= (1ll << 24)) return FS_E_SHAPE;
+    }
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return FS_E_DEVICE;
+    }
+    fs_ctx *c = new (std::nothrow) fs_ctx;
+    if (!c) return FS_E_ALLOC;
+    std::memset(c, 0, sizeof *c);
+    c->desc = *desc;
+    c->prm = *params;
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    c->device = dev;
+    GridP &G = c->G;
+    G.nx = desc->nx; G.ny = desc->ny; G.nz = desc->nz; G.nb = desc->n_bones; G.P = desc->n_poses;
+    G.sy = desc->nz * 12;
+    G.sx = desc->ny * desc->nz * 12;
+    G.V = V;
+    const int n[3] = {desc->nx, desc->ny, desc->nz};
+    for (int a = 0; a < 3; ++a) {
+        G.lo[a] = desc->lo[a];
+        G.hi[a] = desc->hi[a];
+        G.inv_h[a] = (float)(n[a] - 1) / (desc->hi[a] - desc->lo[a]);
+        G.h[a] = (desc->hi[a] - desc->lo[a]) / (float)(n[a] - 1);
+        G.m[a] = (float)(n[a] - 1);
+    }
+    const size_t P = desc->n_poses, nb = desc->n_bones;
+    bool ok = dev_alloc(&c->T, P * V * 12) && dev_alloc(&c->Bdev, P * nb * 12) && dev_alloc(&c->Binv, P * nb * 12) &&
+              dev_alloc(&c->Bok, P * nb);
+    if (ok && params->init_mode == FS_INIT_VOXEL) {
+        CorrP &C = c->C;
+        C.cx = params->corr_nx; C.cy = params->corr_ny; C.cz = params->corr_nz; C.ck = params->corr_k;
+        C.ncell = C.cx * C.cy * C.cz;
+        ok = dev_alloc(&c->Y, P * V * 3) && dev_alloc(&c->bb_ord, P * 6) && dev_alloc(&c->bbox, P * 6) &&
+             dev_alloc(&c->cell_of, P * V) && dev_alloc(&c->count, P * C.ncell + 1) && dev_alloc(&c->fill, P * C.ncell) &&
+             dev_alloc(&c->order, P * V) && dev_alloc(&c->cand, P * (size_t)C.ncell * C.ck);
+    }
+    if (!ok) {
+        free_all(c);
+        delete c;
+        return FS_E_ALLOC;
+    }
+    *out = c;
+    return FS_OK;
+}
+
+fs_status fs_destroy(fs_ctx *ctx)
+{
+    if (!ctx) return FS_OK;
+    (void)hipStreamSynchronize(ctx->stream);
+    free_all(ctx);
+    delete ctx;
+    return FS_OK;
+}
+
+fs_status fs_set_params(fs_ctx *ctx, const fs_params *params)
+{
+    if (!ctx) return FS_E_ARG;
+    if (!params) return fail(ctx, FS_E_ARG, "fs_set_params: params is NULL");
+    char why[128];
+    if (!params_ok(params, why, sizeof why)) return fail(ctx, FS_E_ARG, "fs_set_params: %s", why);
+    ctx->prm.tol = params->tol;
+    ctx->prm.div_thresh = params->div_thresh;
+    ctx->prm.max_iters = params->max_iters;
+    ctx->prm.grad_mode = params->grad_mode;
+    return FS_OK;
+}
+
+fs_status fs_precompute(fs_ctx *ctx, const float *d_W, const float *d_B)
+{
+    if (!ctx) return FS_E_ARG;
+    FS_CHECK_PTR(ctx, d_W, false);
+    FS_CHECK_PTR(ctx, d_B, false);
+    const GridP &G = ctx->G;
+    const int nB = G.P * G.nb * 12;
+    hipStream_t st = ctx->stream;
+    if (hipMemcpyAsync(ctx->Bdev, d_B, sizeof(float) * nB, hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return launch_status(ctx, "fs_precompute: copy of bone transforms");
+    k_bone_inverse<<<grid1d(G.P * G.nb, 64), 64, 0, st>>>(G.P * G.nb, d_B, ctx->Binv, ctx->Bok);
+    k_precompute<<<grid1d(G.V, 256), 256, sizeof(float) * nB, st>>>(G, d_W, d_B, ctx->T);
+    if (ctx->prm.init_mode == FS_INIT_VOXEL) {
+        const CorrP &C = ctx->C;
+        const int ncp = G.P * C.ncell;
+        k_corr_reset<<<grid1d(ncp > G.P * 3 ? ncp : G.P * 3, 256), 256, 0, st>>>(G.P, C.ncell, ctx->bb_ord, ctx->count, ctx->fill);
+        const dim3 gv(grid1d(G.V, 256), G.P);
+        k_corr_warp<<<gv, 256, 0, st>>>(G, ctx->T, ctx->Y, ctx->bb_ord);
+        k_corr_bbox<<<1, 64 * ((G.P * 6 + 63) / 64), 0, st>>>(G.P, ctx->bb_ord, ctx->bbox);
+        k_corr_count<<<gv, 256, 0, st>>>(G, C, ctx->Y, ctx->bbox, ctx->cell_of, ctx->count);
+        k_scan_exclusive<<<1, 1024, 0, st>>>(ncp, ctx->count);
+        k_corr_scatter<<<gv, 256, 0, st>>>(G, C, ctx->cell_of, ctx->count, ctx->fill, ctx->order);
+        k_corr_select<<<grid1d((long long)ncp * WAVE, 256), 256, 0, st>>>(G, C, ctx->Y, ctx->bbox, ctx->count, ctx->order, ctx->cand);
+    }
+    fs_status s = launch_status(ctx, "fs_precompute");
+    if (s == FS_OK) ctx->have_T = true;
+    return s;
+}
+
+fs_status fs_init(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_t N, float *d_x0, float *d_Jinv0,
+                  uint8_t *d_valid0)
+{
+    if (!ctx) return FS_E_ARG;
+    if (!ctx->have_T) return fail(ctx, FS_E_STATE, "fs_init: call fs_precompute first");
+    const int K = lanes_K(ctx);
+    if (N < 0 || (long long)N * K >= (1ll << 31)) return fail(ctx, FS_E_SHAPE, "fs_init: need 0 <= N and K*N < 2^31");
+    if (N == 0) return FS_OK;
+    if (ctx->desc.n_poses > 1 && !d_pose) return fail(ctx, FS_E_ARG, "fs_init: d_pose is required when n_poses > 1");
+    FS_CHECK_PTR(ctx, d_xq, false);
+    FS_CHECK_PTR(ctx, d_pose, true);
+    FS_CHECK_PTR(ctx, d_x0, false);
+    FS_CHECK_PTR(ctx, d_Jinv0, false);
+    FS_CHECK_PTR(ctx, d_valid0, false);
+    const long long total = (long long)N * K;
+    if (ctx->prm.init_mode == FS_INIT_BONE)
+        k_init_bone<<<grid1d(total, 256), 256, 0, ctx->stream>>>(ctx->G, ctx->T, ctx->Binv, ctx->Bok, d_xq, d_pose, N,
+                                                                 d_x0, d_Jinv0, d_valid0);
+    else
+        k_init_voxel<<<grid1d(total, 256), 256, 0, ctx->stream>>>(ctx->G, ctx->C, ctx->T, ctx->bbox, ctx->cand, d_xq,
+                                                                  d_pose, N, d_x0, d_Jinv0, d_valid0);
+    return launch_status(ctx, "fs_init");
+}
+
+fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_t N, int32_t K, const float *d_x0,
+                   const float *d_Jinv0, const uint8_t *d_valid0, float *d_xc, uint8_t *d_conv, float *d_Jinv,
+                   uint8_t *d_iters)
+{
+    if (!ctx) return FS_E_ARG;
+    if (!ctx->have_T) return fail(ctx, FS_E_STATE, "fs_solve: call fs_precompute first");
+    if (K != lanes_K(ctx)) return fail(ctx, FS_E_SHAPE, "fs_solve: K = %d but the init mode produces %d lanes per point", K, lanes_K(ctx));
+    if (N < 0 || (long long)N * K >= (1ll << 31)) return fail(ctx, FS_E_SHAPE, "fs_solve: need 0 <= N and K*N < 2^31");
+    if (N == 0) return FS_OK;
+    if (ctx->desc.n_poses > 1 && !d_pose) return fail(ctx, FS_E_ARG, "fs_solve: d_pose is required when n_poses > 1");
+    FS_CHECK_PTR(ctx, d_xq, false);
+    FS_CHECK_PTR(ctx, d_pose, true);
+    FS_CHECK_PTR(ctx, d_x0, false);
+    FS_CHECK_PTR(ctx, d_Jinv0, false);
+    FS_CHECK_PTR(ctx, d_valid0, false);
+    FS_CHECK_PTR(ctx, d_xc, false);
+    FS_CHECK_PTR(ctx, d_conv, false);
+    FS_CHECK_PTR(ctx, d_Jinv, true);
+    FS_CHECK_PTR(ctx, d_iters, true);
+    SolveP S;
+    S.N = N;
+    S.total = (long long)N * K;
+    S.max_iters = ctx->prm.max_iters;
+    S.tol2 = ctx->prm.tol * ctx->prm.tol;
+    S.div2 = ctx->prm.div_thresh * ctx->prm.div_thresh;
+    S.chunk = 1024;
+    S.refill_min = 16;
+    const long long waves = (S.total + S.chunk - 1) / S.chunk;
+    const int wpb = 4;
+    k_solve<<<grid1d(waves, wpb), wpb * WAVE, 0, ctx->stream>>>(ctx->G, S, ctx->T, d_xq, d_pose, d_x0, d_Jinv0, d_valid0,
+                                                                d_xc, d_conv, d_Jinv, d_iters);
+    return launch_status(ctx, "fs_solve");
+}
+
+fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float *d_Jinv, const uint8_t *d_conv,
+                  const float *d_gxc, const int32_t *d_pose, int64_t N, int32_t K, float *d_gW, float *d_gB,
+                  float *d_gxq)
+{
+    if (!ctx) return FS_E_ARG;
+    if (!ctx->have_T) return fail(ctx, FS_E_STATE, "fs_grad: call fs_precompute first");
+    if (K < 1 || K > FS_MAX_BONES) return fail(ctx, FS_E_SHAPE, "fs_grad: K out of range");
+    if (N < 0 || (long long)N * K >= (1ll << 31)) return fail(ctx, FS_E_SHAPE, "fs_grad: need 0 <= N and K*N < 2^31");
+    if (ctx->desc.n_poses > 1 && !d_pose && N > 0) return fail(ctx, FS_E_ARG, "fs_grad: d_pose is required when n_poses > 1");
+    const int mode = ctx->prm.grad_mode;
+    FS_CHECK_PTR(ctx, d_W, false);
+    FS_CHECK_PTR(ctx, d_gW, false);
+    FS_CHECK_PTR(ctx, d_gB, false);
+    FS_CHECK_PTR(ctx, d_gxq, true);
+    if (N > 0) {
+        FS_CHECK_PTR(ctx, d_xc, false);
+        FS_CHECK_PTR(ctx, d_Jinv, mode == FS_GRAD_EXACT_J);
+        FS_CHECK_PTR(ctx, d_conv, false);
+        FS_CHECK_PTR(ctx, d_gxc, false);
+        FS_CHECK_PTR(ctx, d_pose, true);
+    }
+    const GridP &G = ctx->G;
+    if (!ctx->GT && !dev_alloc(&ctx->GT, (size_t)G.P * G.V * 12)) return fail(ctx, FS_E_ALLOC, "fs_grad: out of device memory");
+    hipStream_t st = ctx->stream;
+    const long long nGT = (long long)G.P * G.V * 12;
+    k_fill_zero<<<(int)std::min<long long>(grid1d(nGT, 256), 4096), 256, 0, st>>>(nGT, ctx->GT);
+    k_fill_zero<<<grid1d(G.P * G.nb * 12, 256), 256, 0, st>>>((long long)G.P * G.nb * 12, d_gB);
+    if (d_gxq && N > 0) k_fill_zero<<<(int)std::min<long long>(grid1d(3 * N, 256), 4096), 256, 0, st>>>(3 * (long long)N, d_gxq);
+    if (N > 0)
+        k_grad_scatter<<<grid1d((long long)N * K, 256), 256, 0, st>>>(G, mode, ctx->T, d_xc, d_Jinv, d_conv, d_gxc, d_pose,
+                                                                      N, K, ctx->GT, d_gxq);
+    const size_t shB = sizeof(float) * G.P * G.nb * 12;
+    k_grad_weights<<<grid1d(G.V * G.nb, 256), 256, shB, st>>>(G, ctx->GT, ctx->Bdev, d_gW);
+    const dim3 gb(grid1d(G.V, GB_TILE), G.P);
+    k_grad_bones<<<gb, 256, sizeof(float) * GB_TILE * (G.nb + 12), st>>>(G, d_W, ctx->GT, d_gB);
+    return launch_status(ctx, "fs_grad");
+}
+
+fs_status fs_get_transforms(fs_ctx *ctx, float *d_T)
+{
+    if (!ctx) return FS_E_ARG;
+    if (!ctx->have_T) return fail(ctx, FS_E_STATE, "fs_get_transforms: call fs_precompute first");
+    FS_CHECK_PTR(ctx, d_T, false);
+    if (hipMemcpyAsync(d_T, ctx->T, sizeof(float) * ctx->G.P * ctx->G.V * 12, hipMemcpyDeviceToDevice, ctx->stream) != hipSuccess)
+        return launch_status(ctx, "fs_get_transforms");
+    return FS_OK;
+}
+
+fs_status fs_get_corr(fs_ctx *ctx, float *d_bbox, int32_t *d_cand)
+{
+    if (!ctx) return FS_E_ARG;
+    if (ctx->prm.init_mode != FS_INIT_VOXEL) return fail(ctx, FS_E_STATE, "fs_get_corr: context was not created with FS_INIT_VOXEL");
+    if (!ctx->have_T) return fail(ctx, FS_E_STATE, "fs_get_corr: call fs_precompute first");
+    FS_CHECK_PTR(ctx, d_bbox, false);
+    FS_CHECK_PTR(ctx, d_cand, false);
+    hipError_t e = hipMemcpyAsync(d_bbox, ctx->bbox, sizeof(float) * ctx->G.P * 6, hipMemcpyDeviceToDevice, ctx->stream);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(d_cand, ctx->cand, sizeof(int32_t) * ctx->G.P * (size_t)ctx->C.ncell * ctx->C.ck,
+                           hipMemcpyDeviceToDevice, ctx->stream);
+    if (e != hipSuccess) return launch_status(ctx, "fs_get_corr");
+    return FS_OK;
+}
+
+}  // extern "C"

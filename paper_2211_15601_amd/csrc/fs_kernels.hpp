@@ -1,0 +1,550 @@
+// HIP kernels of the articulation path for gfx950 (wave64).
+#pragma once
+#include "fs_field.hpp"
+
+namespace fs {
+
+constexpr int WAVE = 64;
+constexpr int FS_MAX_CORR_K_DEV = 8;
+
+// ------------------------------------------------------------------------------------------------
+// Pre-computed LBS (Eq. (13)): one thread per node, all poses; bone transforms staged in LDS.
+// Reads W once (96 B / node for 24 bones), writes 48 B per node and pose.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_precompute(GridP G, const float *__restrict__ W,
+                                                    const float *__restrict__ B, float *__restrict__ T)
+{
+    extern __shared__ float sB[];   // [P][nb][12]
+    const int nB = G.P * G.nb * 12;
+    for (int i = threadIdx.x; i < nB; i += blockDim.x) sB[i] = B[i];
+    __syncthreads();
+    const long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= G.V) return;
+    const float *w = W + v * G.nb;
+    for (int p = 0; p < G.P; ++p) {
+        const float *Bp = sB + p * G.nb * 12;
+        float acc[12];
+        const float w0 = w[0];
+#pragma unroll
+        for (int e = 0; e < 12; ++e) acc[e] = w0 * Bp[e];
+        for (int b = 1; b < G.nb; ++b) {
+            const float wb = w[b];
+#pragma unroll
+            for (int e = 0; e < 12; ++e) acc[e] = FS_FMA(wb, Bp[b * 12 + e], acc[e]);
+        }
+        float4 *o = reinterpret_cast<float4 *>(T + ((long long)p * G.V + v) * 12);
+        o[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        o[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+        o[2] = make_float4(acc[8], acc[9], acc[10], acc[11]);
+    }
+}
+
+// Inverse of every bone's linear part for Eq. (8): Binv [P][nb][12] = 9 inverse entries + t, ok flag.
+__global__ void k_bone_inverse(int n, const float *__restrict__ B, float *__restrict__ Binv,
+                               uint8_t *__restrict__ ok)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const float *b = B + i * 12;
+    const float R[9] = {b[0], b[1], b[2], b[4], b[5], b[6], b[8], b[9], b[10]};
+    float Ri[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+    const bool good = inv3(R, Ri);
+    for (int e = 0; e < 9; ++e) Binv[i * 12 + e] = Ri[e];
+    Binv[i * 12 + 9] = b[3];
+    Binv[i * 12 + 10] = b[7];
+    Binv[i * 12 + 11] = b[11];
+    ok[i] = good ? 1 : 0;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Initial states.  One thread per lane q = k*N + n.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ void write_init(long long q, long long N, int k, long long n, const float x0[3],
+                                           const float Ji[9], bool ok, float *__restrict__ o_x0,
+                                           float *__restrict__ o_J, uint8_t *__restrict__ o_v)
+{
+#pragma unroll
+    for (int r = 0; r < 3; ++r) o_x0[((long long)k * 3 + r) * N + n] = x0[r];
+#pragma unroll
+    for (int e = 0; e < 9; ++e) o_J[((long long)k * 9 + e) * N + n] = ok ? Ji[e] : 0.0f;
+    o_v[q] = ok ? 1 : 0;
+}
+
+__global__ __launch_bounds__(256) void k_init_bone(GridP G, const float *__restrict__ T,
+                                                   const float *__restrict__ Binv, const uint8_t *__restrict__ Bok,
+                                                   const float *__restrict__ xq, const int32_t *__restrict__ pose,
+                                                   long long N, float *__restrict__ o_x0, float *__restrict__ o_J,
+                                                   uint8_t *__restrict__ o_v)
+{
+    const long long q = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= N * G.nb) return;
+    const int k = (int)(q / N);
+    const long long n = q - (long long)k * N;
+    const int p = pose ? pose[n] : 0;
+    const float *bi = Binv + ((long long)p * G.nb + k) * 12;
+    float x0[3] = {0, 0, 0}, Ji[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+    bool ok = Bok[p * G.nb + k] != 0;
+    if (ok) {
+        const float y[3] = {xq[n] - bi[9], xq[N + n] - bi[10], xq[2 * N + n] - bi[11]};
+#pragma unroll
+        for (int r = 0; r < 3; ++r)
+            x0[r] = FS_FMA(bi[r * 3 + 0], y[0], FS_FMA(bi[r * 3 + 1], y[1], bi[r * 3 + 2] * y[2]));
+        float d[3], J[9];
+        field_dJ(T + (long long)p * G.V * 12, G, x0, d, J);
+        ok = inv3(J, Ji);
+    }
+    write_init(q, N, k, n, x0, Ji, ok, o_x0, o_J, o_v);
+}
+
+struct CorrP {
+    int cx, cy, cz, ck;
+    int ncell;
+};
+
+__device__ __forceinline__ int cell_coord(float y, float blo, float cs, int n)
+{
+    if (!(cs > 0.0f)) return 0;
+    float t = (y - blo) / cs;
+    if (!(t >= 0.0f)) t = 0.0f;
+    if (t > (float)(n - 1)) t = (float)(n - 1);
+    return (int)t;
+}
+
+__device__ __forceinline__ int cell_index(const CorrP &C, const float *__restrict__ bb, const float y[3])
+{
+    const float cs0 = (bb[3] - bb[0]) / (float)C.cx;
+    const float cs1 = (bb[4] - bb[1]) / (float)C.cy;
+    const float cs2 = (bb[5] - bb[2]) / (float)C.cz;
+    return (cell_coord(y[0], bb[0], cs0, C.cx) * C.cy + cell_coord(y[1], bb[1], cs1, C.cy)) * C.cz +
+           cell_coord(y[2], bb[2], cs2, C.cz);
+}
+
+__global__ __launch_bounds__(256) void k_init_voxel(GridP G, CorrP C, const float *__restrict__ T,
+                                                    const float *__restrict__ bbox, const int32_t *__restrict__ cand,
+                                                    const float *__restrict__ xq, const int32_t *__restrict__ pose,
+                                                    long long N, float *__restrict__ o_x0, float *__restrict__ o_J,
+                                                    uint8_t *__restrict__ o_v)
+{
+    const long long q = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= N * C.ck) return;
+    const int k = (int)(q / N);
+    const long long n = q - (long long)k * N;
+    const int p = pose ? pose[n] : 0;
+    const float y[3] = {xq[n], xq[N + n], xq[2 * N + n]};
+    const int cell = cell_index(C, bbox + p * 6, y);
+    const int v = cand[((long long)p * C.ncell + cell) * C.ck + k];
+    float x0[3] = {0, 0, 0}, Ji[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+    bool ok = false;
+    if (v >= 0) {
+        node_pos(G, v, x0);
+        float d[3], J[9];
+        field_dJ(T + (long long)p * G.V * 12, G, x0, d, J);
+        ok = inv3(J, Ji);
+    }
+    write_init(q, N, k, n, x0, Ji, ok, o_x0, o_J, o_v);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Correspondence grid build (voxel-based initialisation).
+// ------------------------------------------------------------------------------------------------
+// monotone float <-> uint mapping so that min / max can use integer atomics (exact, order-free)
+__device__ __forceinline__ unsigned f2ord(float f)
+{
+    const unsigned u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float ord2f(unsigned o)
+{
+    return __uint_as_float((o & 0x80000000u) ? (o & 0x7fffffffu) : ~o);
+}
+
+__global__ void k_corr_reset(int P, int ncell, unsigned *__restrict__ bb_ord, int *__restrict__ count,
+                             int *__restrict__ fill)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < P * 3) { bb_ord[(i / 3) * 6 + i % 3] = 0xffffffffu; bb_ord[(i / 3) * 6 + 3 + i % 3] = 0u; }
+    if (i < P * ncell) { count[i] = 0; fill[i] = 0; }
+    if (i == 0) count[P * ncell] = 0;
+}
+
+// images of all nodes, y_v = T_v x_v, and their bounding box per pose
+__global__ __launch_bounds__(256) void k_corr_warp(GridP G, const float *__restrict__ T, float *__restrict__ Y,
+                                                   unsigned *__restrict__ bb_ord)
+{
+    const long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int p = blockIdx.y;
+    unsigned mn[3] = {0xffffffffu, 0xffffffffu, 0xffffffffu}, mx[3] = {0u, 0u, 0u};
+    if (v < G.V) {
+        float x[3], y[3], t[12];
+        node_pos(G, v, x);
+        load12(T + ((long long)p * G.V + v) * 12, t);
+        apply12(t, x, y);
+        float *o = Y + ((long long)p * G.V + v) * 3;
+        o[0] = y[0]; o[1] = y[1]; o[2] = y[2];
+#pragma unroll
+        for (int a = 0; a < 3; ++a) mn[a] = mx[a] = f2ord(y[a]);
+    }
+#pragma unroll
+    for (int a = 0; a < 3; ++a) {
+#pragma unroll
+        for (int s = 32; s >= 1; s >>= 1) {
+            mn[a] = min(mn[a], (unsigned)__shfl_xor((int)mn[a], s));
+            mx[a] = max(mx[a], (unsigned)__shfl_xor((int)mx[a], s));
+        }
+    }
+    if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+        for (int a = 0; a < 3; ++a) {
+            atomicMin(bb_ord + p * 6 + a, mn[a]);
+            atomicMax(bb_ord + p * 6 + 3 + a, mx[a]);
+        }
+    }
+}
+
+__global__ void k_corr_bbox(int P, const unsigned *__restrict__ bb_ord, float *__restrict__ bbox)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < P * 6) bbox[i] = ord2f(bb_ord[i]);
+}
+
+__global__ __launch_bounds__(256) void k_corr_count(GridP G, CorrP C, const float *__restrict__ Y,
+                                                    const float *__restrict__ bbox, int *__restrict__ cell_of,
+                                                    int *__restrict__ count)
+{
+    const long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int p = blockIdx.y;
+    if (v >= G.V) return;
+    const float *yp = Y + ((long long)p * G.V + v) * 3;
+    const float y[3] = {yp[0], yp[1], yp[2]};
+    const int c = cell_index(C, bbox + p * 6, y);
+    cell_of[(long long)p * G.V + v] = c;
+    atomicAdd(count + p * C.ncell + c, 1);
+}
+
+// exclusive scan of count[0..n] in place (single block; n <= a few 100k)
+__global__ __launch_bounds__(1024) void k_scan_exclusive(int n, int *__restrict__ a)
+{
+    __shared__ int part[1024];
+    const int t = threadIdx.x;
+    const int per = (n + 1023) / 1024;
+    const int s = t * per, e = min(n, s + per);
+    int sum = 0;
+    for (int i = s; i < e; ++i) sum += a[i];
+    part[t] = sum;
+    __syncthreads();
+    for (int d = 1; d < 1024; d <<= 1) {
+        const int add = t >= d ? part[t - d] : 0;
+        __syncthreads();
+        part[t] += add;
+        __syncthreads();
+    }
+    int run = part[t] - sum;
+    for (int i = s; i < e; ++i) { const int c = a[i]; a[i] = run; run += c; }
+    if (t == 1023) a[n] = part[1023];
+}
+
+__global__ __launch_bounds__(256) void k_corr_scatter(GridP G, CorrP C, const int *__restrict__ cell_of,
+                                                      const int *__restrict__ offset, int *__restrict__ fill,
+                                                      int *__restrict__ order)
+{
+    const long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int p = blockIdx.y;
+    if (v >= G.V) return;
+    const int c = p * C.ncell + cell_of[(long long)p * G.V + v];
+    const int pos = atomicAdd(fill + c, 1);
+    order[offset[c] + pos] = (int)v;
+}
+
+// One wave per cell.  Candidate j is the sample with the smallest (distance^2 of its image to the
+// cell centre, node index) among those farther than r_sep (canonical distance) from candidates
+// 0..j-1: the same set, in the same order, as visiting the samples by increasing key and accepting
+// greedily.
+__global__ __launch_bounds__(256) void k_corr_select(GridP G, CorrP C, const float *__restrict__ Y,
+                                                     const float *__restrict__ bbox, const int *__restrict__ offset,
+                                                     const int *__restrict__ order, int32_t *__restrict__ cand)
+{
+    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int lane = threadIdx.x & 63;
+    if (wave >= G.P * C.ncell) return;
+    const int p = wave / C.ncell, c = wave - p * C.ncell;
+    const float *bb = bbox + p * 6;
+    const int beg = offset[wave], end = offset[wave + 1];
+    const int ciz = c % C.cz, ciy = (c / C.cz) % C.cy, cix = c / (C.cz * C.cy);
+    const float cs0 = (bb[3] - bb[0]) / (float)C.cx;
+    const float cs1 = (bb[4] - bb[1]) / (float)C.cy;
+    const float cs2 = (bb[5] - bb[2]) / (float)C.cz;
+    const float ctr[3] = {FS_FMA((float)cix + 0.5f, cs0, bb[0]), FS_FMA((float)ciy + 0.5f, cs1, bb[1]),
+                          FS_FMA((float)ciz + 0.5f, cs2, bb[2])};
+    const float rs2 = 6.25f * FS_FMA(G.h[2], G.h[2], FS_FMA(G.h[1], G.h[1], G.h[0] * G.h[0]));
+    float acc[FS_MAX_CORR_K_DEV][3];
+    int na = 0;
+    int32_t *out = cand + (long long)wave * C.ck;
+    for (int j = 0; j < C.ck; ++j) {
+        float bkey = __builtin_inff();
+        int bv = 0x7fffffff;
+        for (int s = beg + lane; s < end; s += WAVE) {
+            const int v = order[s];
+            float x[3];
+            node_pos(G, v, x);
+            bool far = true;
+            for (int a = 0; a < na; ++a) {
+                const float ex = x[0] - acc[a][0], ey = x[1] - acc[a][1], ez = x[2] - acc[a][2];
+                const float d2 = FS_FMA(ez, ez, FS_FMA(ey, ey, ex * ex));
+                if (!(d2 > rs2)) far = false;
+            }
+            if (!far) continue;
+            const float *yp = Y + ((long long)p * G.V + v) * 3;
+            const float dx = yp[0] - ctr[0], dy = yp[1] - ctr[1], dz = yp[2] - ctr[2];
+            const float key = FS_FMA(dz, dz, FS_FMA(dy, dy, dx * dx));
+            if (key < bkey || (key == bkey && v < bv)) { bkey = key; bv = v; }
+        }
+#pragma unroll
+        for (int s = 32; s >= 1; s >>= 1) {
+            const float ok = __shfl_xor(bkey, s);
+            const int ov = __shfl_xor(bv, s);
+            if (ok < bkey || (ok == bkey && ov < bv)) { bkey = ok; bv = ov; }
+        }
+        if (bv == 0x7fffffff) break;     // wave-uniform
+        node_pos(G, bv, acc[na]);
+        ++na;
+        if (lane == 0) out[j] = bv;
+    }
+    if (lane == 0)
+        for (int j = na; j < C.ck; ++j) out[j] = -1;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Broyden solve.  Lanes are persistent: every wave owns a contiguous chunk of lanes q = k*N + n
+// and hands a new one to each SIMD lane that has finished, so that a wave does not idle behind
+// its slowest trajectory.  Every loop iteration evaluates the field once per active lane: for a
+// freshly loaded lane at x0, otherwise at x + dx followed by the rank-one update of J~.
+// ------------------------------------------------------------------------------------------------
+struct SolveP {
+    long long N;
+    long long total;     // K * N
+    int chunk;           // lanes per wave
+    int refill_min;      // refill when at least this many SIMD lanes are idle
+    int max_iters;
+    float tol2, div2;
+};
+
+__global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, const float *__restrict__ T,
+                                               const float *__restrict__ xq, const int32_t *__restrict__ pose,
+                                               const float *__restrict__ x0, const float *__restrict__ J0,
+                                               const uint8_t *__restrict__ valid0, float *__restrict__ o_x,
+                                               uint8_t *__restrict__ o_conv, float *__restrict__ o_J,
+                                               uint8_t *__restrict__ o_it)
+{
+    const int lane = threadIdx.x & 63;
+    const long long wave = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const long long c1 = min(S.total, (wave + 1) * (long long)S.chunk);
+    long long next = wave * (long long)S.chunk;      // wave-uniform cursor
+    const long long N = S.N;
+
+    bool active = false, fresh = false;
+    long long n = 0;
+    int k = 0, it = 0;
+    const float *Tp = T;
+    float xp[3] = {0, 0, 0}, x[3] = {0, 0, 0}, xt[3] = {0, 0, 0}, g[3] = {0, 0, 0}, dx[3] = {0, 0, 0};
+    float J[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+
+    while (true) {
+        const unsigned long long idle = __ballot(!active);
+        const int nidle = __popcll(idle);
+        if (next < c1 && nidle >= S.refill_min) {
+            const int rank = __popcll(idle & ((1ull << lane) - 1ull));
+            const long long q = next + rank;
+            if (!active && q < c1) {
+                k = (int)(q / N);
+                n = q - (long long)k * N;
+#pragma unroll
+                for (int r = 0; r < 3; ++r) {
+                    xp[r] = xq[r * N + n];
+                    xt[r] = x0[((long long)k * 3 + r) * N + n];
+                }
+#pragma unroll
+                for (int e = 0; e < 9; ++e) J[e] = J0[((long long)k * 9 + e) * N + n];
+                Tp = T + (long long)(pose ? pose[n] : 0) * G.V * 12;
+                it = 0;
+                if (valid0[q]) {
+                    active = true;
+                    fresh = true;
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 3; ++r) o_x[((long long)k * 3 + r) * N + n] = xt[r];
+                    o_conv[q] = 0;
+                    if (o_J) {
+#pragma unroll
+                        for (int e = 0; e < 9; ++e) o_J[((long long)k * 9 + e) * N + n] = J[e];
+                    }
+                    if (o_it) o_it[q] = 0;
+                }
+            }
+            next += min((long long)nidle, c1 - next);
+        }
+        if (!__any(active)) {
+            if (next >= c1) break;
+            continue;
+        }
+        if (active) {
+            float d[3], gn[3];
+            field_d(Tp, G, xt, d);
+#pragma unroll
+            for (int r = 0; r < 3; ++r) gn[r] = d[r] - xp[r];
+            if (!fresh) {
+                float dg[3], v[3], u[3];
+#pragma unroll
+                for (int r = 0; r < 3; ++r) dg[r] = gn[r] - g[r];
+#pragma unroll
+                for (int c = 0; c < 3; ++c) v[c] = FS_FMA(dx[2], J[6 + c], FS_FMA(dx[1], J[3 + c], dx[0] * J[c]));
+#pragma unroll
+                for (int r = 0; r < 3; ++r)
+                    u[r] = dx[r] - FS_FMA(J[r * 3 + 2], dg[2], FS_FMA(J[r * 3 + 1], dg[1], J[r * 3] * dg[0]));
+                const float den = FS_FMA(v[2], dg[2], FS_FMA(v[1], dg[1], v[0] * dg[0]));
+                if (den != 0.0f && __builtin_fabsf(den) < __builtin_inff()) {
+                    const float rinv = 1.0f / den;
+#pragma unroll
+                    for (int r = 0; r < 3; ++r) {
+                        const float s = u[r] * rinv;
+#pragma unroll
+                        for (int c = 0; c < 3; ++c) J[r * 3 + c] = FS_FMA(s, v[c], J[r * 3 + c]);
+                    }
+                }
+                ++it;
+            }
+            fresh = false;
+#pragma unroll
+            for (int r = 0; r < 3; ++r) { x[r] = xt[r]; g[r] = gn[r]; }
+            const float r2 = FS_FMA(g[2], g[2], FS_FMA(g[1], g[1], g[0] * g[0]));
+            const bool conv = r2 < S.tol2;
+            const bool done = conv || !(r2 < S.div2) || it >= S.max_iters;
+            if (done) {
+                const long long q = (long long)k * N + n;
+#pragma unroll
+                for (int r = 0; r < 3; ++r) o_x[((long long)k * 3 + r) * N + n] = x[r];
+                o_conv[q] = conv ? 1 : 0;
+                if (o_J) {
+#pragma unroll
+                    for (int e = 0; e < 9; ++e) o_J[((long long)k * 9 + e) * N + n] = J[e];
+                }
+                if (o_it) o_it[q] = (uint8_t)it;
+                active = false;
+            } else {
+#pragma unroll
+                for (int r = 0; r < 3; ++r) {
+                    dx[r] = -FS_FMA(J[r * 3 + 2], g[2], FS_FMA(J[r * 3 + 1], g[1], J[r * 3] * g[0]));
+                    xt[r] = x[r] + dx[r];
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Backward (Eq. (11)/(12), (15)).
+// ------------------------------------------------------------------------------------------------
+__global__ void k_fill_zero(long long n, float *__restrict__ a)
+{
+    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long stride = (long long)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) a[i] = 0.0f;
+}
+
+// One thread per lane: lambda = -M^T g_x, then 8 corners x 12 atomic adds into G_T.
+__global__ __launch_bounds__(256) void k_grad_scatter(GridP G, int mode, const float *__restrict__ T,
+                                                      const float *__restrict__ xc, const float *__restrict__ Jinv,
+                                                      const uint8_t *__restrict__ conv, const float *__restrict__ gxc,
+                                                      const int32_t *__restrict__ pose, long long N, int K,
+                                                      float *__restrict__ GT, float *__restrict__ gxq)
+{
+    const long long q = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= N * K) return;
+    if (!conv[q]) return;
+    const int k = (int)(q / N);
+    const long long n = q - (long long)k * N;
+    const int p = pose ? pose[n] : 0;
+    float x[3], gx[3], M[9];
+#pragma unroll
+    for (int r = 0; r < 3; ++r) {
+        x[r] = xc[((long long)k * 3 + r) * N + n];
+        gx[r] = gxc[((long long)k * 3 + r) * N + n];
+    }
+    if (mode == 0) {
+#pragma unroll
+        for (int e = 0; e < 9; ++e) M[e] = Jinv[((long long)k * 9 + e) * N + n];
+    } else {
+        float d[3], J[9];
+        field_dJ(T + (long long)p * G.V * 12, G, x, d, J);
+        if (!inv3(J, M)) return;
+    }
+    float lam[3];
+#pragma unroll
+    for (int r = 0; r < 3; ++r) lam[r] = -FS_FMA(M[6 + r], gx[2], FS_FMA(M[3 + r], gx[1], M[r] * gx[0]));
+    if (gxq) {
+#pragma unroll
+        for (int r = 0; r < 3; ++r) unsafeAtomicAdd(gxq + r * N + n, -lam[r]);
+    }
+    const Cell c = locate(G, x);
+    float om[8];
+    corner_weights(c, om);
+    float *Gp = GT + (long long)p * G.V * 12 + c.base;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+        float *o = Gp + corner_off(G, kk);
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            const float wl = om[kk] * lam[r];
+            unsafeAtomicAdd(o + r * 4 + 0, wl * x[0]);
+            unsafeAtomicAdd(o + r * 4 + 1, wl * x[1]);
+            unsafeAtomicAdd(o + r * 4 + 2, wl * x[2]);
+            unsafeAtomicAdd(o + r * 4 + 3, wl);
+        }
+    }
+}
+
+// gW[v][b] = sum_p sum_e G_T[p][v][e] B[p][b][e]; one thread per output, bones fastest so that the
+// threads of a node share its G_T record through the cache and the store is coalesced.
+__global__ __launch_bounds__(256) void k_grad_weights(GridP G, const float *__restrict__ GT,
+                                                      const float *__restrict__ B, float *__restrict__ gW)
+{
+    extern __shared__ float sB[];
+    const int nB = G.P * G.nb * 12;
+    for (int i = threadIdx.x; i < nB; i += blockDim.x) sB[i] = B[i];
+    __syncthreads();
+    const long long o = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (o >= G.V * G.nb) return;
+    const long long v = o / G.nb;
+    const int b = (int)(o - v * G.nb);
+    float acc = 0.0f;
+    for (int p = 0; p < G.P; ++p) {
+        float gt[12];
+        load12(GT + ((long long)p * G.V + v) * 12, gt);
+#pragma unroll
+        for (int e = 0; e < 12; ++e) acc = FS_FMA(gt[e], sB[(p * G.nb + b) * 12 + e], acc);
+    }
+    gW[o] = acc;
+}
+
+// gB[p][b][e] = sum_v W[v][b] G_T[p][v][e]; a block reduces a tile of nodes, then one atomic per output.
+constexpr int GB_TILE = 128;
+__global__ __launch_bounds__(256) void k_grad_bones(GridP G, const float *__restrict__ W,
+                                                    const float *__restrict__ GT, float *__restrict__ gB)
+{
+    extern __shared__ float sm[];              // sW [GB_TILE][nb] then sG [GB_TILE][12]
+    float *sW = sm;
+    float *sG = sm + GB_TILE * G.nb;
+    const int p = blockIdx.y;
+    const long long v0 = (long long)blockIdx.x * GB_TILE;
+    const int cnt = (int)min((long long)GB_TILE, G.V - v0);
+    for (int i = threadIdx.x; i < cnt * G.nb; i += blockDim.x) sW[i] = W[v0 * G.nb + i];
+    for (int i = threadIdx.x; i < cnt * 12; i += blockDim.x) sG[i] = GT[((long long)p * G.V + v0) * 12 + i];
+    __syncthreads();
+    for (int o = threadIdx.x; o < G.nb * 12; o += blockDim.x) {
+        const int b = o / 12, e = o - b * 12;
+        float acc = 0.0f;
+        for (int i = 0; i < cnt; ++i) acc = FS_FMA(sW[i * G.nb + b], sG[i * 12 + e], acc);
+        unsafeAtomicAdd(gB + ((long long)p * G.nb + b) * 12 + e, acc);
+    }
+}
+
+}  // namespace fs
