@@ -83,6 +83,12 @@ fs_status fs_destroy(fs_ctx *ctx);
  * init_mode and the correspondence-grid shape are fixed at creation). */
 fs_status fs_set_params(fs_ctx *ctx, const fs_params *params);
 
+/* Launch-shape knobs of the solve kernel; results never depend on them.  chunk = lanes a wave draws
+ * from the work cursor at a time (64..65536), refill_min = idle SIMD lanes that trigger a refill
+ * (1..64), blocks_per_cu = resident 256-thread blocks per compute unit (0 = what the occupancy query
+ * reports).  A value of 0 keeps the current setting. */
+fs_status fs_set_tuning(fs_ctx *ctx, int32_t chunk, int32_t refill_min, int32_t blocks_per_cu);
+
 /* Pre-compute linear blend skinning on the grid nodes, Eq. (13) / Sec. 3.1 "Pre-computing
  * LBS": T[p][v] = sum_b W[v][b] * B[p][b], bones accumulated in index order with fused
  * multiply-adds.  Also inverts every bone transform for Eq. (8) and, for FS_INIT_VOXEL,

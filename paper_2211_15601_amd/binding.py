@@ -20,7 +20,7 @@ STATUS_NAMES = ["FS_OK", "FS_E_ARG", "FS_E_SHAPE", "FS_E_STATE", "FS_E_ALLOC", "
 FS_INIT_BONE, FS_INIT_VOXEL = 0, 1
 FS_GRAD_BROYDEN_J, FS_GRAD_EXACT_J = 0, 1
 
-EXPORTS = ["fs_create", "fs_destroy", "fs_set_params", "fs_precompute", "fs_init", "fs_solve", "fs_grad",
+EXPORTS = ["fs_create", "fs_destroy", "fs_set_params", "fs_set_tuning", "fs_precompute", "fs_init", "fs_solve", "fs_grad",
            "fs_get_transforms", "fs_get_corr", "fs_last_error", "fs_version"]
 
 
@@ -69,7 +69,8 @@ def load():
     L.fs_last_error.restype = ctypes.c_char_p
     L.fs_version.argtypes = []
     L.fs_version.restype = ctypes.c_char_p
-    for name in EXPORTS[:9]:
+    L.fs_set_tuning.argtypes = [vp, i32, i32, i32]
+    for name in EXPORTS[:10]:
         getattr(L, name).restype = ctypes.c_int
     _lib = L
     return L
@@ -134,6 +135,9 @@ class Context:
         if max_iters is not None: p.max_iters = int(max_iters)
         if grad_mode is not None: p.grad_mode = int(grad_mode)
         return self._ret(self._L.fs_set_params(self._h, ctypes.byref(p)), check)
+
+    def set_tuning(self, chunk=0, refill_min=0, blocks_per_cu=0, check=True):
+        return self._ret(self._L.fs_set_tuning(self._h, int(chunk), int(refill_min), int(blocks_per_cu)), check)
 
     def precompute(self, W, B, check=True):
         return self._ret(self._L.fs_precompute(self._h, _ptr(W), _ptr(B)), check)

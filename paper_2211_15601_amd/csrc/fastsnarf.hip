@@ -4,6 +4,7 @@
 #include "fs_kernels.hpp"
 
 #include <hip/hip_runtime.h>
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -35,6 +36,13 @@ struct fs_ctx {
     int *fill;         // [P*ncell]
     int *order;        // [P][V]
     int32_t *cand;     // [P][ncell][ck]
+    unsigned *cursor;  // work cursor of the solve kernel
+    int *gcount;       // [P*ncells + 1] per-cell lane counts, then offsets (backward)
+    int *gpos;         // [K*N] position of a lane inside its cell's list (grows on demand)
+    float *grec;       // [K*N][6] cell-sorted {x*, lambda} records (grows on demand)
+    size_t gcap;       // lanes gpos / grec can hold
+    int solve_blocks;  // resident blocks of the solve kernel on this device
+    int n_cus, occ_blocks_per_cu, chunk, refill_min;
     char err[256];
 };
 
@@ -110,7 +118,7 @@ int grid1d(long long n, int block) { return (int)((n + block - 1) / block); }
 void free_all(fs_ctx *c)
 {
     void *ptrs[] = {c->T, c->Bdev, c->Binv, c->Bok, c->GT, c->Y, c->bb_ord, c->bbox,
-                    c->cell_of, c->count, c->fill, c->order, c->cand};
+                    c->cell_of, c->count, c->fill, c->order, c->cand, c->cursor, c->gcount, c->gpos, c->grec};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
 }
@@ -173,7 +181,18 @@ fs_status fs_create(const fs_grid_desc *desc, const fs_params *params, void *hip
     }
     const size_t P = desc->n_poses, nb = desc->n_bones;
     bool ok = dev_alloc(&c->T, P * V * 12) && dev_alloc(&c->Bdev, P * nb * 12) && dev_alloc(&c->Binv, P * nb * 12) &&
-              dev_alloc(&c->Bok, P * nb);
+              dev_alloc(&c->Bok, P * nb) && dev_alloc(&c->cursor, 4);
+    {
+        int per_cu = 0, cus = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_solve, 256, 0) != hipSuccess || per_cu < 1) per_cu = 4;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+        (void)hipGetLastError();
+        c->solve_blocks = per_cu * cus;
+        c->n_cus = cus;
+        c->occ_blocks_per_cu = per_cu;
+        c->chunk = 128;
+        c->refill_min = 32;
+    }
     if (ok && params->init_mode == FS_INIT_VOXEL) {
         CorrP &C = c->C;
         C.cx = params->corr_nx; C.cy = params->corr_ny; C.cz = params->corr_nz; C.ck = params->corr_k;
@@ -210,6 +229,18 @@ fs_status fs_set_params(fs_ctx *ctx, const fs_params *params)
     ctx->prm.div_thresh = params->div_thresh;
     ctx->prm.max_iters = params->max_iters;
     ctx->prm.grad_mode = params->grad_mode;
+    return FS_OK;
+}
+
+fs_status fs_set_tuning(fs_ctx *ctx, int32_t chunk, int32_t refill_min, int32_t blocks_per_cu)
+{
+    if (!ctx) return FS_E_ARG;
+    if ((chunk != 0 && (chunk < 64 || chunk > 65536)) || (refill_min != 0 && (refill_min < 1 || refill_min > 64)) ||
+        blocks_per_cu < 0 || blocks_per_cu > 32)
+        return fail(ctx, FS_E_ARG, "fs_set_tuning: value out of range");
+    if (chunk) ctx->chunk = chunk;
+    if (refill_min) ctx->refill_min = refill_min;
+    ctx->solve_blocks = (blocks_per_cu ? std::min(blocks_per_cu, ctx->occ_blocks_per_cu) : ctx->occ_blocks_per_cu) * ctx->n_cus;
     return FS_OK;
 }
 
@@ -291,12 +322,14 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     S.max_iters = ctx->prm.max_iters;
     S.tol2 = ctx->prm.tol * ctx->prm.tol;
     S.div2 = ctx->prm.div_thresh * ctx->prm.div_thresh;
-    S.chunk = 1024;
-    S.refill_min = 16;
-    const long long waves = (S.total + S.chunk - 1) / S.chunk;
+    S.chunk = ctx->chunk;
+    S.refill_min = ctx->refill_min;
+    const long long chunks = (S.total + S.chunk - 1) / S.chunk;
     const int wpb = 4;
-    k_solve<<<grid1d(waves, wpb), wpb * WAVE, 0, ctx->stream>>>(ctx->G, S, ctx->T, d_xq, d_pose, d_x0, d_Jinv0, d_valid0,
-                                                                d_xc, d_conv, d_Jinv, d_iters);
+    const int blocks = (int)std::min<long long>(grid1d(chunks, wpb), ctx->solve_blocks);
+    k_reset_cursor<<<1, 64, 0, ctx->stream>>>(ctx->cursor);
+    k_solve<<<blocks, wpb * WAVE, 0, ctx->stream>>>(ctx->G, S, ctx->T, d_xq, d_pose, d_x0, d_Jinv0, d_valid0, d_xc,
+                                                    d_conv, d_Jinv, d_iters, ctx->cursor);
     return launch_status(ctx, "fs_solve");
 }
 
@@ -322,15 +355,30 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
         FS_CHECK_PTR(ctx, d_pose, true);
     }
     const GridP &G = ctx->G;
+    const int ncell = (G.nx - 1) * (G.ny - 1) * (G.nz - 1);
+    const long long ncp = (long long)G.P * ncell;
+    if (ncp + 1 >= (1ll << 31)) return fail(ctx, FS_E_SHAPE, "fs_grad: too many grid cells");
     if (!ctx->GT && !dev_alloc(&ctx->GT, (size_t)G.P * G.V * 12)) return fail(ctx, FS_E_ALLOC, "fs_grad: out of device memory");
+    if (!ctx->gcount && !dev_alloc(&ctx->gcount, (size_t)ncp + 1)) return fail(ctx, FS_E_ALLOC, "fs_grad: out of device memory");
+    const size_t lanes = (size_t)N * K;
+    if (lanes > ctx->gcap) {
+        (void)hipStreamSynchronize(ctx->stream);
+        if (ctx->gpos) (void)hipFree(ctx->gpos);
+        if (ctx->grec) (void)hipFree(ctx->grec);
+        ctx->gpos = nullptr; ctx->grec = nullptr; ctx->gcap = 0;
+        if (!dev_alloc(&ctx->gpos, lanes) || !dev_alloc(&ctx->grec, lanes * 6))
+            return fail(ctx, FS_E_ALLOC, "fs_grad: out of device memory for %zu lanes", lanes);
+        ctx->gcap = lanes;
+    }
     hipStream_t st = ctx->stream;
-    const long long nGT = (long long)G.P * G.V * 12;
-    k_fill_zero<<<(int)std::min<long long>(grid1d(nGT, 256), 4096), 256, 0, st>>>(nGT, ctx->GT);
+    k_fill_zero_i32<<<(int)std::min<long long>(grid1d(ncp + 1, 256), 4096), 256, 0, st>>>(ncp + 1, ctx->gcount);
     k_fill_zero<<<grid1d(G.P * G.nb * 12, 256), 256, 0, st>>>((long long)G.P * G.nb * 12, d_gB);
-    if (d_gxq && N > 0) k_fill_zero<<<(int)std::min<long long>(grid1d(3 * N, 256), 4096), 256, 0, st>>>(3 * (long long)N, d_gxq);
+    if (N > 0) k_grad_count<<<grid1d((long long)N * K, 256), 256, 0, st>>>(G, d_xc, d_conv, d_pose, N, K, ncell, ctx->gcount, ctx->gpos);
+    k_scan_exclusive<<<1, 1024, 0, st>>>((int)ncp, ctx->gcount);
     if (N > 0)
-        k_grad_scatter<<<grid1d((long long)N * K, 256), 256, 0, st>>>(G, mode, ctx->T, d_xc, d_Jinv, d_conv, d_gxc, d_pose,
-                                                                      N, K, ctx->GT, d_gxq);
+        k_grad_records<<<grid1d(N, 256), 256, 0, st>>>(G, mode, ctx->T, d_xc, d_Jinv, d_conv, d_gxc, d_pose, N, K, ncell,
+                                                       ctx->gcount, ctx->gpos, ctx->grec, d_gxq);
+    k_grad_gather<<<grid1d((long long)G.P * G.V * WAVE, 256), 256, 0, st>>>(G, ncell, ctx->gcount, ctx->grec, ctx->GT);
     const size_t shB = sizeof(float) * G.P * G.nb * 12;
     k_grad_weights<<<grid1d(G.V * G.nb, 256), 256, shB, st>>>(G, ctx->GT, ctx->Bdev, d_gW);
     const dim3 gb(grid1d(G.V, GB_TILE), G.P);

@@ -314,31 +314,36 @@ __global__ __launch_bounds__(256) void k_corr_select(GridP G, CorrP C, const flo
 }
 
 // ------------------------------------------------------------------------------------------------
-// Broyden solve.  Lanes are persistent: every wave owns a contiguous chunk of lanes q = k*N + n
-// and hands a new one to each SIMD lane that has finished, so that a wave does not idle behind
-// its slowest trajectory.  Every loop iteration evaluates the field once per active lane: for a
-// freshly loaded lane at x0, otherwise at x + dx followed by the rank-one update of J~.
+// Broyden solve.  Lanes are persistent: a wave draws chunks of consecutive lanes q = k*N + n from a
+// global cursor and hands a new one to each SIMD lane that has finished, so that a wave does not
+// idle behind its slowest trajectory and the grid drains only once, at the very end.  Every loop
+// iteration evaluates the field once per active lane: for a freshly loaded lane at x0, otherwise
+// at x + dx followed by the rank-one update of J~.
 // ------------------------------------------------------------------------------------------------
 struct SolveP {
     long long N;
     long long total;     // K * N
-    int chunk;           // lanes per wave
+    int chunk;           // lanes drawn from the global cursor at a time
     int refill_min;      // refill when at least this many SIMD lanes are idle
     int max_iters;
     float tol2, div2;
 };
+
+__global__ void k_reset_cursor(unsigned *__restrict__ cursor)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) *cursor = 0u;
+}
 
 __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, const float *__restrict__ T,
                                                const float *__restrict__ xq, const int32_t *__restrict__ pose,
                                                const float *__restrict__ x0, const float *__restrict__ J0,
                                                const uint8_t *__restrict__ valid0, float *__restrict__ o_x,
                                                uint8_t *__restrict__ o_conv, float *__restrict__ o_J,
-                                               uint8_t *__restrict__ o_it)
+                                               uint8_t *__restrict__ o_it, unsigned *__restrict__ cursor)
 {
     const int lane = threadIdx.x & 63;
-    const long long wave = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    const long long c1 = min(S.total, (wave + 1) * (long long)S.chunk);
-    long long next = wave * (long long)S.chunk;      // wave-uniform cursor
+    long long next = 0, c1 = 0;      // wave-uniform: the wave's current chunk is [next, c1)
+    bool exhausted = false;          // wave-uniform: the global cursor has run past the end
     const long long N = S.N;
 
     bool active = false, fresh = false;
@@ -351,39 +356,52 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, const float *_
     while (true) {
         const unsigned long long idle = __ballot(!active);
         const int nidle = __popcll(idle);
-        if (next < c1 && nidle >= S.refill_min) {
-            const int rank = __popcll(idle & ((1ull << lane) - 1ull));
-            const long long q = next + rank;
-            if (!active && q < c1) {
-                k = (int)(q / N);
-                n = q - (long long)k * N;
-#pragma unroll
-                for (int r = 0; r < 3; ++r) {
-                    xp[r] = xq[r * N + n];
-                    xt[r] = x0[((long long)k * 3 + r) * N + n];
-                }
-#pragma unroll
-                for (int e = 0; e < 9; ++e) J[e] = J0[((long long)k * 9 + e) * N + n];
-                Tp = T + (long long)(pose ? pose[n] : 0) * G.V * 12;
-                it = 0;
-                if (valid0[q]) {
-                    active = true;
-                    fresh = true;
+        if (!exhausted && nidle >= S.refill_min) {
+            if (next >= c1) {
+                unsigned b = 0;
+                if (lane == 0) b = atomicAdd(cursor, (unsigned)S.chunk);
+                b = (unsigned)__shfl((int)b, 0);
+                if ((long long)b >= S.total) {
+                    exhausted = true;
                 } else {
-#pragma unroll
-                    for (int r = 0; r < 3; ++r) o_x[((long long)k * 3 + r) * N + n] = xt[r];
-                    o_conv[q] = 0;
-                    if (o_J) {
-#pragma unroll
-                        for (int e = 0; e < 9; ++e) o_J[((long long)k * 9 + e) * N + n] = J[e];
-                    }
-                    if (o_it) o_it[q] = 0;
+                    next = b;
+                    c1 = min(S.total, (long long)b + S.chunk);
                 }
             }
-            next += min((long long)nidle, c1 - next);
+            if (!exhausted) {
+                const int rank = __popcll(idle & ((1ull << lane) - 1ull));
+                const long long q = next + rank;
+                if (!active && q < c1) {
+                    k = (int)(q / N);
+                    n = q - (long long)k * N;
+#pragma unroll
+                    for (int r = 0; r < 3; ++r) {
+                        xp[r] = xq[r * N + n];
+                        xt[r] = x0[((long long)k * 3 + r) * N + n];
+                    }
+#pragma unroll
+                    for (int e = 0; e < 9; ++e) J[e] = J0[((long long)k * 9 + e) * N + n];
+                    Tp = T + (long long)(pose ? pose[n] : 0) * G.V * 12;
+                    it = 0;
+                    if (valid0[q]) {
+                        active = true;
+                        fresh = true;
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 3; ++r) o_x[((long long)k * 3 + r) * N + n] = xt[r];
+                        o_conv[q] = 0;
+                        if (o_J) {
+#pragma unroll
+                            for (int e = 0; e < 9; ++e) o_J[((long long)k * 9 + e) * N + n] = J[e];
+                        }
+                        if (o_it) o_it[q] = 0;
+                    }
+                }
+                next += min((long long)nidle, c1 - next);
+            }
         }
         if (!__any(active)) {
-            if (next >= c1) break;
+            if (exhausted) break;
             continue;
         }
         if (active) {
@@ -450,55 +468,146 @@ __global__ void k_fill_zero(long long n, float *__restrict__ a)
     for (; i < n; i += stride) a[i] = 0.0f;
 }
 
-// One thread per lane: lambda = -M^T g_x, then 8 corners x 12 atomic adds into G_T.
-__global__ __launch_bounds__(256) void k_grad_scatter(GridP G, int mode, const float *__restrict__ T,
-                                                      const float *__restrict__ xc, const float *__restrict__ Jinv,
-                                                      const uint8_t *__restrict__ conv, const float *__restrict__ gxc,
-                                                      const int32_t *__restrict__ pose, long long N, int K,
-                                                      float *__restrict__ GT, float *__restrict__ gxq)
+// The gradient w.r.t. the transform grid, G_T[p][v] = sum over converged lanes of
+// omega_corner * lambda (x) [x*; 1], is accumulated without floating-point atomics (device-scope
+// atomics leave the L2 on this chip and are slow): converged lanes are counting-sorted by the grid
+// cell of x*, then one wave per grid node sums the contributions of the lanes in its 8 adjacent cells.
+
+__global__ void k_fill_zero_i32(long long n, int *__restrict__ a)
+{
+    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long stride = (long long)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) a[i] = 0;
+}
+
+__device__ __forceinline__ int cell_linear(const GridP &G, const Cell &c)
+{
+    // c.base = ((ix*ny + iy)*nz + iz)*12 in node strides; recover the cell's own linear index
+    const int ix = c.base / G.sx, rem = c.base - ix * G.sx;
+    const int iy = rem / G.sy, iz = (rem - iy * G.sy) / 12;
+    return (ix * (G.ny - 1) + iy) * (G.nz - 1) + iz;
+}
+
+// pass 1: one thread per lane; position of the lane inside its cell's list (arrival order)
+__global__ __launch_bounds__(256) void k_grad_count(GridP G, const float *__restrict__ xc,
+                                                    const uint8_t *__restrict__ conv, const int32_t *__restrict__ pose,
+                                                    long long N, int K, int ncell, int *__restrict__ count,
+                                                    int *__restrict__ pos)
 {
     const long long q = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (q >= N * K) return;
     if (!conv[q]) return;
     const int k = (int)(q / N);
     const long long n = q - (long long)k * N;
-    const int p = pose ? pose[n] : 0;
-    float x[3], gx[3], M[9];
-#pragma unroll
-    for (int r = 0; r < 3; ++r) {
-        x[r] = xc[((long long)k * 3 + r) * N + n];
-        gx[r] = gxc[((long long)k * 3 + r) * N + n];
-    }
-    if (mode == 0) {
-#pragma unroll
-        for (int e = 0; e < 9; ++e) M[e] = Jinv[((long long)k * 9 + e) * N + n];
-    } else {
-        float d[3], J[9];
-        field_dJ(T + (long long)p * G.V * 12, G, x, d, J);
-        if (!inv3(J, M)) return;
-    }
-    float lam[3];
-#pragma unroll
-    for (int r = 0; r < 3; ++r) lam[r] = -FS_FMA(M[6 + r], gx[2], FS_FMA(M[3 + r], gx[1], M[r] * gx[0]));
-    if (gxq) {
-#pragma unroll
-        for (int r = 0; r < 3; ++r) unsafeAtomicAdd(gxq + r * N + n, -lam[r]);
-    }
+    const float x[3] = {xc[((long long)k * 3 + 0) * N + n], xc[((long long)k * 3 + 1) * N + n],
+                        xc[((long long)k * 3 + 2) * N + n]};
     const Cell c = locate(G, x);
-    float om[8];
-    corner_weights(c, om);
-    float *Gp = GT + (long long)p * G.V * 12 + c.base;
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-        float *o = Gp + corner_off(G, kk);
+    const int p = pose ? pose[n] : 0;
+    pos[q] = atomicAdd(count + p * ncell + cell_linear(G, c), 1);
+}
+
+// pass 2: one thread per point, all its lanes: lambda = -M^T g_x, record {x*, lambda} written to the
+// lane's slot of the cell-sorted list; dL/dx' = sum_k M^T g_x without atomics.
+__global__ __launch_bounds__(256) void k_grad_records(GridP G, int mode, const float *__restrict__ T,
+                                                      const float *__restrict__ xc, const float *__restrict__ Jinv,
+                                                      const uint8_t *__restrict__ conv, const float *__restrict__ gxc,
+                                                      const int32_t *__restrict__ pose, long long N, int K, int ncell,
+                                                      const int *__restrict__ offset, const int *__restrict__ pos,
+                                                      float *__restrict__ rec, float *__restrict__ gxq)
+{
+    const long long n = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= N) return;
+    const int p = pose ? pose[n] : 0;
+    float gq[3] = {0.0f, 0.0f, 0.0f};
+    for (int k = 0; k < K; ++k) {
+        const long long q = (long long)k * N + n;
+        if (!conv[q]) continue;
+        float x[3], gx[3], M[9];
 #pragma unroll
         for (int r = 0; r < 3; ++r) {
-            const float wl = om[kk] * lam[r];
-            unsafeAtomicAdd(o + r * 4 + 0, wl * x[0]);
-            unsafeAtomicAdd(o + r * 4 + 1, wl * x[1]);
-            unsafeAtomicAdd(o + r * 4 + 2, wl * x[2]);
-            unsafeAtomicAdd(o + r * 4 + 3, wl);
+            x[r] = xc[((long long)k * 3 + r) * N + n];
+            gx[r] = gxc[((long long)k * 3 + r) * N + n];
         }
+        bool ok = true;
+        if (mode == 0) {
+#pragma unroll
+            for (int e = 0; e < 9; ++e) M[e] = Jinv[((long long)k * 9 + e) * N + n];
+        } else {
+            float d[3], J[9];
+            field_dJ(T + (long long)p * G.V * 12, G, x, d, J);
+            ok = inv3(J, M);
+        }
+        float lam[3] = {0.0f, 0.0f, 0.0f};
+        if (ok) {
+#pragma unroll
+            for (int r = 0; r < 3; ++r) {
+                lam[r] = -FS_FMA(M[6 + r], gx[2], FS_FMA(M[3 + r], gx[1], M[r] * gx[0]));
+                gq[r] -= lam[r];
+            }
+        }
+        const Cell c = locate(G, x);
+        const long long slot = (long long)offset[p * ncell + cell_linear(G, c)] + pos[q];
+        float2 *o = reinterpret_cast<float2 *>(rec + slot * 6);
+        o[0] = make_float2(x[0], x[1]);
+        o[1] = make_float2(x[2], lam[0]);
+        o[2] = make_float2(lam[1], lam[2]);
+    }
+    if (gxq) {
+#pragma unroll
+        for (int r = 0; r < 3; ++r) gxq[r * N + n] = gq[r];
+    }
+}
+
+// pass 3: one wave per (pose, node): sum over the lanes of the (up to) 8 cells that have the node as
+// a corner; lanes of the wave stride over a cell's records, then a butterfly reduction.
+__global__ __launch_bounds__(256) void k_grad_gather(GridP G, int ncell, const int *__restrict__ offset,
+                                                     const float *__restrict__ rec, float *__restrict__ GT)
+{
+    const long long wv = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int lane = threadIdx.x & 63;
+    if (wv >= (long long)G.P * G.V) return;
+    const int p = (int)(wv / G.V);
+    const long long v = wv - (long long)p * G.V;
+    const int iz = (int)(v % G.nz), iy = (int)((v / G.nz) % G.ny), ix = (int)(v / ((long long)G.nz * G.ny));
+    float acc[12];
+#pragma unroll
+    for (int e = 0; e < 12; ++e) acc[e] = 0.0f;
+    for (int cn = 0; cn < 8; ++cn) {
+        const int da = cn & 1, db = (cn >> 1) & 1, dc = (cn >> 2) & 1;
+        const int cx = ix - da, cy = iy - db, cz = iz - dc;
+        if (cx < 0 || cy < 0 || cz < 0 || cx > G.nx - 2 || cy > G.ny - 2 || cz > G.nz - 2) continue;
+        const int cell = p * ncell + (cx * (G.ny - 1) + cy) * (G.nz - 1) + cz;
+        const int beg = offset[cell], end = offset[cell + 1];
+        for (int s = beg + lane; s < end; s += WAVE) {
+            const float2 *r = reinterpret_cast<const float2 *>(rec + (long long)s * 6);
+            const float2 r0 = r[0], r1 = r[1], r2 = r[2];
+            const float x[3] = {r0.x, r0.y, r1.x};
+            const float lam[3] = {r1.y, r2.x, r2.y};
+            const Cell c = locate(G, x);
+            const float wx = da ? c.f[0] : 1.0f - c.f[0];
+            const float wy = db ? c.f[1] : 1.0f - c.f[1];
+            const float wz = dc ? c.f[2] : 1.0f - c.f[2];
+            const float om = (wx * wy) * wz;
+#pragma unroll
+            for (int rr = 0; rr < 3; ++rr) {
+                const float wl = om * lam[rr];
+                acc[rr * 4 + 0] = FS_FMA(wl, x[0], acc[rr * 4 + 0]);
+                acc[rr * 4 + 1] = FS_FMA(wl, x[1], acc[rr * 4 + 1]);
+                acc[rr * 4 + 2] = FS_FMA(wl, x[2], acc[rr * 4 + 2]);
+                acc[rr * 4 + 3] += wl;
+            }
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 12; ++e) {
+#pragma unroll
+        for (int s = 32; s >= 1; s >>= 1) acc[e] += __shfl_xor(acc[e], s);
+    }
+    if (lane == 0) {
+        float4 *o = reinterpret_cast<float4 *>(GT + ((long long)p * G.V + v) * 12);
+        o[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        o[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+        o[2] = make_float4(acc[8], acc[9], acc[10], acc[11]);
     }
 }
 
