@@ -38,6 +38,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload configuration 1..5 (default 2: SMPL-scale)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-grad", action="store_true", help="leave fs_grad out of the step")
+    ap.add_argument("--unfused", action="store_true",
+                    help="materialise the initial states with fs_init instead of computing them inside fs_solve")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (lanes are independent; see DESIGN.md for how the "
@@ -83,9 +85,13 @@ def main():
         if record: e[0].record()
         ctx.precompute(W, B)
         if record: e[1].record()
-        ctx.init(xq, pose, N, x0, J0, v0)
+        if args.unfused:
+            ctx.init(xq, pose, N, x0, J0, v0)
         if record: e[2].record()
-        ctx.solve(xq, pose, N, K, x0, J0, v0, xc, cv, Jo, it)
+        if args.unfused:
+            ctx.solve(xq, pose, N, K, x0, J0, v0, xc, cv, Jo, it)
+        else:
+            ctx.solve(xq, pose, N, K, None, None, None, xc, cv, Jo, it)
         if record: e[3].record()
         if not args.no_grad:
             ctx.grad(W, xc, Jo, cv, gxc, pose, N, K, gW, gB, gxq)
@@ -105,6 +111,8 @@ def main():
     phases = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(4)] for e in marks])   # ms
     pre_ms, init_ms, solve_ms, grad_ms = phases.mean(0)
 
+    ctx.init(xq, pose, N, x0, J0, v0)                 # (untimed) validity flags for the lane-iteration count
+    torch.cuda.synchronize()
     conv = int(cv.sum().item())
     valid = int(v0.sum().item())
     steps_total = int(it.to(torch.int64)[v0 == 1].sum().item())
@@ -122,7 +130,8 @@ def main():
         "config": {"workload": f"config {args.config} ({w.name}): grid {w.dims[0]}x{w.dims[1]}x{w.dims[2]}, "
                                f"{w.n_bones} bones, {w.n_poses} pose(s), {N} points x {K} inits, "
                                f"max_iters {w.max_iters}, tol {w.tol}",
-                   "step": "fs_precompute + fs_init + fs_solve" + ("" if args.no_grad else " + fs_grad"),
+                   "step": "fs_precompute + " + ("fs_init + fs_solve" if args.unfused else "fs_solve (initial states fused)")
+                           + ("" if args.no_grad else " + fs_grad"),
                    "pairs": N * K, "valid_pairs": valid, "converged_pairs": conv,
                    "lane_iterations": evals},
         "breakdown_ms": {"fs_precompute": float(pre_ms), "fs_init": float(init_ms), "fs_solve": float(solve_ms),

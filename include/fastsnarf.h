@@ -85,8 +85,8 @@ fs_status fs_set_params(fs_ctx *ctx, const fs_params *params);
 
 /* Launch-shape knobs of the solve kernel; results never depend on them.  chunk = lanes a wave draws
  * from the work cursor at a time (64..65536), refill_min = idle SIMD lanes that trigger a refill
- * (1..64), blocks_per_cu = resident 256-thread blocks per compute unit (0 = what the occupancy query
- * reports).  A value of 0 keeps the current setting. */
+ * (1..64), blocks_per_cu = resident 256-thread blocks per compute unit (capped by what the occupancy
+ * query reports).  A value of 0 keeps the current setting. */
 fs_status fs_set_tuning(fs_ctx *ctx, int32_t chunk, int32_t refill_min, int32_t blocks_per_cu);
 
 /* Pre-compute linear blend skinning on the grid nodes, Eq. (13) / Sec. 3.1 "Pre-computing
@@ -114,6 +114,8 @@ fs_status fs_init(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_t
  * (converged, Eq. (9)), when !(|d(x)-x'|^2 < div_thresh^2) (diverged or NaN), or after max_iters
  * steps (Sec. 3.1 "Custom CUDA Kernel": per-iteration filtering).
  *   K must equal n_bones (FS_INIT_BONE) or corr_k (FS_INIT_VOXEL); K*N < 2^31.
+ *   d_x0, d_Jinv0, d_valid0 all NULL: the kernel computes the initial states of the context's
+ *   init_mode itself (same arithmetic as fs_init, bit-identical results) and fs_init is not needed.
  *   out: d_xc [K][3][N] last iterate; d_conv [K][N] 1 = converged; d_Jinv [K][9][N] last J~ (may be
  *   NULL); d_iters [K][N] steps taken (may be NULL).  Lanes with valid0 == 0 return x0, conv 0. */
 fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_t N, int32_t K,

@@ -41,8 +41,9 @@ struct fs_ctx {
     int *gpos;         // [K*N] position of a lane inside its cell's list (grows on demand)
     float *grec;       // [K*N][6] cell-sorted {x*, lambda} records (grows on demand)
     size_t gcap;       // lanes gpos / grec can hold
-    int solve_blocks;  // resident blocks of the solve kernel on this device
-    int n_cus, occ_blocks_per_cu, chunk, refill_min;
+    int *scan_sums;    // tile sums of the prefix scans
+    int scan_cap;      // tiles scan_sums can hold
+    int n_cus, occ_blocks_per_cu, chunk, refill_min, blocks_per_cu;
     char err[256];
 };
 
@@ -118,9 +119,26 @@ int grid1d(long long n, int block) { return (int)((n + block - 1) / block); }
 void free_all(fs_ctx *c)
 {
     void *ptrs[] = {c->T, c->Bdev, c->Binv, c->Bok, c->GT, c->Y, c->bb_ord, c->bbox,
-                    c->cell_of, c->count, c->fill, c->order, c->cand, c->cursor, c->gcount, c->gpos, c->grec};
+                    c->cell_of, c->count, c->fill, c->order, c->cand, c->cursor, c->gcount, c->gpos, c->grec, c->scan_sums};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
+}
+
+// exclusive scan of a[0..n) in place on the context's stream, a[n] = total
+fs_status scan_exclusive(fs_ctx *c, int n, int *a)
+{
+    const int m = (n + SCAN_TILE - 1) / SCAN_TILE;
+    if (m + 1 > c->scan_cap) {
+        (void)hipStreamSynchronize(c->stream);
+        if (c->scan_sums) (void)hipFree(c->scan_sums);
+        c->scan_cap = 0;
+        if (!dev_alloc(&c->scan_sums, (size_t)m + 1)) return fail(c, FS_E_ALLOC, "out of device memory (scan)");
+        c->scan_cap = m + 1;
+    }
+    k_scan_tile_sums<<<m, 1024, 0, c->stream>>>(n, a, c->scan_sums);
+    k_scan_sums<<<1, 1024, 0, c->stream>>>(m, c->scan_sums);
+    k_scan_tiles<<<m, 1024, 0, c->stream>>>(n, a, c->scan_sums, m);
+    return FS_OK;
 }
 
 int lanes_K(const fs_ctx *c) { return c->prm.init_mode == FS_INIT_BONE ? c->desc.n_bones : c->prm.corr_k; }
@@ -141,7 +159,7 @@ fs_status fs_create(const fs_grid_desc *desc, const fs_params *params, void *hip
         desc->n_poses < 1 || desc->n_poses > FS_MAX_POSES)
         return FS_E_SHAPE;
     const long long V = (long long)desc->nx * desc->ny * desc->nz;
-    if (V * 12 >= (1ll << 31)) return FS_E_SHAPE;
+    if ((long long)desc->n_poses * V * 12 >= (1ll << 31)) return FS_E_SHAPE;   /* grid offsets are 32-bit */
     if (desc->n_poses * desc->n_bones > 1024) return FS_E_UNSUPPORTED;   /* bone tables are staged in 48 KiB of LDS */
     for (int a = 0; a < 3; ++a)
         if (!(desc->hi[a] > desc->lo[a]) || !std::isfinite(desc->hi[a]) || !std::isfinite(desc->lo[a])) return FS_E_ARG;
@@ -184,10 +202,10 @@ fs_status fs_create(const fs_grid_desc *desc, const fs_params *params, void *hip
               dev_alloc(&c->Bok, P * nb) && dev_alloc(&c->cursor, 4);
     {
         int per_cu = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_solve, 256, 0) != hipSuccess || per_cu < 1) per_cu = 4;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_solve<true>, 256, 0) != hipSuccess || per_cu < 1) per_cu = 2;
+        c->blocks_per_cu = 2;   /* the kernel is bound by the vector-memory path: more waves only thrash the L1 */
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
         (void)hipGetLastError();
-        c->solve_blocks = per_cu * cus;
         c->n_cus = cus;
         c->occ_blocks_per_cu = per_cu;
         c->chunk = 128;
@@ -240,7 +258,7 @@ fs_status fs_set_tuning(fs_ctx *ctx, int32_t chunk, int32_t refill_min, int32_t 
         return fail(ctx, FS_E_ARG, "fs_set_tuning: value out of range");
     if (chunk) ctx->chunk = chunk;
     if (refill_min) ctx->refill_min = refill_min;
-    ctx->solve_blocks = (blocks_per_cu ? std::min(blocks_per_cu, ctx->occ_blocks_per_cu) : ctx->occ_blocks_per_cu) * ctx->n_cus;
+    if (blocks_per_cu) ctx->blocks_per_cu = blocks_per_cu;
     return FS_OK;
 }
 
@@ -264,7 +282,7 @@ fs_status fs_precompute(fs_ctx *ctx, const float *d_W, const float *d_B)
         k_corr_warp<<<gv, 256, 0, st>>>(G, ctx->T, ctx->Y, ctx->bb_ord);
         k_corr_bbox<<<1, 64 * ((G.P * 6 + 63) / 64), 0, st>>>(G.P, ctx->bb_ord, ctx->bbox);
         k_corr_count<<<gv, 256, 0, st>>>(G, C, ctx->Y, ctx->bbox, ctx->cell_of, ctx->count);
-        k_scan_exclusive<<<1, 1024, 0, st>>>(ncp, ctx->count);
+        { fs_status ss = scan_exclusive(ctx, ncp, ctx->count); if (ss != FS_OK) return ss; }
         k_corr_scatter<<<gv, 256, 0, st>>>(G, C, ctx->cell_of, ctx->count, ctx->fill, ctx->order);
         k_corr_select<<<grid1d((long long)ncp * WAVE, 256), 256, 0, st>>>(G, C, ctx->Y, ctx->bbox, ctx->count, ctx->order, ctx->cand);
     }
@@ -309,9 +327,14 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     if (ctx->desc.n_poses > 1 && !d_pose) return fail(ctx, FS_E_ARG, "fs_solve: d_pose is required when n_poses > 1");
     FS_CHECK_PTR(ctx, d_xq, false);
     FS_CHECK_PTR(ctx, d_pose, true);
-    FS_CHECK_PTR(ctx, d_x0, false);
-    FS_CHECK_PTR(ctx, d_Jinv0, false);
-    FS_CHECK_PTR(ctx, d_valid0, false);
+    const bool fused = d_x0 == nullptr;
+    if (fused && (d_Jinv0 || d_valid0))
+        return fail(ctx, FS_E_ARG, "fs_solve: d_x0, d_Jinv0 and d_valid0 must be all NULL (fused initial states) or all set");
+    if (!fused) {
+        FS_CHECK_PTR(ctx, d_x0, false);
+        FS_CHECK_PTR(ctx, d_Jinv0, false);
+        FS_CHECK_PTR(ctx, d_valid0, false);
+    }
     FS_CHECK_PTR(ctx, d_xc, false);
     FS_CHECK_PTR(ctx, d_conv, false);
     FS_CHECK_PTR(ctx, d_Jinv, true);
@@ -326,10 +349,22 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     S.refill_min = ctx->refill_min;
     const long long chunks = (S.total + S.chunk - 1) / S.chunk;
     const int wpb = 4;
-    const int blocks = (int)std::min<long long>(grid1d(chunks, wpb), ctx->solve_blocks);
+    const int per_cu = std::max(1, std::min(ctx->blocks_per_cu, ctx->occ_blocks_per_cu));
+    const int blocks = (int)std::min<long long>(grid1d(chunks, wpb), (long long)per_cu * ctx->n_cus);
     k_reset_cursor<<<1, 64, 0, ctx->stream>>>(ctx->cursor);
-    k_solve<<<blocks, wpb * WAVE, 0, ctx->stream>>>(ctx->G, S, ctx->T, d_xq, d_pose, d_x0, d_Jinv0, d_valid0, d_xc,
-                                                    d_conv, d_Jinv, d_iters, ctx->cursor);
+    InitP I;
+    I.mode = ctx->prm.init_mode;
+    I.Binv = ctx->Binv;
+    I.Bok = ctx->Bok;
+    I.C = ctx->C;
+    I.bbox = ctx->bbox;
+    I.cand = ctx->cand;
+    if (fused)
+        k_solve<true><<<blocks, wpb * WAVE, 0, ctx->stream>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, nullptr, nullptr, nullptr,
+                                                              d_xc, d_conv, d_Jinv, d_iters, ctx->cursor);
+    else
+        k_solve<false><<<blocks, wpb * WAVE, 0, ctx->stream>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, d_x0, d_Jinv0, d_valid0,
+                                                               d_xc, d_conv, d_Jinv, d_iters, ctx->cursor);
     return launch_status(ctx, "fs_solve");
 }
 
@@ -374,7 +409,7 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
     k_fill_zero_i32<<<(int)std::min<long long>(grid1d(ncp + 1, 256), 4096), 256, 0, st>>>(ncp + 1, ctx->gcount);
     k_fill_zero<<<grid1d(G.P * G.nb * 12, 256), 256, 0, st>>>((long long)G.P * G.nb * 12, d_gB);
     if (N > 0) k_grad_count<<<grid1d((long long)N * K, 256), 256, 0, st>>>(G, d_xc, d_conv, d_pose, N, K, ncell, ctx->gcount, ctx->gpos);
-    k_scan_exclusive<<<1, 1024, 0, st>>>((int)ncp, ctx->gcount);
+    { fs_status ss = scan_exclusive(ctx, (int)ncp, ctx->gcount); if (ss != FS_OK) return ss; }
     if (N > 0)
         k_grad_records<<<grid1d(N, 256), 256, 0, st>>>(G, mode, ctx->T, d_xc, d_Jinv, d_conv, d_gxc, d_pose, N, K, ncell,
                                                        ctx->gcount, ctx->gpos, ctx->grec, d_gxq);

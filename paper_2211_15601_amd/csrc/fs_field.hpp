@@ -80,13 +80,10 @@ __device__ __forceinline__ void apply12(const float (&T)[12], const float x[3], 
         d[r] = FS_FMA(T[r * 4 + 0], x[0], FS_FMA(T[r * 4 + 1], x[1], FS_FMA(T[r * 4 + 2], x[2], T[r * 4 + 3])));
 }
 
-// Forward map of Eq. (5) with T(x) interpolated from the grid of one pose (Tp).
-__device__ __forceinline__ void field_d(const float *__restrict__ Tp, const GridP &G, const float x[3], float d[3])
+// Blend the 8 corner transforms q[c] (c = a + 2b + 4cz) with the tri-linear weights of `c` in corner
+// order (first term a product, the rest fused multiply-adds) and apply the result to x: Eq. (4)/(5).
+__device__ __forceinline__ void blend_apply(const Cell &c, const float (&q)[8][12], const float x[3], float d[3])
 {
-    const Cell c = locate(G, x);
-    float q[8][12];
-#pragma unroll
-    for (int k = 0; k < 8; ++k) load12(Tp + c.base + corner_off(G, k), q[k]);
     float om[8];
     corner_weights(c, om);
     float T[12];
@@ -99,16 +96,22 @@ __device__ __forceinline__ void field_d(const float *__restrict__ Tp, const Grid
     apply12(T, x, d);
 }
 
-// Forward map plus spatial Jacobian dd/dx (row-major 3x3): interpolated rotation part plus the
-// derivative of the interpolation weights applied to every corner's image of x; no weight
-// derivative along an axis on which the lookup was clamped.
-__device__ __forceinline__ void field_dJ(const float *__restrict__ Tp, const GridP &G, const float x[3],
-                                         float d[3], float J[9])
+// Forward map of Eq. (5) with T(x) interpolated from the grid of one pose (Tp).
+__device__ __forceinline__ void field_d(const float *__restrict__ Tp, const GridP &G, const float x[3], float d[3])
 {
     const Cell c = locate(G, x);
     float q[8][12];
 #pragma unroll
     for (int k = 0; k < 8; ++k) load12(Tp + c.base + corner_off(G, k), q[k]);
+    blend_apply(c, q, x, d);
+}
+
+// Forward map plus spatial Jacobian dd/dx (row-major 3x3) from the 8 corner records q of cell c:
+// interpolated rotation part plus the derivative of the interpolation weights applied to every
+// corner's image of x; no weight derivative along an axis on which the lookup was clamped.
+__device__ __forceinline__ void jacobian_from_corners(const GridP &G, const Cell &c, const float (&q)[8][12],
+                                                      const float x[3], float d[3], float J[9])
+{
     float om[8];
     corner_weights(c, om);
     float T[12];
@@ -140,6 +143,16 @@ __device__ __forceinline__ void field_dJ(const float *__restrict__ Tp, const Gri
 #pragma unroll
             for (int j = 0; j < 3; ++j) J[r * 3 + j] = FS_FMA(dw[j], dc[r], J[r * 3 + j]);
     }
+}
+
+__device__ __forceinline__ void field_dJ(const float *__restrict__ Tp, const GridP &G, const float x[3],
+                                         float d[3], float J[9])
+{
+    const Cell c = locate(G, x);
+    float q[8][12];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) load12(Tp + c.base + corner_off(G, k), q[k]);
+    jacobian_from_corners(G, c, q, x, d, J);
 }
 
 // Adjugate / determinant inverse of a row-major 3x3; false if |det| < 1e-12 or NaN.

@@ -221,26 +221,78 @@ __global__ __launch_bounds__(256) void k_corr_count(GridP G, CorrP C, const floa
     atomicAdd(count + p * C.ncell + c, 1);
 }
 
-// exclusive scan of count[0..n] in place (single block; n <= a few 100k)
-__global__ __launch_bounds__(1024) void k_scan_exclusive(int n, int *__restrict__ a)
+// Exclusive prefix sum of a[0..n) in place, a[n] = total.  Three launches: per-tile sums (tile = 4096
+// entries), a single-block scan of the tile sums, then every tile scans itself from its carry-in.
+constexpr int SCAN_TILE = 4096;   // 1024 threads x 4 entries
+
+__device__ __forceinline__ int block_exclusive_scan_1024(int v, int *total)
 {
-    __shared__ int part[1024];
-    const int t = threadIdx.x;
-    const int per = (n + 1023) / 1024;
-    const int s = t * per, e = min(n, s + per);
-    int sum = 0;
-    for (int i = s; i < e; ++i) sum += a[i];
-    part[t] = sum;
-    __syncthreads();
-    for (int d = 1; d < 1024; d <<= 1) {
-        const int add = t >= d ? part[t - d] : 0;
-        __syncthreads();
-        part[t] += add;
-        __syncthreads();
+    __shared__ int wsum[16];
+    const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int o = __shfl_up(inc, d);
+        if (lane >= d) inc += o;
     }
-    int run = part[t] - sum;
-    for (int i = s; i < e; ++i) { const int c = a[i]; a[i] = run; run += c; }
-    if (t == 1023) a[n] = part[1023];
+    __syncthreads();                       // wsum may still be read by a previous call
+    if (lane == 63) wsum[wid] = inc;
+    __syncthreads();
+    int carry = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+        const int x = wsum[w];
+        if (w < wid) carry += x;
+        tot += x;
+    }
+    *total = tot;
+    return carry + inc - v;
+}
+
+__global__ __launch_bounds__(1024) void k_scan_tile_sums(int n, const int *__restrict__ a, int *__restrict__ sums)
+{
+    const long long base = (long long)blockIdx.x * SCAN_TILE + threadIdx.x * 4;
+    int v = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        if (base + e < n) v += a[base + e];
+    int tot;
+    block_exclusive_scan_1024(v, &tot);
+    if (threadIdx.x == 0) sums[blockIdx.x] = tot;
+}
+
+// sums[0..m) -> exclusive scan in place, sums[m] = total (one block, loops over m in steps of 1024)
+__global__ __launch_bounds__(1024) void k_scan_sums(int m, int *__restrict__ sums)
+{
+    int run = 0;
+    for (int s0 = 0; s0 < m; s0 += 1024) {
+        const int i = s0 + threadIdx.x;
+        const int v = i < m ? sums[i] : 0;
+        int tot;
+        const int ex = block_exclusive_scan_1024(v, &tot);
+        if (i < m) sums[i] = run + ex;
+        run += tot;
+    }
+    if (threadIdx.x == 0) sums[m] = run;
+}
+
+__global__ __launch_bounds__(1024) void k_scan_tiles(int n, int *__restrict__ a, const int *__restrict__ sums, int m)
+{
+    const long long base = (long long)blockIdx.x * SCAN_TILE + threadIdx.x * 4;
+    int e4[4], v = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        e4[e] = base + e < n ? a[base + e] : 0;
+        v += e4[e];
+    }
+    int tot;
+    int run = sums[blockIdx.x] + block_exclusive_scan_1024(v, &tot);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        if (base + e < n) a[base + e] = run;
+        run += e4[e];
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) a[n] = sums[m];
 }
 
 __global__ __launch_bounds__(256) void k_corr_scatter(GridP G, CorrP C, const int *__restrict__ cell_of,
@@ -329,12 +381,27 @@ struct SolveP {
     float tol2, div2;
 };
 
+// What the fused variant needs to compute initial states itself (same arithmetic as k_init_*).
+struct InitP {
+    int mode;                 // 0: one state per bone (Eq. (8)); 1: candidates of the correspondence grid
+    const float *Binv;        // [P][nb][12]
+    const uint8_t *Bok;       // [P][nb]
+    CorrP C;
+    const float *bbox;        // [P][6]
+    const int32_t *cand;      // [P][ncell][ck]
+};
+
 __global__ void k_reset_cursor(unsigned *__restrict__ cursor)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) *cursor = 0u;
 }
 
-__global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, const float *__restrict__ T,
+// FUSED = false: initial states are read from x0 / J0 / valid0.  FUSED = true: a lane computes its
+// initial state when it picks up a pair (Sec. 3.1 "Custom CUDA Kernel": the kernel first computes the
+// initialisation states); the corner records fetched for the Jacobian then also serve the first
+// evaluation of the field, and the 53 bytes per pair of initial state never touch memory.
+template <bool FUSED>
+__global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const float *__restrict__ T,
                                                const float *__restrict__ xq, const int32_t *__restrict__ pose,
                                                const float *__restrict__ x0, const float *__restrict__ J0,
                                                const uint8_t *__restrict__ valid0, float *__restrict__ o_x,
@@ -352,6 +419,8 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, const float *_
     const float *Tp = T;
     float xp[3] = {0, 0, 0}, x[3] = {0, 0, 0}, xt[3] = {0, 0, 0}, g[3] = {0, 0, 0}, dx[3] = {0, 0, 0};
     float J[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+    float q[8][12];                  // corner records of the lane's current cell, kept across iterations
+    long long held = -1;             // grid offset of the cell whose corners q holds (-1: none)
 
     while (true) {
         const unsigned long long idle = __ballot(!active);
@@ -370,31 +439,69 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, const float *_
             }
             if (!exhausted) {
                 const int rank = __popcll(idle & ((1ull << lane) - 1ull));
-                const long long q = next + rank;
-                if (!active && q < c1) {
-                    k = (int)(q / N);
-                    n = q - (long long)k * N;
-#pragma unroll
-                    for (int r = 0; r < 3; ++r) {
-                        xp[r] = xq[r * N + n];
-                        xt[r] = x0[((long long)k * 3 + r) * N + n];
-                    }
-#pragma unroll
-                    for (int e = 0; e < 9; ++e) J[e] = J0[((long long)k * 9 + e) * N + n];
-                    Tp = T + (long long)(pose ? pose[n] : 0) * G.V * 12;
+                const long long pq = next + rank;
+                if (!active && pq < c1) {
+                    k = (int)(pq / N);
+                    n = pq - (long long)k * N;
+                    const int p = pose ? pose[n] : 0;
+                    Tp = T + (long long)p * G.V * 12;
                     it = 0;
-                    if (valid0[q]) {
+                    held = -1;
+                    bool ok;
+#pragma unroll
+                    for (int r = 0; r < 3; ++r) xp[r] = xq[r * N + n];
+                    if (FUSED) {
+#pragma unroll
+                        for (int r = 0; r < 3; ++r) xt[r] = 0.0f;
+#pragma unroll
+                        for (int e = 0; e < 9; ++e) J[e] = 0.0f;
+                        if (I.mode == 0) {
+                            const float *bi = I.Binv + ((long long)p * G.nb + k) * 12;
+                            ok = I.Bok[p * G.nb + k] != 0;
+                            if (ok) {
+                                const float y[3] = {xp[0] - bi[9], xp[1] - bi[10], xp[2] - bi[11]};
+#pragma unroll
+                                for (int r = 0; r < 3; ++r)
+                                    xt[r] = FS_FMA(bi[r * 3 + 0], y[0], FS_FMA(bi[r * 3 + 1], y[1], bi[r * 3 + 2] * y[2]));
+                            }
+                        } else {
+                            const int cidx = cell_index(I.C, I.bbox + p * 6, xp);
+                            const int v = I.cand[((long long)p * I.C.ncell + cidx) * I.C.ck + k];
+                            ok = v >= 0;
+                            if (ok) node_pos(G, v, xt);
+                        }
+                        if (ok) {
+                            const Cell c0 = locate(G, xt);
+#pragma unroll
+                            for (int c = 0; c < 8; ++c) load12(Tp + c0.base + corner_off(G, c), q[c]);
+                            held = (long long)(Tp - T) + c0.base;
+                            float d0[3], Jac[9];
+                            jacobian_from_corners(G, c0, q, xt, d0, Jac);
+                            ok = inv3(Jac, J);
+                            if (!ok) {
+#pragma unroll
+                                for (int e = 0; e < 9; ++e) J[e] = 0.0f;
+                            }
+                        }
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 3; ++r) xt[r] = x0[((long long)k * 3 + r) * N + n];
+#pragma unroll
+                        for (int e = 0; e < 9; ++e) J[e] = J0[((long long)k * 9 + e) * N + n];
+                        ok = valid0[pq] != 0;
+                    }
+                    if (ok) {
                         active = true;
                         fresh = true;
                     } else {
 #pragma unroll
                         for (int r = 0; r < 3; ++r) o_x[((long long)k * 3 + r) * N + n] = xt[r];
-                        o_conv[q] = 0;
+                        o_conv[pq] = 0;
                         if (o_J) {
 #pragma unroll
                             for (int e = 0; e < 9; ++e) o_J[((long long)k * 9 + e) * N + n] = J[e];
                         }
-                        if (o_it) o_it[q] = 0;
+                        if (o_it) o_it[pq] = 0;
                     }
                 }
                 next += min((long long)nidle, c1 - next);
@@ -406,7 +513,16 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, const float *_
         }
         if (active) {
             float d[3], gn[3];
-            field_d(Tp, G, xt, d);
+            // steps shrink as a lane converges, so it often stays in the cell it was in: reload the
+            // 8 corner records only when the cell changed
+            const Cell cell = locate(G, xt);
+            const long long want = (long long)(Tp - T) + cell.base;
+            if (want != held) {
+#pragma unroll
+                for (int c = 0; c < 8; ++c) load12(Tp + cell.base + corner_off(G, c), q[c]);
+                held = want;
+            }
+            blend_apply(cell, q, xt, d);
 #pragma unroll
             for (int r = 0; r < 3; ++r) gn[r] = d[r] - xp[r];
             if (!fresh) {
@@ -437,15 +553,15 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, const float *_
             const bool conv = r2 < S.tol2;
             const bool done = conv || !(r2 < S.div2) || it >= S.max_iters;
             if (done) {
-                const long long q = (long long)k * N + n;
+                const long long pq = (long long)k * N + n;
 #pragma unroll
                 for (int r = 0; r < 3; ++r) o_x[((long long)k * 3 + r) * N + n] = x[r];
-                o_conv[q] = conv ? 1 : 0;
+                o_conv[pq] = conv ? 1 : 0;
                 if (o_J) {
 #pragma unroll
                     for (int e = 0; e < 9; ++e) o_J[((long long)k * 9 + e) * N + n] = J[e];
                 }
-                if (o_it) o_it[q] = (uint8_t)it;
+                if (o_it) o_it[pq] = (uint8_t)it;
                 active = false;
             } else {
 #pragma unroll

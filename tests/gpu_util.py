@@ -57,11 +57,15 @@ class GpuRun:
         torch.cuda.synchronize()
         return self.x0.cpu().numpy(), self.J0.cpu().numpy(), self.v0.cpu().numpy()
 
-    def solve(self, x0=None, J0=None, v0=None, want_J=True):
+    def solve(self, x0=None, J0=None, v0=None, want_J=True, fused=False):
+        """fused=True passes NULL initial states: the solve kernel computes them itself."""
         N, K = self.N, self.K
-        x0 = self.x0 if x0 is None else dev(x0)
-        J0 = self.J0 if J0 is None else dev(J0)
-        v0 = self.v0 if v0 is None else dev(v0)
+        if fused:
+            x0 = J0 = v0 = None
+        else:
+            x0 = self.x0 if x0 is None else dev(x0)
+            J0 = self.J0 if J0 is None else dev(J0)
+            v0 = self.v0 if v0 is None else dev(v0)
         self.xc = torch.full((K, 3, N), float("nan"), dtype=torch.float32, device=DEV)
         self.cv = torch.full((K, N), 77, dtype=torch.uint8, device=DEV)
         self.Jo = torch.full((K, 9, N), float("nan"), dtype=torch.float32, device=DEV) if want_J else None

@@ -66,6 +66,10 @@ def test_precompute_init_solve_parity(lib, case):
     # solve from the GPU's own inits gives the same result (they are bit-equal)
     out2 = run.solve()
     np.testing.assert_array_equal(out2[1], out[1])
+    # the fused variant (initial states computed inside the solve kernel) gives the same bits
+    out3 = run.solve(fused=True)
+    for a, b in zip(out3, out):
+        np.testing.assert_array_equal(a.view(np.uint8), b.view(np.uint8))
     # last J~ of converged lanes, needed by the backward
     m = np.broadcast_to((ref[1] == 1)[:, None, :], ref[2].shape)
     np.testing.assert_allclose(out[2][m], ref[2][m], rtol=1e-5, atol=1e-6)
@@ -133,6 +137,8 @@ def test_edge_cases(lib):
     assert ctx.solve(run.xq, None, N, K + 1, x0, J0, v0, xc, cv, check=False) == binding.FS_E_SHAPE
     assert ctx.solve(run.xq, None, -1, K, x0, J0, v0, xc, cv, check=False) == binding.FS_E_SHAPE
     assert ctx.solve(run.xq, None, 2 ** 31, K, x0, J0, v0, xc, cv, check=False) == binding.FS_E_SHAPE
+    # fused initial states: all three NULL or none
+    assert ctx.solve(run.xq, None, N, K, None, J0, v0, xc, cv, check=False) == binding.FS_E_ARG
     # empty input is a no-op, also with null pointers
     assert ctx._L.fs_solve(ctx._h, None, None, 0, K, None, None, None, None, None, None, None) == binding.FS_OK
     assert ctx._L.fs_init(ctx._h, None, None, 0, None, None, None) == binding.FS_OK
