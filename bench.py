@@ -27,7 +27,12 @@ if ROOT not in sys.path:
 FLOP_EVAL = 237      # locate 12, corner weights 19, 8x12 tri-linear blend 180, T x 18, g 3, |g|^2 5
 FLOP_UPDATE = 63     # dg 3, v = J~^T dx 15, u = dx - J~ dg 18, v.dg 5, divide 1, u/den 3, rank-one 18
 FLOP_STEP = 18       # dx = -J~ g 15, x + dx 3
-PEAK_FP32_TFLOPS = 157.3
+LOADS_EVAL = 24      # 8 corner records x 3 rows of 16 bytes
+PEAK_FP32_TFLOPS = 157.3            # published fp32 vector peak (needs packed fp32 instructions)
+PEAK_FP32_UNPACKED_TFLOPS = 78.6    # 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz: one FMA per lane per clock
+# HBM traffic of one k_solve launch on the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE
+# (profiles/k_solve_config2_hbm_traffic.md); None for other workloads
+SOLVE_TRAFFIC_BYTES = {2: None}
 
 
 def main():
@@ -38,6 +43,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload configuration 1..5 (default 2: SMPL-scale)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-grad", action="store_true", help="leave fs_grad out of the step")
+    ap.add_argument("--probe-copy-mib", type=int, default=0,
+                    help="after the timed region copy this many MiB device to device once (a kernel of known "
+                         "traffic, for calibrating the FETCH_SIZE / WRITE_SIZE counters under rocprofv3)")
     ap.add_argument("--unfused", action="store_true",
                     help="materialise the initial states with fs_init instead of computing them inside fs_solve")
     args = ap.parse_args()
@@ -143,9 +151,32 @@ def main():
                      "flop_per_launch": flops, "avg_launch_ms": float(solve_ms)},
     }
 
+    # ceilings of the solve kernel measured on this device by the library's micro-benchmarks
+    grid_bytes = int(w.n_poses * w.dims[0] * w.dims[1] * w.dims[2] * 48)
+    fma = binding.microbench(binding.MB_FMA)
+    gl = binding.microbench(binding.MB_GATHER_LANE, max(grid_bytes, 4096))
+    gline = binding.microbench(binding.MB_GATHER_LINE, max(grid_bytes, 4096))
+    glds = binding.microbench(binding.MB_LDS_GATHER)
+    loads = evals * LOADS_EVAL / (solve_ms * 1e-3)
+    out["roofline"].update({
+        "peak_unpacked": PEAK_FP32_UNPACKED_TFLOPS, "frac_unpacked": achieved / PEAK_FP32_UNPACKED_TFLOPS,
+        "measured_fma_tflops": fma / 1e12,
+        "gather_path": {"algorithmic_16B_loads_per_s": loads,
+                        "ceiling_lane_random_gather_same_footprint": gl, "frac_of_lane_gather": loads / gl,
+                        "ceiling_line_coalesced_gather_same_footprint": gline,
+                        "ceiling_lds_lane_random_gather": glds, "footprint_bytes": grid_bytes},
+        "traffic": SOLVE_TRAFFIC_BYTES.get(args.config)})
+
+    if args.probe_copy_mib > 0:
+        a = torch.empty(args.probe_copy_mib << 18, dtype=f32, device=dev)
+        b = torch.ones(args.probe_copy_mib << 18, dtype=f32, device=dev)
+        torch.cuda.synchronize()
+        a.copy_(b)
+        torch.cuda.synchronize()
+
     if not args.no_cpu_baseline:
         import oracle
-        ncores = len(os.sched_getaffinity(0))
+        ncores = int(os.environ.get("OMP_NUM_THREADS", len(os.sched_getaffinity(0))))
         pz = w.pose if w.n_poses > 1 else None
         best = None
         for rep in range(2):

@@ -141,6 +141,17 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
 fs_status fs_get_transforms(fs_ctx *ctx, float *d_T);
 fs_status fs_get_corr(fs_ctx *ctx, float *d_bbox, int32_t *d_cand);
 
+/* Measurement support (not part of the articulation path): micro-benchmarks of the ceilings that bound
+ * fs_solve on the current device, run on the default stream, synchronising.
+ *   FS_MB_FMA          *result = fp32 flop/s of independent fused multiply-add chains
+ *   FS_MB_GATHER_LANE  *result = 16-byte loads per second when every SIMD lane reads its own random
+ *                      address inside an array of array_bytes (the tri-linear lookup's access pattern)
+ *   FS_MB_GATHER_LINE  same, but 8 adjacent lanes share one aligned 128-byte line
+ *   FS_MB_LDS_GATHER   16-byte loads per second, every lane its own random address in 48 KiB of LDS
+ * array_bytes is used by the two global gathers only (4 KiB .. 4 GiB). */
+enum { FS_MB_FMA = 0, FS_MB_GATHER_LANE = 1, FS_MB_GATHER_LINE = 2, FS_MB_LDS_GATHER = 3 };
+fs_status fs_microbench(int32_t which, int64_t array_bytes, double *result);
+
 /* Message for the last non-OK status returned on this context ("" if none). */
 const char *fs_last_error(const fs_ctx *ctx);
 

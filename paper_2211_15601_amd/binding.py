@@ -21,7 +21,7 @@ FS_INIT_BONE, FS_INIT_VOXEL = 0, 1
 FS_GRAD_BROYDEN_J, FS_GRAD_EXACT_J = 0, 1
 
 EXPORTS = ["fs_create", "fs_destroy", "fs_set_params", "fs_set_tuning", "fs_precompute", "fs_init", "fs_solve", "fs_grad",
-           "fs_get_transforms", "fs_get_corr", "fs_last_error", "fs_version"]
+           "fs_get_transforms", "fs_get_corr", "fs_microbench", "fs_last_error", "fs_version"]
 
 
 class GridDesc(ctypes.Structure):
@@ -70,7 +70,8 @@ def load():
     L.fs_version.argtypes = []
     L.fs_version.restype = ctypes.c_char_p
     L.fs_set_tuning.argtypes = [vp, i32, i32, i32]
-    for name in EXPORTS[:10]:
+    L.fs_microbench.argtypes = [i32, i64, ctypes.POINTER(ctypes.c_double)]
+    for name in EXPORTS[:11]:
         getattr(L, name).restype = ctypes.c_int
     _lib = L
     return L
@@ -158,6 +159,19 @@ class Context:
 
     def get_corr(self, bbox, cand, check=True):
         return self._ret(self._L.fs_get_corr(self._h, _ptr(bbox), _ptr(cand)), check)
+
+
+MB_FMA, MB_GATHER_LANE, MB_GATHER_LINE, MB_LDS_GATHER = range(4)
+
+
+def microbench(which: int, array_bytes: int = 3 << 20) -> float:
+    """Run one of the library's micro-benchmarks; returns flop/s (MB_FMA) or 16-byte loads/s."""
+    L = load()
+    r = ctypes.c_double()
+    st = L.fs_microbench(int(which), int(array_bytes), ctypes.byref(r))
+    if st != FS_OK:
+        raise FsError(st, "fs_microbench failed")
+    return r.value
 
 
 def version() -> str:

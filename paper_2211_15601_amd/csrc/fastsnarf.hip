@@ -41,6 +41,8 @@ struct fs_ctx {
     int *gpos;         // [K*N] position of a lane inside its cell's list (grows on demand)
     float *grec;       // [K*N][6] cell-sorted {x*, lambda} records (grows on demand)
     size_t gcap;       // lanes gpos / grec can hold
+    float4 *srec;      // per-pair result records of the solve kernel (grows on demand)
+    size_t srec_cap;   // float4 entries srec can hold
     int *scan_sums;    // tile sums of the prefix scans
     int scan_cap;      // tiles scan_sums can hold
     int n_cus, occ_blocks_per_cu, chunk, refill_min, blocks_per_cu;
@@ -119,7 +121,7 @@ int grid1d(long long n, int block) { return (int)((n + block - 1) / block); }
 void free_all(fs_ctx *c)
 {
     void *ptrs[] = {c->T, c->Bdev, c->Binv, c->Bok, c->GT, c->Y, c->bb_ord, c->bbox,
-                    c->cell_of, c->count, c->fill, c->order, c->cand, c->cursor, c->gcount, c->gpos, c->grec, c->scan_sums};
+                    c->cell_of, c->count, c->fill, c->order, c->cand, c->cursor, c->gcount, c->gpos, c->grec, c->scan_sums, c->srec};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
 }
@@ -202,7 +204,7 @@ fs_status fs_create(const fs_grid_desc *desc, const fs_params *params, void *hip
               dev_alloc(&c->Bok, P * nb) && dev_alloc(&c->cursor, 4);
     {
         int per_cu = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_solve<true>, 256, 0) != hipSuccess || per_cu < 1) per_cu = 2;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_solve<true, true>, 256, 0) != hipSuccess || per_cu < 1) per_cu = 2;
         c->blocks_per_cu = 2;   /* the kernel is bound by the vector-memory path: more waves only thrash the L1 */
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
         (void)hipGetLastError();
@@ -351,7 +353,6 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     const int wpb = 4;
     const int per_cu = std::max(1, std::min(ctx->blocks_per_cu, ctx->occ_blocks_per_cu));
     const int blocks = (int)std::min<long long>(grid1d(chunks, wpb), (long long)per_cu * ctx->n_cus);
-    k_reset_cursor<<<1, 64, 0, ctx->stream>>>(ctx->cursor);
     InitP I;
     I.mode = ctx->prm.init_mode;
     I.Binv = ctx->Binv;
@@ -359,12 +360,31 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     I.C = ctx->C;
     I.bbox = ctx->bbox;
     I.cand = ctx->cand;
-    if (fused)
-        k_solve<true><<<blocks, wpb * WAVE, 0, ctx->stream>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, nullptr, nullptr, nullptr,
-                                                              d_xc, d_conv, d_Jinv, d_iters, ctx->cursor);
+    const bool with_J = d_Jinv != nullptr;
+    const size_t need = (size_t)S.total * (with_J ? 4 : 1);
+    if (need > ctx->srec_cap) {
+        (void)hipStreamSynchronize(ctx->stream);
+        if (ctx->srec) (void)hipFree(ctx->srec);
+        ctx->srec = nullptr;
+        ctx->srec_cap = 0;
+        if (!dev_alloc(&ctx->srec, need)) return fail(ctx, FS_E_ALLOC, "fs_solve: out of device memory for %zu result records", (size_t)S.total);
+        ctx->srec_cap = need;
+    }
+    k_reset_cursor<<<1, 64, 0, ctx->stream>>>(ctx->cursor);
+    const dim3 grd(blocks), blk(wpb * WAVE);
+    hipStream_t st = ctx->stream;
+    if (fused && with_J)
+        k_solve<true, true><<<grd, blk, 0, st>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, nullptr, nullptr, nullptr, ctx->srec, ctx->cursor);
+    else if (fused)
+        k_solve<true, false><<<grd, blk, 0, st>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, nullptr, nullptr, nullptr, ctx->srec, ctx->cursor);
+    else if (with_J)
+        k_solve<false, true><<<grd, blk, 0, st>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, d_x0, d_Jinv0, d_valid0, ctx->srec, ctx->cursor);
     else
-        k_solve<false><<<blocks, wpb * WAVE, 0, ctx->stream>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, d_x0, d_Jinv0, d_valid0,
-                                                               d_xc, d_conv, d_Jinv, d_iters, ctx->cursor);
+        k_solve<false, false><<<grd, blk, 0, st>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, d_x0, d_Jinv0, d_valid0, ctx->srec, ctx->cursor);
+    if (with_J)
+        k_solve_unpack<true><<<grid1d(S.total, 256), 256, 0, st>>>(N, S.total, ctx->srec, d_xc, d_conv, d_Jinv, d_iters);
+    else
+        k_solve_unpack<false><<<grid1d(S.total, 256), 256, 0, st>>>(N, S.total, ctx->srec, d_xc, d_conv, d_Jinv, d_iters);
     return launch_status(ctx, "fs_solve");
 }
 

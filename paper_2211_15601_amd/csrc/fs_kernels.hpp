@@ -391,6 +391,45 @@ struct InitP {
     const int32_t *cand;      // [P][ncell][ck]
 };
 
+template <bool WITH_J>
+__device__ __forceinline__ void write_record(float4 *__restrict__ rec, long long pq, const float x[3], const float J[9],
+                                             int flags)
+{
+    if (WITH_J) {
+        float4 *o = rec + pq * 4;
+        o[0] = make_float4(x[0], x[1], x[2], __int_as_float(flags));
+        o[1] = make_float4(J[0], J[1], J[2], J[3]);
+        o[2] = make_float4(J[4], J[5], J[6], J[7]);
+        o[3] = make_float4(J[8], 0.0f, 0.0f, 0.0f);
+    } else {
+        rec[pq] = make_float4(x[0], x[1], x[2], __int_as_float(flags));
+    }
+}
+
+// records -> caller's layout: one thread per pair q = k*N + n, consecutive threads consecutive n
+template <bool WITH_J>
+__global__ __launch_bounds__(256) void k_solve_unpack(long long N, long long total, const float4 *__restrict__ rec,
+                                                      float *__restrict__ o_x, uint8_t *__restrict__ o_conv,
+                                                      float *__restrict__ o_J, uint8_t *__restrict__ o_it)
+{
+    const long long pq = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (pq >= total) return;
+    const long long k = pq / N, n = pq - k * N;
+    const float4 a = WITH_J ? rec[pq * 4] : rec[pq];
+    o_x[(k * 3 + 0) * N + n] = a.x;
+    o_x[(k * 3 + 1) * N + n] = a.y;
+    o_x[(k * 3 + 2) * N + n] = a.z;
+    const int flags = __float_as_int(a.w);
+    o_conv[pq] = (uint8_t)(flags & 1);
+    if (o_it) o_it[pq] = (uint8_t)(flags >> 8);
+    if (WITH_J) {
+        const float4 b = rec[pq * 4 + 1], c = rec[pq * 4 + 2], d = rec[pq * 4 + 3];
+        const float J[9] = {b.x, b.y, b.z, b.w, c.x, c.y, c.z, c.w, d.x};
+#pragma unroll
+        for (int e = 0; e < 9; ++e) o_J[(k * 9 + e) * N + n] = J[e];
+    }
+}
+
 __global__ void k_reset_cursor(unsigned *__restrict__ cursor)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) *cursor = 0u;
@@ -400,13 +439,18 @@ __global__ void k_reset_cursor(unsigned *__restrict__ cursor)
 // initial state when it picks up a pair (Sec. 3.1 "Custom CUDA Kernel": the kernel first computes the
 // initialisation states); the corner records fetched for the Jacobian then also serve the first
 // evaluation of the field, and the 53 bytes per pair of initial state never touch memory.
-template <bool FUSED>
+//
+// Results leave the kernel as one contiguous record per pair (lanes finish at different times, so
+// writing the caller's structure-of-arrays layout from here would touch 14 cache lines per pair with
+// 4 bytes each); k_solve_unpack then moves the records into that layout with coalesced stores.
+// Record: WITH_J ? 16 floats {x*[3], flags, J~[9], pad[3]} : 4 floats {x*[3], flags};
+// flags = conv | iters << 8 (as an integer bit pattern).
+template <bool FUSED, bool WITH_J>
 __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const float *__restrict__ T,
                                                const float *__restrict__ xq, const int32_t *__restrict__ pose,
                                                const float *__restrict__ x0, const float *__restrict__ J0,
-                                               const uint8_t *__restrict__ valid0, float *__restrict__ o_x,
-                                               uint8_t *__restrict__ o_conv, float *__restrict__ o_J,
-                                               uint8_t *__restrict__ o_it, unsigned *__restrict__ cursor)
+                                               const uint8_t *__restrict__ valid0, float4 *__restrict__ rec,
+                                               unsigned *__restrict__ cursor)
 {
     const int lane = threadIdx.x & 63;
     long long next = 0, c1 = 0;      // wave-uniform: the wave's current chunk is [next, c1)
@@ -494,14 +538,7 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const
                         active = true;
                         fresh = true;
                     } else {
-#pragma unroll
-                        for (int r = 0; r < 3; ++r) o_x[((long long)k * 3 + r) * N + n] = xt[r];
-                        o_conv[pq] = 0;
-                        if (o_J) {
-#pragma unroll
-                            for (int e = 0; e < 9; ++e) o_J[((long long)k * 9 + e) * N + n] = J[e];
-                        }
-                        if (o_it) o_it[pq] = 0;
+                        write_record<WITH_J>(rec, pq, xt, J, 0);
                     }
                 }
                 next += min((long long)nidle, c1 - next);
@@ -553,15 +590,7 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const
             const bool conv = r2 < S.tol2;
             const bool done = conv || !(r2 < S.div2) || it >= S.max_iters;
             if (done) {
-                const long long pq = (long long)k * N + n;
-#pragma unroll
-                for (int r = 0; r < 3; ++r) o_x[((long long)k * 3 + r) * N + n] = x[r];
-                o_conv[pq] = conv ? 1 : 0;
-                if (o_J) {
-#pragma unroll
-                    for (int e = 0; e < 9; ++e) o_J[((long long)k * 9 + e) * N + n] = J[e];
-                }
-                if (o_it) o_it[pq] = (uint8_t)it;
+                write_record<WITH_J>(rec, (long long)k * N + n, x, J, (conv ? 1 : 0) | (it << 8));
                 active = false;
             } else {
 #pragma unroll
