@@ -33,7 +33,7 @@ struct fs_ctx {
     float *bbox;       // [P][6]
     int *cell_of;      // [P][V]
     int *count;        // [P*ncell + 1] counts, then offsets
-    int *fill;         // [P*ncell]
+    int *fill;         // [P][V] arrival slot of a node inside its cell
     int *order;        // [P][V]
     int32_t *cand;     // [P][ncell][ck]
     unsigned *cursor;  // work cursor of the solve kernel
@@ -41,6 +41,9 @@ struct fs_ctx {
     int *gpos;         // [K*N] position of a lane inside its cell's list (grows on demand)
     float *grec;       // [K*N][6] cell-sorted {x*, lambda} records (grows on demand)
     size_t gcap;       // lanes gpos / grec can hold
+    int *glist;        // [1 + P*V] number of grid nodes with work, then their indices (backward)
+    float *gpart;      // [P][gb_blocks][nb*12] partial sums of dL/dB
+    int gb_blocks;
     float4 *srec;      // per-pair result records of the solve kernel (grows on demand)
     size_t srec_cap;   // float4 entries srec can hold
     int *scan_sums;    // tile sums of the prefix scans
@@ -121,7 +124,7 @@ int grid1d(long long n, int block) { return (int)((n + block - 1) / block); }
 void free_all(fs_ctx *c)
 {
     void *ptrs[] = {c->T, c->Bdev, c->Binv, c->Bok, c->GT, c->Y, c->bb_ord, c->bbox,
-                    c->cell_of, c->count, c->fill, c->order, c->cand, c->cursor, c->gcount, c->gpos, c->grec, c->scan_sums, c->srec};
+                    c->cell_of, c->count, c->fill, c->order, c->cand, c->cursor, c->gcount, c->gpos, c->grec, c->scan_sums, c->srec, c->glist, c->gpart};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
 }
@@ -218,7 +221,7 @@ fs_status fs_create(const fs_grid_desc *desc, const fs_params *params, void *hip
         C.cx = params->corr_nx; C.cy = params->corr_ny; C.cz = params->corr_nz; C.ck = params->corr_k;
         C.ncell = C.cx * C.cy * C.cz;
         ok = dev_alloc(&c->Y, P * V * 3) && dev_alloc(&c->bb_ord, P * 6) && dev_alloc(&c->bbox, P * 6) &&
-             dev_alloc(&c->cell_of, P * V) && dev_alloc(&c->count, P * C.ncell + 1) && dev_alloc(&c->fill, P * C.ncell) &&
+             dev_alloc(&c->cell_of, P * V) && dev_alloc(&c->count, P * C.ncell + 1) && dev_alloc(&c->fill, P * V) &&
              dev_alloc(&c->order, P * V) && dev_alloc(&c->cand, P * (size_t)C.ncell * C.ck);
     }
     if (!ok) {
@@ -275,15 +278,15 @@ fs_status fs_precompute(fs_ctx *ctx, const float *d_W, const float *d_B)
     if (hipMemcpyAsync(ctx->Bdev, d_B, sizeof(float) * nB, hipMemcpyDeviceToDevice, st) != hipSuccess)
         return launch_status(ctx, "fs_precompute: copy of bone transforms");
     k_bone_inverse<<<grid1d(G.P * G.nb, 64), 64, 0, st>>>(G.P * G.nb, d_B, ctx->Binv, ctx->Bok);
-    k_precompute<<<grid1d(G.V, 256), 256, sizeof(float) * nB, st>>>(G, d_W, d_B, ctx->T);
+    k_precompute<<<grid1d(G.V, 256), 256, 0, st>>>(G, d_W, d_B, ctx->T);
     if (ctx->prm.init_mode == FS_INIT_VOXEL) {
         const CorrP &C = ctx->C;
         const int ncp = G.P * C.ncell;
-        k_corr_reset<<<grid1d(ncp > G.P * 3 ? ncp : G.P * 3, 256), 256, 0, st>>>(G.P, C.ncell, ctx->bb_ord, ctx->count, ctx->fill);
+        k_corr_reset<<<grid1d(ncp > G.P * 3 ? ncp : G.P * 3, 256), 256, 0, st>>>(G.P, C.ncell, ctx->bb_ord, ctx->count);
         const dim3 gv(grid1d(G.V, 256), G.P);
-        k_corr_warp<<<gv, 256, 0, st>>>(G, ctx->T, ctx->Y, ctx->bb_ord);
+        k_corr_warp<<<dim3(std::min(grid1d(G.V, 256), 256), G.P), 256, 0, st>>>(G, ctx->T, ctx->Y, ctx->bb_ord);
         k_corr_bbox<<<1, 64 * ((G.P * 6 + 63) / 64), 0, st>>>(G.P, ctx->bb_ord, ctx->bbox);
-        k_corr_count<<<gv, 256, 0, st>>>(G, C, ctx->Y, ctx->bbox, ctx->cell_of, ctx->count);
+        k_corr_count<<<gv, 256, 0, st>>>(G, C, ctx->Y, ctx->bbox, ctx->cell_of, ctx->count, ctx->fill);
         { fs_status ss = scan_exclusive(ctx, ncp, ctx->count); if (ss != FS_OK) return ss; }
         k_corr_scatter<<<gv, 256, 0, st>>>(G, C, ctx->cell_of, ctx->count, ctx->fill, ctx->order);
         k_corr_select<<<grid1d((long long)ncp * WAVE, 256), 256, 0, st>>>(G, C, ctx->Y, ctx->bbox, ctx->count, ctx->order, ctx->cand);
@@ -370,9 +373,9 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
         if (!dev_alloc(&ctx->srec, need)) return fail(ctx, FS_E_ALLOC, "fs_solve: out of device memory for %zu result records", (size_t)S.total);
         ctx->srec_cap = need;
     }
-    k_reset_cursor<<<1, 64, 0, ctx->stream>>>(ctx->cursor);
-    const dim3 grd(blocks), blk(wpb * WAVE);
     hipStream_t st = ctx->stream;
+    k_reset_cursor<<<1, 64, 0, st>>>(ctx->cursor);
+    const dim3 grd(blocks), blk(wpb * WAVE);
     if (fused && with_J)
         k_solve<true, true><<<grd, blk, 0, st>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, nullptr, nullptr, nullptr, ctx->srec, ctx->cursor);
     else if (fused)
@@ -415,6 +418,11 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
     if (ncp + 1 >= (1ll << 31)) return fail(ctx, FS_E_SHAPE, "fs_grad: too many grid cells");
     if (!ctx->GT && !dev_alloc(&ctx->GT, (size_t)G.P * G.V * 12)) return fail(ctx, FS_E_ALLOC, "fs_grad: out of device memory");
     if (!ctx->gcount && !dev_alloc(&ctx->gcount, (size_t)ncp + 1)) return fail(ctx, FS_E_ALLOC, "fs_grad: out of device memory");
+    if (!ctx->glist && !dev_alloc(&ctx->glist, (size_t)G.P * G.V + 1)) return fail(ctx, FS_E_ALLOC, "fs_grad: out of device memory");
+    if (!ctx->gpart) {
+        ctx->gb_blocks = (int)std::min<long long>(grid1d(G.V, GB_TILE), 256);
+        if (!dev_alloc(&ctx->gpart, (size_t)G.P * ctx->gb_blocks * G.nb * 12)) return fail(ctx, FS_E_ALLOC, "fs_grad: out of device memory");
+    }
     const size_t lanes = (size_t)N * K;
     if (lanes > ctx->gcap) {
         (void)hipStreamSynchronize(ctx->stream);
@@ -427,17 +435,19 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
     }
     hipStream_t st = ctx->stream;
     k_fill_zero_i32<<<(int)std::min<long long>(grid1d(ncp + 1, 256), 4096), 256, 0, st>>>(ncp + 1, ctx->gcount);
-    k_fill_zero<<<grid1d(G.P * G.nb * 12, 256), 256, 0, st>>>((long long)G.P * G.nb * 12, d_gB);
+    k_fill_zero_i32<<<1, 64, 0, st>>>(1, ctx->glist);
     if (N > 0) k_grad_count<<<grid1d((long long)N * K, 256), 256, 0, st>>>(G, d_xc, d_conv, d_pose, N, K, ncell, ctx->gcount, ctx->gpos);
     { fs_status ss = scan_exclusive(ctx, (int)ncp, ctx->gcount); if (ss != FS_OK) return ss; }
     if (N > 0)
         k_grad_records<<<grid1d(N, 256), 256, 0, st>>>(G, mode, ctx->T, d_xc, d_Jinv, d_conv, d_gxc, d_pose, N, K, ncell,
                                                        ctx->gcount, ctx->gpos, ctx->grec, d_gxq);
-    k_grad_gather<<<grid1d((long long)G.P * G.V * WAVE, 256), 256, 0, st>>>(G, ncell, ctx->gcount, ctx->grec, ctx->GT);
+    k_grad_nodes<<<grid1d((long long)G.P * G.V, 256), 256, 0, st>>>(G, ncell, ctx->gcount, ctx->grec, ctx->GT, ctx->glist, ctx->glist + 1);
+    k_grad_gather<<<ctx->n_cus * 8, 256, 0, st>>>(G, ncell, ctx->gcount, ctx->grec, ctx->glist, ctx->glist + 1, ctx->GT);
     const size_t shB = sizeof(float) * G.P * G.nb * 12;
     k_grad_weights<<<grid1d(G.V * G.nb, 256), 256, shB, st>>>(G, ctx->GT, ctx->Bdev, d_gW);
-    const dim3 gb(grid1d(G.V, GB_TILE), G.P);
-    k_grad_bones<<<gb, 256, sizeof(float) * GB_TILE * (G.nb + 12), st>>>(G, d_W, ctx->GT, d_gB);
+    const int nout = G.nb * 12;
+    k_grad_bones_partial<<<dim3(ctx->gb_blocks, G.P), 256, sizeof(float) * GB_TILE * (G.nb + 12), st>>>(G, d_W, ctx->GT, ctx->gpart);
+    k_grad_bones_final<<<G.P * nout, 64, 0, st>>>(G.P, ctx->gb_blocks, nout, ctx->gpart, d_gB);
     return launch_status(ctx, "fs_grad");
 }
 

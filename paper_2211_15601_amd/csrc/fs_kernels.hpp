@@ -5,24 +5,30 @@
 namespace fs {
 
 constexpr int WAVE = 64;
+
+// pose index of point n, forced into [0, P) so that a bad index in the caller's array cannot send
+// a kernel outside the transform grids
+__device__ __forceinline__ int pose_of(const int32_t *__restrict__ pose, long long n, int P)
+{
+    if (!pose) return 0;
+    const int p = pose[n];
+    return p < 0 ? 0 : (p >= P ? P - 1 : p);
+}
 constexpr int FS_MAX_CORR_K_DEV = 8;
 
 // ------------------------------------------------------------------------------------------------
-// Pre-computed LBS (Eq. (13)): one thread per node, all poses; bone transforms staged in LDS.
+// Pre-computed LBS (Eq. (13)): one thread per node, all poses.  The bone transforms are read with
+// wave-uniform addresses, i.e. through the scalar cache into SGPR operands of the multiply-adds.
 // Reads W once (96 B / node for 24 bones), writes 48 B per node and pose.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_precompute(GridP G, const float *__restrict__ W,
                                                     const float *__restrict__ B, float *__restrict__ T)
 {
-    extern __shared__ float sB[];   // [P][nb][12]
-    const int nB = G.P * G.nb * 12;
-    for (int i = threadIdx.x; i < nB; i += blockDim.x) sB[i] = B[i];
-    __syncthreads();
     const long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (v >= G.V) return;
     const float *w = W + v * G.nb;
     for (int p = 0; p < G.P; ++p) {
-        const float *Bp = sB + p * G.nb * 12;
+        const float *Bp = B + (long long)p * G.nb * 12;
         float acc[12];
         const float w0 = w[0];
 #pragma unroll
@@ -80,7 +86,7 @@ __global__ __launch_bounds__(256) void k_init_bone(GridP G, const float *__restr
     if (q >= N * G.nb) return;
     const int k = (int)(q / N);
     const long long n = q - (long long)k * N;
-    const int p = pose ? pose[n] : 0;
+    const int p = pose_of(pose, n, G.P);
     const float *bi = Binv + ((long long)p * G.nb + k) * 12;
     float x0[3] = {0, 0, 0}, Ji[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
     bool ok = Bok[p * G.nb + k] != 0;
@@ -129,7 +135,7 @@ __global__ __launch_bounds__(256) void k_init_voxel(GridP G, CorrP C, const floa
     if (q >= N * C.ck) return;
     const int k = (int)(q / N);
     const long long n = q - (long long)k * N;
-    const int p = pose ? pose[n] : 0;
+    const int p = pose_of(pose, n, G.P);
     const float y[3] = {xq[n], xq[N + n], xq[2 * N + n]};
     const int cell = cell_index(C, bbox + p * 6, y);
     const int v = cand[((long long)p * C.ncell + cell) * C.ck + k];
@@ -158,23 +164,23 @@ __device__ __forceinline__ float ord2f(unsigned o)
     return __uint_as_float((o & 0x80000000u) ? (o & 0x7fffffffu) : ~o);
 }
 
-__global__ void k_corr_reset(int P, int ncell, unsigned *__restrict__ bb_ord, int *__restrict__ count,
-                             int *__restrict__ fill)
+__global__ void k_corr_reset(int P, int ncell, unsigned *__restrict__ bb_ord, int *__restrict__ count)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < P * 3) { bb_ord[(i / 3) * 6 + i % 3] = 0xffffffffu; bb_ord[(i / 3) * 6 + 3 + i % 3] = 0u; }
-    if (i < P * ncell) { count[i] = 0; fill[i] = 0; }
+    if (i < P * ncell) count[i] = 0;
     if (i == 0) count[P * ncell] = 0;
 }
 
-// images of all nodes, y_v = T_v x_v, and their bounding box per pose
+// images of all nodes, y_v = T_v x_v, and their bounding box per pose (grid-stride; one set of
+// atomics per block)
 __global__ __launch_bounds__(256) void k_corr_warp(GridP G, const float *__restrict__ T, float *__restrict__ Y,
                                                    unsigned *__restrict__ bb_ord)
 {
-    const long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    __shared__ unsigned smn[4][3], smx[4][3];
     const int p = blockIdx.y;
     unsigned mn[3] = {0xffffffffu, 0xffffffffu, 0xffffffffu}, mx[3] = {0u, 0u, 0u};
-    if (v < G.V) {
+    for (long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x; v < G.V; v += (long long)gridDim.x * blockDim.x) {
         float x[3], y[3], t[12];
         node_pos(G, v, x);
         load12(T + ((long long)p * G.V + v) * 12, t);
@@ -182,7 +188,11 @@ __global__ __launch_bounds__(256) void k_corr_warp(GridP G, const float *__restr
         float *o = Y + ((long long)p * G.V + v) * 3;
         o[0] = y[0]; o[1] = y[1]; o[2] = y[2];
 #pragma unroll
-        for (int a = 0; a < 3; ++a) mn[a] = mx[a] = f2ord(y[a]);
+        for (int a = 0; a < 3; ++a) {
+            const unsigned ov = f2ord(y[a]);
+            mn[a] = min(mn[a], ov);
+            mx[a] = max(mx[a], ov);
+        }
     }
 #pragma unroll
     for (int a = 0; a < 3; ++a) {
@@ -192,12 +202,16 @@ __global__ __launch_bounds__(256) void k_corr_warp(GridP G, const float *__restr
             mx[a] = max(mx[a], (unsigned)__shfl_xor((int)mx[a], s));
         }
     }
+    const int wid = threadIdx.x >> 6;
     if ((threadIdx.x & 63) == 0) {
 #pragma unroll
-        for (int a = 0; a < 3; ++a) {
-            atomicMin(bb_ord + p * 6 + a, mn[a]);
-            atomicMax(bb_ord + p * 6 + 3 + a, mx[a]);
-        }
+        for (int a = 0; a < 3; ++a) { smn[wid][a] = mn[a]; smx[wid][a] = mx[a]; }
+    }
+    __syncthreads();
+    if (threadIdx.x < 3) {
+        const int a = threadIdx.x;
+        atomicMin(bb_ord + p * 6 + a, min(min(smn[0][a], smn[1][a]), min(smn[2][a], smn[3][a])));
+        atomicMax(bb_ord + p * 6 + 3 + a, max(max(smx[0][a], smx[1][a]), max(smx[2][a], smx[3][a])));
     }
 }
 
@@ -209,7 +223,7 @@ __global__ void k_corr_bbox(int P, const unsigned *__restrict__ bb_ord, float *_
 
 __global__ __launch_bounds__(256) void k_corr_count(GridP G, CorrP C, const float *__restrict__ Y,
                                                     const float *__restrict__ bbox, int *__restrict__ cell_of,
-                                                    int *__restrict__ count)
+                                                    int *__restrict__ count, int *__restrict__ slot)
 {
     const long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     const int p = blockIdx.y;
@@ -218,7 +232,7 @@ __global__ __launch_bounds__(256) void k_corr_count(GridP G, CorrP C, const floa
     const float y[3] = {yp[0], yp[1], yp[2]};
     const int c = cell_index(C, bbox + p * 6, y);
     cell_of[(long long)p * G.V + v] = c;
-    atomicAdd(count + p * C.ncell + c, 1);
+    slot[(long long)p * G.V + v] = atomicAdd(count + p * C.ncell + c, 1);    // arrival order inside the cell
 }
 
 // Exclusive prefix sum of a[0..n) in place, a[n] = total.  Three launches: per-tile sums (tile = 4096
@@ -296,15 +310,14 @@ __global__ __launch_bounds__(1024) void k_scan_tiles(int n, int *__restrict__ a,
 }
 
 __global__ __launch_bounds__(256) void k_corr_scatter(GridP G, CorrP C, const int *__restrict__ cell_of,
-                                                      const int *__restrict__ offset, int *__restrict__ fill,
+                                                      const int *__restrict__ offset, const int *__restrict__ slot,
                                                       int *__restrict__ order)
 {
     const long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     const int p = blockIdx.y;
     if (v >= G.V) return;
     const int c = p * C.ncell + cell_of[(long long)p * G.V + v];
-    const int pos = atomicAdd(fill + c, 1);
-    order[offset[c] + pos] = (int)v;
+    order[offset[c] + slot[(long long)p * G.V + v]] = (int)v;
 }
 
 // One wave per cell.  Candidate j is the sample with the smallest (distance^2 of its image to the
@@ -467,9 +480,11 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const
     long long held = -1;             // grid offset of the cell whose corners q holds (-1: none)
 
     while (true) {
-        const unsigned long long idle = __ballot(!active);
-        const int nidle = __popcll(idle);
-        if (!exhausted && nidle >= S.refill_min) {
+        unsigned long long idle = __ballot(!active);
+        int nidle = __popcll(idle);
+        // hand out pairs until fewer than refill_min lanes are idle: a pair whose initial state is
+        // invalid is answered on the spot and its lane asks again
+        while (!exhausted && nidle >= S.refill_min) {
             if (next >= c1) {
                 unsigned b = 0;
                 if (lane == 0) b = atomicAdd(cursor, (unsigned)S.chunk);
@@ -487,7 +502,7 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const
                 if (!active && pq < c1) {
                     k = (int)(pq / N);
                     n = pq - (long long)k * N;
-                    const int p = pose ? pose[n] : 0;
+                    const int p = pose_of(pose, n, G.P);
                     Tp = T + (long long)p * G.V * 12;
                     it = 0;
                     held = -1;
@@ -532,17 +547,19 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const
                         for (int r = 0; r < 3; ++r) xt[r] = x0[((long long)k * 3 + r) * N + n];
 #pragma unroll
                         for (int e = 0; e < 9; ++e) J[e] = J0[((long long)k * 9 + e) * N + n];
-                        ok = valid0[pq] != 0;
+                        ok = valid0[(long long)k * N + n] != 0;
                     }
                     if (ok) {
                         active = true;
                         fresh = true;
                     } else {
-                        write_record<WITH_J>(rec, pq, xt, J, 0);
+                        write_record<WITH_J>(rec, (long long)k * N + n, xt, J, 0);
                     }
                 }
                 next += min((long long)nidle, c1 - next);
             }
+            idle = __ballot(!active);
+            nidle = __popcll(idle);
         }
         if (!__any(active)) {
             if (exhausted) break;
@@ -647,7 +664,7 @@ __global__ __launch_bounds__(256) void k_grad_count(GridP G, const float *__rest
     const float x[3] = {xc[((long long)k * 3 + 0) * N + n], xc[((long long)k * 3 + 1) * N + n],
                         xc[((long long)k * 3 + 2) * N + n]};
     const Cell c = locate(G, x);
-    const int p = pose ? pose[n] : 0;
+    const int p = pose_of(pose, n, G.P);
     pos[q] = atomicAdd(count + p * ncell + cell_linear(G, c), 1);
 }
 
@@ -662,7 +679,7 @@ __global__ __launch_bounds__(256) void k_grad_records(GridP G, int mode, const f
 {
     const long long n = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (n >= N) return;
-    const int p = pose ? pose[n] : 0;
+    const int p = pose_of(pose, n, G.P);
     float gq[3] = {0.0f, 0.0f, 0.0f};
     for (int k = 0; k < K; ++k) {
         const long long q = (long long)k * N + n;
@@ -703,56 +720,131 @@ __global__ __launch_bounds__(256) void k_grad_records(GridP G, int mode, const f
     }
 }
 
-// pass 3: one wave per (pose, node): sum over the lanes of the (up to) 8 cells that have the node as
-// a corner; lanes of the wave stride over a cell's records, then a butterfly reduction.
-__global__ __launch_bounds__(256) void k_grad_gather(GridP G, int ncell, const int *__restrict__ offset,
-                                                     const float *__restrict__ rec, float *__restrict__ GT)
+// pass 3a: one thread per (pose, node): nodes none of whose adjacent cells holds a lane get zeros at
+// once, nodes with a few lanes around them are summed by the thread itself, the others are appended
+// to a work list (one atomic per wave).
+constexpr int GRAD_LIGHT = 24;
+
+__device__ __forceinline__ void grad_accumulate(const GridP &G, const float *__restrict__ rec, int s, int da, int db,
+                                                int dc, float (&acc)[12])
 {
-    const long long wv = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const float2 *r = reinterpret_cast<const float2 *>(rec + (long long)s * 6);
+    const float2 r0 = r[0], r1 = r[1], r2 = r[2];
+    const float x[3] = {r0.x, r0.y, r1.x};
+    const float lam[3] = {r1.y, r2.x, r2.y};
+    const Cell c = locate(G, x);
+    const float wx = da ? c.f[0] : 1.0f - c.f[0];
+    const float wy = db ? c.f[1] : 1.0f - c.f[1];
+    const float wz = dc ? c.f[2] : 1.0f - c.f[2];
+    const float om = (wx * wy) * wz;
+#pragma unroll
+    for (int rr = 0; rr < 3; ++rr) {
+        const float wl = om * lam[rr];
+        acc[rr * 4 + 0] = FS_FMA(wl, x[0], acc[rr * 4 + 0]);
+        acc[rr * 4 + 1] = FS_FMA(wl, x[1], acc[rr * 4 + 1]);
+        acc[rr * 4 + 2] = FS_FMA(wl, x[2], acc[rr * 4 + 2]);
+        acc[rr * 4 + 3] += wl;
+    }
+}
+
+__device__ __forceinline__ int adjacent_cell(const GridP &G, int ncell, int p, int ix, int iy, int iz, int cn)
+{
+    const int cx = ix - (cn & 1), cy = iy - ((cn >> 1) & 1), cz = iz - ((cn >> 2) & 1);
+    if (cx < 0 || cy < 0 || cz < 0 || cx > G.nx - 2 || cy > G.ny - 2 || cz > G.nz - 2) return -1;
+    return p * ncell + (cx * (G.ny - 1) + cy) * (G.nz - 1) + cz;
+}
+
+__global__ __launch_bounds__(256) void k_grad_nodes(GridP G, int ncell, const int *__restrict__ offset,
+                                                    const float *__restrict__ rec, float *__restrict__ GT,
+                                                    int *__restrict__ nactive, int *__restrict__ list)
+{
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     const int lane = threadIdx.x & 63;
-    if (wv >= (long long)G.P * G.V) return;
-    const int p = (int)(wv / G.V);
-    const long long v = wv - (long long)p * G.V;
-    const int iz = (int)(v % G.nz), iy = (int)((v / G.nz) % G.ny), ix = (int)(v / ((long long)G.nz * G.ny));
-    float acc[12];
+    bool act = false;
+    if (i < (long long)G.P * G.V) {
+        const int p = (int)(i / G.V);
+        const long long v = i - (long long)p * G.V;
+        const int iz = (int)(v % G.nz), iy = (int)((v / G.nz) % G.ny), ix = (int)(v / ((long long)G.nz * G.ny));
+        int total = 0;
 #pragma unroll
-    for (int e = 0; e < 12; ++e) acc[e] = 0.0f;
-    for (int cn = 0; cn < 8; ++cn) {
-        const int da = cn & 1, db = (cn >> 1) & 1, dc = (cn >> 2) & 1;
-        const int cx = ix - da, cy = iy - db, cz = iz - dc;
-        if (cx < 0 || cy < 0 || cz < 0 || cx > G.nx - 2 || cy > G.ny - 2 || cz > G.nz - 2) continue;
-        const int cell = p * ncell + (cx * (G.ny - 1) + cy) * (G.nz - 1) + cz;
-        const int beg = offset[cell], end = offset[cell + 1];
-        for (int s = beg + lane; s < end; s += WAVE) {
-            const float2 *r = reinterpret_cast<const float2 *>(rec + (long long)s * 6);
-            const float2 r0 = r[0], r1 = r[1], r2 = r[2];
-            const float x[3] = {r0.x, r0.y, r1.x};
-            const float lam[3] = {r1.y, r2.x, r2.y};
-            const Cell c = locate(G, x);
-            const float wx = da ? c.f[0] : 1.0f - c.f[0];
-            const float wy = db ? c.f[1] : 1.0f - c.f[1];
-            const float wz = dc ? c.f[2] : 1.0f - c.f[2];
-            const float om = (wx * wy) * wz;
+        for (int cn = 0; cn < 8; ++cn) {
+            const int c = adjacent_cell(G, ncell, p, ix, iy, iz, cn);
+            if (c >= 0) total += offset[c + 1] - offset[c];
+        }
+        act = total > GRAD_LIGHT;
+        if (!act) {
+            float acc[12];
 #pragma unroll
-            for (int rr = 0; rr < 3; ++rr) {
-                const float wl = om * lam[rr];
-                acc[rr * 4 + 0] = FS_FMA(wl, x[0], acc[rr * 4 + 0]);
-                acc[rr * 4 + 1] = FS_FMA(wl, x[1], acc[rr * 4 + 1]);
-                acc[rr * 4 + 2] = FS_FMA(wl, x[2], acc[rr * 4 + 2]);
-                acc[rr * 4 + 3] += wl;
+            for (int e = 0; e < 12; ++e) acc[e] = 0.0f;
+            if (total > 0) {
+                for (int cn = 0; cn < 8; ++cn) {
+                    const int c = adjacent_cell(G, ncell, p, ix, iy, iz, cn);
+                    if (c < 0) continue;
+                    const int end = offset[c + 1];
+                    for (int s = offset[c]; s < end; ++s) grad_accumulate(G, rec, s, cn & 1, (cn >> 1) & 1, (cn >> 2) & 1, acc);
+                }
             }
+            float4 *o = reinterpret_cast<float4 *>(GT + i * 12);
+            o[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+            o[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+            o[2] = make_float4(acc[8], acc[9], acc[10], acc[11]);
         }
     }
-#pragma unroll
-    for (int e = 0; e < 12; ++e) {
-#pragma unroll
-        for (int s = 32; s >= 1; s >>= 1) acc[e] += __shfl_xor(acc[e], s);
+    const unsigned long long m = __ballot(act);
+    if (m) {
+        int base = 0;
+        if (lane == 0) base = atomicAdd(nactive, __popcll(m));
+        base = __shfl(base, 0);
+        if (act) list[base + __popcll(m & ((1ull << lane) - 1ull))] = (int)i;
     }
-    if (lane == 0) {
-        float4 *o = reinterpret_cast<float4 *>(GT + ((long long)p * G.V + v) * 12);
-        o[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
-        o[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
-        o[2] = make_float4(acc[8], acc[9], acc[10], acc[11]);
+}
+
+// pass 3b: waves stride over the work list.  A node with few lanes around it is handled with 8 SIMD
+// lanes per adjacent cell (all 8 cells at once); one with many, cell after cell with the whole wave.
+// A butterfly reduction over the wave follows.
+__global__ __launch_bounds__(256) void k_grad_gather(GridP G, int ncell, const int *__restrict__ offset,
+                                                     const float *__restrict__ rec, const int *__restrict__ nactive,
+                                                     const int *__restrict__ list, float *__restrict__ GT)
+{
+    const int lane = threadIdx.x & 63;
+    const int nwaves = (gridDim.x * blockDim.x) >> 6;
+    const int n = *nactive;
+    for (int w = (blockIdx.x * blockDim.x + threadIdx.x) >> 6; w < n; w += nwaves) {
+        const long long i = list[w];
+        const int p = (int)(i / G.V);
+        const long long v = i - (long long)p * G.V;
+        const int iz = (int)(v % G.nz), iy = (int)((v / G.nz) % G.ny), ix = (int)(v / ((long long)G.nz * G.ny));
+        float acc[12];
+#pragma unroll
+        for (int e = 0; e < 12; ++e) acc[e] = 0.0f;
+        // lane 8c+j looks at adjacent cell c
+        const int mycn = lane >> 3;
+        const int mycell = adjacent_cell(G, ncell, p, ix, iy, iz, mycn);
+        const int mybeg = mycell >= 0 ? offset[mycell] : 0, myend = mycell >= 0 ? offset[mycell + 1] : 0;
+        int longest = myend - mybeg;
+#pragma unroll
+        for (int s = 32; s >= 8; s >>= 1) longest = max(longest, __shfl_xor(longest, s));
+        if (longest <= 256) {
+            for (int s = mybeg + (lane & 7); s < myend; s += 8)
+                grad_accumulate(G, rec, s, mycn & 1, (mycn >> 1) & 1, (mycn >> 2) & 1, acc);
+        } else {
+            for (int cn = 0; cn < 8; ++cn) {
+                const int beg = __shfl(mybeg, cn * 8), end = __shfl(myend, cn * 8);
+                for (int s = beg + lane; s < end; s += WAVE)
+                    grad_accumulate(G, rec, s, cn & 1, (cn >> 1) & 1, (cn >> 2) & 1, acc);
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 12; ++e) {
+#pragma unroll
+            for (int s = 32; s >= 1; s >>= 1) acc[e] += __shfl_xor(acc[e], s);
+        }
+        if (lane == 0) {
+            float4 *o = reinterpret_cast<float4 *>(GT + i * 12);
+            o[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+            o[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+            o[2] = make_float4(acc[8], acc[9], acc[10], acc[11]);
+        }
     }
 }
 
@@ -779,26 +871,57 @@ __global__ __launch_bounds__(256) void k_grad_weights(GridP G, const float *__re
     gW[o] = acc;
 }
 
-// gB[p][b][e] = sum_v W[v][b] G_T[p][v][e]; a block reduces a tile of nodes, then one atomic per output.
+// gB[p][b][e] = sum_v W[v][b] G_T[p][v][e] in two stages without atomics: blocks stride over tiles of
+// nodes and write one partial sum per output, then one thread per output adds the partials.
 constexpr int GB_TILE = 128;
-__global__ __launch_bounds__(256) void k_grad_bones(GridP G, const float *__restrict__ W,
-                                                    const float *__restrict__ GT, float *__restrict__ gB)
+constexpr int GB_MAX_OUT = 3;     // outputs per thread: n_bones * 12 <= 768 = 3 * 256
+__global__ __launch_bounds__(256) void k_grad_bones_partial(GridP G, const float *__restrict__ W,
+                                                            const float *__restrict__ GT, float *__restrict__ part)
 {
     extern __shared__ float sm[];              // sW [GB_TILE][nb] then sG [GB_TILE][12]
     float *sW = sm;
     float *sG = sm + GB_TILE * G.nb;
     const int p = blockIdx.y;
-    const long long v0 = (long long)blockIdx.x * GB_TILE;
-    const int cnt = (int)min((long long)GB_TILE, G.V - v0);
-    for (int i = threadIdx.x; i < cnt * G.nb; i += blockDim.x) sW[i] = W[v0 * G.nb + i];
-    for (int i = threadIdx.x; i < cnt * 12; i += blockDim.x) sG[i] = GT[((long long)p * G.V + v0) * 12 + i];
-    __syncthreads();
-    for (int o = threadIdx.x; o < G.nb * 12; o += blockDim.x) {
-        const int b = o / 12, e = o - b * 12;
-        float acc = 0.0f;
-        for (int i = 0; i < cnt; ++i) acc = FS_FMA(sW[i * G.nb + b], sG[i * 12 + e], acc);
-        unsafeAtomicAdd(gB + ((long long)p * G.nb + b) * 12 + e, acc);
+    const int nout = G.nb * 12;
+    const int ntiles = (int)((G.V + GB_TILE - 1) / GB_TILE);
+    float acc[GB_MAX_OUT] = {0.0f, 0.0f, 0.0f};
+    for (int t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        const long long v0 = (long long)t * GB_TILE;
+        const int cnt = (int)min((long long)GB_TILE, G.V - v0);
+        __syncthreads();
+        for (int i = threadIdx.x; i < cnt * G.nb; i += blockDim.x) sW[i] = W[v0 * G.nb + i];
+        for (int i = threadIdx.x; i < cnt * 12; i += blockDim.x) sG[i] = GT[((long long)p * G.V + v0) * 12 + i];
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < GB_MAX_OUT; ++u) {
+            const int o = threadIdx.x + u * 256;
+            if (o < nout) {
+                const int b = o / 12, e = o - b * 12;
+                float a = acc[u];
+                for (int i = 0; i < cnt; ++i) a = FS_FMA(sW[i * G.nb + b], sG[i * 12 + e], a);
+                acc[u] = a;
+            }
+        }
     }
+#pragma unroll
+    for (int u = 0; u < GB_MAX_OUT; ++u) {
+        const int o = threadIdx.x + u * 256;
+        if (o < nout) part[((long long)p * gridDim.x + blockIdx.x) * nout + o] = acc[u];
+    }
+}
+
+// one wave per output adds that output's partial sums
+__global__ __launch_bounds__(64) void k_grad_bones_final(int P, int nblk, int nout, const float *__restrict__ part,
+                                                         float *__restrict__ gB)
+{
+    const int i = blockIdx.x;
+    if (i >= P * nout) return;
+    const int p = i / nout, o = i - p * nout;
+    float a = 0.0f;
+    for (int b = threadIdx.x; b < nblk; b += WAVE) a += part[((long long)p * nblk + b) * nout + o];
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) a += __shfl_xor(a, s);
+    if (threadIdx.x == 0) gB[i] = a;
 }
 
 }  // namespace fs
