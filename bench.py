@@ -2,13 +2,15 @@
 """Benchmark of the Fast-SNARF articulation hot path on one MI355X.
 
 One "step" = one pass of the whole path over one synthetic batch that is already resident in
-HBM: fs_precompute -> fs_init -> fs_solve (keeping J~ and iteration counts) -> fs_grad.
+HBM: fs_precompute -> fs_solve (initial states computed inside the kernel; J~ and iteration counts
+kept) -> fs_grad.  `--unfused` materialises the initial states with fs_init first.
 Workload: the SMPL-scale single-pose configuration (24 bones, 64x64x16 weight grid,
 65,536 query points x 24 per-bone initial states, max 50 iterations, tol 1e-5).
 
 Prints ONE JSON line.  `value` = converged (point, init) root solves per second over the whole
-step.  `roofline` describes the Broyden solve kernel (the dominant one), timed with events on
-the stream it runs on.  `cpu_baseline` is the CPU oracle timed on this machine's host cores.
+step.  `roofline` describes the Broyden kernel k_solve (the dominant one), timed by the library with
+HIP events around that kernel on the stream it runs on.  `cpu_baseline` is the CPU oracle timed on
+this machine's host cores.
 """
 import argparse
 import json
@@ -32,7 +34,7 @@ PEAK_FP32_TFLOPS = 157.3            # published fp32 vector peak (needs packed f
 PEAK_FP32_UNPACKED_TFLOPS = 78.6    # 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz: one FMA per lane per clock
 # HBM traffic of one k_solve launch on the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE
 # (profiles/k_solve_config2_hbm_traffic.md); None for other workloads
-SOLVE_TRAFFIC_BYTES = {2: None}
+SOLVE_TRAFFIC_BYTES = {2: 204.6e6}
 
 
 def main():
@@ -109,6 +111,7 @@ def main():
     for _ in range(args.warmup):
         step(False)
     torch.cuda.synchronize()
+    ctx.set_timing(True)          # HIP events around the Broyden kernel itself, on its stream
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step(True)
@@ -116,6 +119,9 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
+    kernel_ms_total, kernel_launches = ctx.get_timing()
+    ctx.set_timing(False)
+    solve_kernel_ms = kernel_ms_total / max(kernel_launches, 1)
     phases = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(4)] for e in marks])   # ms
     pre_ms, init_ms, solve_ms, grad_ms = phases.mean(0)
 
@@ -126,7 +132,7 @@ def main():
     steps_total = int(it.to(torch.int64)[v0 == 1].sum().item())
     evals = steps_total + valid                       # field evaluations = active lane-iterations
     flops = evals * FLOP_EVAL + steps_total * (FLOP_UPDATE + FLOP_STEP)
-    achieved = flops / (solve_ms * 1e-3) / 1e12
+    achieved = flops / (solve_kernel_ms * 1e-3) / 1e12
 
     out = {
         "metric": "converged (point, init) root solves/sec",
@@ -148,7 +154,7 @@ def main():
                        "lane_iterations_per_s": evals / (solve_ms * 1e-3)},
         "roofline": {"kernel": "k_solve", "bound": "alu", "achieved": achieved, "peak": PEAK_FP32_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_TFLOPS, "traffic": None,
-                     "flop_per_launch": flops, "avg_launch_ms": float(solve_ms)},
+                     "flop_per_launch": flops, "avg_launch_ms": float(solve_kernel_ms), "launches_timed": kernel_launches},
     }
 
     # ceilings of the solve kernel measured on this device by the library's micro-benchmarks
@@ -157,7 +163,7 @@ def main():
     gl = binding.microbench(binding.MB_GATHER_LANE, max(grid_bytes, 4096))
     gline = binding.microbench(binding.MB_GATHER_LINE, max(grid_bytes, 4096))
     glds = binding.microbench(binding.MB_LDS_GATHER)
-    loads = evals * LOADS_EVAL / (solve_ms * 1e-3)
+    loads = evals * LOADS_EVAL / (solve_kernel_ms * 1e-3)
     out["roofline"].update({
         "peak_unpacked": PEAK_FP32_UNPACKED_TFLOPS, "frac_unpacked": achieved / PEAK_FP32_UNPACKED_TFLOPS,
         "measured_fma_tflops": fma / 1e12,

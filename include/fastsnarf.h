@@ -134,6 +134,13 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
                   const uint8_t *d_conv, const float *d_gxc, const int32_t *d_pose, int64_t N, int32_t K,
                   float *d_gW, float *d_gB, float *d_gxq);
 
+/* Timing of the Broyden kernel alone (k_solve, without the unpacking of its results): while enabled,
+ * every fs_solve brackets that kernel with two HIP events on the context's stream.  fs_get_timing
+ * synchronises the stream, returns the summed elapsed milliseconds and the number of launches since
+ * the last call, and releases the events. */
+fs_status fs_set_timing(fs_ctx *ctx, int32_t enable);
+fs_status fs_get_timing(fs_ctx *ctx, double *solve_kernel_ms, int32_t *launches);
+
 /* Copy library-owned state out for inspection (device to device, on the stream).
  *   fs_get_transforms: d_T [n_poses][V][12], the pre-computed grid in node order.
  *   fs_get_corr: d_bbox [n_poses][6] (lo xyz, hi xyz), d_cand [n_poses][ncell][corr_k] node index

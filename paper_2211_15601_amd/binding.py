@@ -21,7 +21,7 @@ FS_INIT_BONE, FS_INIT_VOXEL = 0, 1
 FS_GRAD_BROYDEN_J, FS_GRAD_EXACT_J = 0, 1
 
 EXPORTS = ["fs_create", "fs_destroy", "fs_set_params", "fs_set_tuning", "fs_precompute", "fs_init", "fs_solve", "fs_grad",
-           "fs_get_transforms", "fs_get_corr", "fs_microbench", "fs_last_error", "fs_version"]
+           "fs_get_transforms", "fs_get_corr", "fs_microbench", "fs_set_timing", "fs_get_timing", "fs_last_error", "fs_version"]
 
 
 class GridDesc(ctypes.Structure):
@@ -71,7 +71,9 @@ def load():
     L.fs_version.restype = ctypes.c_char_p
     L.fs_set_tuning.argtypes = [vp, i32, i32, i32]
     L.fs_microbench.argtypes = [i32, i64, ctypes.POINTER(ctypes.c_double)]
-    for name in EXPORTS[:11]:
+    L.fs_set_timing.argtypes = [vp, i32]
+    L.fs_get_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
+    for name in EXPORTS[:13]:
         getattr(L, name).restype = ctypes.c_int
     _lib = L
     return L
@@ -153,6 +155,15 @@ class Context:
     def grad(self, W, xc, Jinv, conv, gxc, pose, N, K, gW, gB, gxq=None, check=True):
         return self._ret(self._L.fs_grad(self._h, _ptr(W), _ptr(xc), _ptr(Jinv), _ptr(conv), _ptr(gxc), _ptr(pose),
                                          N, K, _ptr(gW), _ptr(gB), _ptr(gxq)), check)
+
+    def set_timing(self, enable=True, check=True):
+        return self._ret(self._L.fs_set_timing(self._h, int(bool(enable))), check)
+
+    def get_timing(self):
+        """(summed k_solve milliseconds, launches) since the last call; synchronises the stream."""
+        ms, n = ctypes.c_double(), ctypes.c_int32()
+        self._ret(self._L.fs_get_timing(self._h, ctypes.byref(ms), ctypes.byref(n)), True)
+        return ms.value, n.value
 
     def get_transforms(self, T, check=True):
         return self._ret(self._L.fs_get_transforms(self._h, _ptr(T)), check)

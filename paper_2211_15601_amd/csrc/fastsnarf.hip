@@ -10,6 +10,8 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <utility>
+#include <vector>
 
 using namespace fs;
 
@@ -49,6 +51,9 @@ struct fs_ctx {
     int *scan_sums;    // tile sums of the prefix scans
     int scan_cap;      // tiles scan_sums can hold
     int n_cus, occ_blocks_per_cu, chunk, refill_min, blocks_per_cu;
+    // optional timing of the Broyden kernel alone (events on the context's stream)
+    bool timing;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> *timed;
     char err[256];
 };
 
@@ -237,6 +242,13 @@ fs_status fs_destroy(fs_ctx *ctx)
 {
     if (!ctx) return FS_OK;
     (void)hipStreamSynchronize(ctx->stream);
+    if (ctx->timed) {
+        for (auto &e : *ctx->timed) {
+            (void)hipEventDestroy(e.first);
+            (void)hipEventDestroy(e.second);
+        }
+        delete ctx->timed;
+    }
     free_all(ctx);
     delete ctx;
     return FS_OK;
@@ -376,6 +388,8 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     hipStream_t st = ctx->stream;
     k_reset_cursor<<<1, 64, 0, st>>>(ctx->cursor);
     const dim3 grd(blocks), blk(wpb * WAVE);
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    if (ctx->timing && hipEventCreate(&ev0) == hipSuccess && hipEventCreate(&ev1) == hipSuccess) (void)hipEventRecord(ev0, st);
     if (fused && with_J)
         k_solve<true, true><<<grd, blk, 0, st>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, nullptr, nullptr, nullptr, ctx->srec, ctx->cursor);
     else if (fused)
@@ -384,6 +398,10 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
         k_solve<false, true><<<grd, blk, 0, st>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, d_x0, d_Jinv0, d_valid0, ctx->srec, ctx->cursor);
     else
         k_solve<false, false><<<grd, blk, 0, st>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, d_x0, d_Jinv0, d_valid0, ctx->srec, ctx->cursor);
+    if (ev0 && ev1) {
+        (void)hipEventRecord(ev1, st);
+        ctx->timed->emplace_back(ev0, ev1);
+    }
     if (with_J)
         k_solve_unpack<true><<<grid1d(S.total, 256), 256, 0, st>>>(N, S.total, ctx->srec, d_xc, d_conv, d_Jinv, d_iters);
     else
@@ -449,6 +467,38 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
     k_grad_bones_partial<<<dim3(ctx->gb_blocks, G.P), 256, sizeof(float) * GB_TILE * (G.nb + 12), st>>>(G, d_W, ctx->GT, ctx->gpart);
     k_grad_bones_final<<<G.P * nout, 64, 0, st>>>(G.P, ctx->gb_blocks, nout, ctx->gpart, d_gB);
     return launch_status(ctx, "fs_grad");
+}
+
+fs_status fs_set_timing(fs_ctx *ctx, int32_t enable)
+{
+    if (!ctx) return FS_E_ARG;
+    if (enable && !ctx->timed) {
+        ctx->timed = new (std::nothrow) std::vector<std::pair<hipEvent_t, hipEvent_t>>();
+        if (!ctx->timed) return fail(ctx, FS_E_ALLOC, "fs_set_timing: out of host memory");
+    }
+    ctx->timing = enable != 0;
+    return FS_OK;
+}
+
+fs_status fs_get_timing(fs_ctx *ctx, double *solve_kernel_ms, int32_t *launches)
+{
+    if (!ctx || !solve_kernel_ms || !launches) return FS_E_ARG;
+    *solve_kernel_ms = 0.0;
+    *launches = 0;
+    if (!ctx->timed) return FS_OK;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return launch_status(ctx, "fs_get_timing");
+    for (auto &e : *ctx->timed) {
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, e.first, e.second) == hipSuccess) {
+            *solve_kernel_ms += ms;
+            ++*launches;
+        }
+        (void)hipEventDestroy(e.first);
+        (void)hipEventDestroy(e.second);
+    }
+    (void)hipGetLastError();
+    ctx->timed->clear();
+    return FS_OK;
 }
 
 fs_status fs_get_transforms(fs_ctx *ctx, float *d_T)

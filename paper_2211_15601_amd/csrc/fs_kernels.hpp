@@ -723,7 +723,7 @@ __global__ __launch_bounds__(256) void k_grad_records(GridP G, int mode, const f
 // pass 3a: one thread per (pose, node): nodes none of whose adjacent cells holds a lane get zeros at
 // once, nodes with a few lanes around them are summed by the thread itself, the others are appended
 // to a work list (one atomic per wave).
-constexpr int GRAD_LIGHT = 24;
+constexpr int GRAD_LIGHT = 32;
 
 __device__ __forceinline__ void grad_accumulate(const GridP &G, const float *__restrict__ rec, int s, int da, int db,
                                                 int dc, float (&acc)[12])
