@@ -86,8 +86,10 @@ fs_status fs_set_params(fs_ctx *ctx, const fs_params *params);
 /* Launch-shape knobs of the solve kernel; results never depend on them.  chunk = lanes a wave draws
  * from the work cursor at a time (64..65536), refill_min = idle SIMD lanes that trigger a refill
  * (1..64), blocks_per_cu = resident 256-thread blocks per compute unit (capped by what the occupancy
- * query reports).  A value of 0 keeps the current setting. */
-fs_status fs_set_tuning(fs_ctx *ctx, int32_t chunk, int32_t refill_min, int32_t blocks_per_cu);
+ * query reports); for these a value of 0 keeps the current setting.  point_major = 1: consecutive SIMD
+ * lanes take the K initial states of one point, 0: consecutive points with the same initial state,
+ * -1: keep. */
+fs_status fs_set_tuning(fs_ctx *ctx, int32_t chunk, int32_t refill_min, int32_t blocks_per_cu, int32_t point_major);
 
 /* Pre-compute linear blend skinning on the grid nodes, Eq. (13) / Sec. 3.1 "Pre-computing
  * LBS": T[p][v] = sum_b W[v][b] * B[p][b], bones accumulated in index order with fused

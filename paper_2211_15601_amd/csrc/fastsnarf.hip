@@ -49,8 +49,11 @@ struct fs_ctx {
     float4 *srec;      // per-pair result records of the solve kernel (grows on demand)
     size_t srec_cap;   // float4 entries srec can hold
     int *scan_sums;    // tile sums of the prefix scans
+    int *voffs;        // [N + 1] candidates per point, then offsets (fused voxel solve; grows on demand)
+    int *vlist;        // [K*N] pairs that have a candidate
+    size_t vcap;       // points voffs / vlist can hold
     int scan_cap;      // tiles scan_sums can hold
-    int n_cus, occ_blocks_per_cu, chunk, refill_min, blocks_per_cu;
+    int n_cus, occ_blocks_per_cu, chunk, refill_min, blocks_per_cu, point_major;
     // optional timing of the Broyden kernel alone (events on the context's stream)
     bool timing;
     std::vector<std::pair<hipEvent_t, hipEvent_t>> *timed;
@@ -129,7 +132,7 @@ int grid1d(long long n, int block) { return (int)((n + block - 1) / block); }
 void free_all(fs_ctx *c)
 {
     void *ptrs[] = {c->T, c->Bdev, c->Binv, c->Bok, c->GT, c->Y, c->bb_ord, c->bbox,
-                    c->cell_of, c->count, c->fill, c->order, c->cand, c->cursor, c->gcount, c->gpos, c->grec, c->scan_sums, c->srec, c->glist, c->gpart};
+                    c->cell_of, c->count, c->fill, c->order, c->cand, c->cursor, c->gcount, c->gpos, c->grec, c->scan_sums, c->srec, c->glist, c->gpart, c->voffs, c->vlist};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
 }
@@ -213,7 +216,8 @@ fs_status fs_create(const fs_grid_desc *desc, const fs_params *params, void *hip
     {
         int per_cu = 0, cus = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_solve<true, true>, 256, 0) != hipSuccess || per_cu < 1) per_cu = 2;
-        c->blocks_per_cu = 2;   /* the kernel is bound by the vector-memory path: more waves only thrash the L1 */
+        c->blocks_per_cu = 2;
+        c->point_major = 1;   /* the kernel is bound by the vector-memory path: more waves only thrash the L1 */
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
         (void)hipGetLastError();
         c->n_cus = cus;
@@ -267,15 +271,16 @@ fs_status fs_set_params(fs_ctx *ctx, const fs_params *params)
     return FS_OK;
 }
 
-fs_status fs_set_tuning(fs_ctx *ctx, int32_t chunk, int32_t refill_min, int32_t blocks_per_cu)
+fs_status fs_set_tuning(fs_ctx *ctx, int32_t chunk, int32_t refill_min, int32_t blocks_per_cu, int32_t point_major)
 {
     if (!ctx) return FS_E_ARG;
     if ((chunk != 0 && (chunk < 64 || chunk > 65536)) || (refill_min != 0 && (refill_min < 1 || refill_min > 64)) ||
-        blocks_per_cu < 0 || blocks_per_cu > 32)
+        blocks_per_cu < 0 || blocks_per_cu > 32 || point_major < -1 || point_major > 1)
         return fail(ctx, FS_E_ARG, "fs_set_tuning: value out of range");
     if (chunk) ctx->chunk = chunk;
     if (refill_min) ctx->refill_min = refill_min;
     if (blocks_per_cu) ctx->blocks_per_cu = blocks_per_cu;
+    if (point_major >= 0) ctx->point_major = point_major;
     return FS_OK;
 }
 
@@ -362,6 +367,8 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     S.max_iters = ctx->prm.max_iters;
     S.tol2 = ctx->prm.tol * ctx->prm.tol;
     S.div2 = ctx->prm.div_thresh * ctx->prm.div_thresh;
+    S.K = K;
+    S.point_major = ctx->point_major;
     S.chunk = ctx->chunk;
     S.refill_min = ctx->refill_min;
     const long long chunks = (S.total + S.chunk - 1) / S.chunk;
@@ -386,26 +393,50 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
         ctx->srec_cap = need;
     }
     hipStream_t st = ctx->stream;
+    const int *list = nullptr, *list_len = nullptr;
+    if (fused && ctx->prm.init_mode == FS_INIT_VOXEL) {
+        if ((size_t)N > ctx->vcap) {
+            (void)hipStreamSynchronize(st);
+            if (ctx->voffs) (void)hipFree(ctx->voffs);
+            if (ctx->vlist) (void)hipFree(ctx->vlist);
+            ctx->voffs = ctx->vlist = nullptr;
+            ctx->vcap = 0;
+            if (!dev_alloc(&ctx->voffs, (size_t)N + 1) || !dev_alloc(&ctx->vlist, (size_t)N * K))
+                return fail(ctx, FS_E_ALLOC, "fs_solve: out of device memory for the pair list");
+            ctx->vcap = (size_t)N;
+        }
+        k_voxel_count<<<grid1d(N, 256), 256, 0, st>>>(ctx->G, I, N, d_xq, d_pose, ctx->voffs);
+        { fs_status ss = scan_exclusive(ctx, (int)N, ctx->voffs); if (ss != FS_OK) return ss; }
+        k_voxel_expand<<<grid1d(N, 256), 256, 0, st>>>(N, K, ctx->voffs, ctx->vlist);
+        list = ctx->vlist;
+        list_len = ctx->voffs + N;
+    }
     k_reset_cursor<<<1, 64, 0, st>>>(ctx->cursor);
     const dim3 grd(blocks), blk(wpb * WAVE);
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     if (ctx->timing && hipEventCreate(&ev0) == hipSuccess && hipEventCreate(&ev1) == hipSuccess) (void)hipEventRecord(ev0, st);
     if (fused && with_J)
-        k_solve<true, true><<<grd, blk, 0, st>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, nullptr, nullptr, nullptr, ctx->srec, ctx->cursor);
+        k_solve<true, true><<<grd, blk, 0, st>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, nullptr, nullptr, nullptr, ctx->srec, ctx->cursor, list, list_len);
     else if (fused)
-        k_solve<true, false><<<grd, blk, 0, st>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, nullptr, nullptr, nullptr, ctx->srec, ctx->cursor);
+        k_solve<true, false><<<grd, blk, 0, st>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, nullptr, nullptr, nullptr, ctx->srec, ctx->cursor, list, list_len);
     else if (with_J)
-        k_solve<false, true><<<grd, blk, 0, st>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, d_x0, d_Jinv0, d_valid0, ctx->srec, ctx->cursor);
+        k_solve<false, true><<<grd, blk, 0, st>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, d_x0, d_Jinv0, d_valid0, ctx->srec, ctx->cursor, list, list_len);
     else
-        k_solve<false, false><<<grd, blk, 0, st>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, d_x0, d_Jinv0, d_valid0, ctx->srec, ctx->cursor);
+        k_solve<false, false><<<grd, blk, 0, st>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, d_x0, d_Jinv0, d_valid0, ctx->srec, ctx->cursor, list, list_len);
     if (ev0 && ev1) {
         (void)hipEventRecord(ev1, st);
         ctx->timed->emplace_back(ev0, ev1);
     }
-    if (with_J)
-        k_solve_unpack<true><<<grid1d(S.total, 256), 256, 0, st>>>(N, S.total, ctx->srec, d_xc, d_conv, d_Jinv, d_iters);
+    const bool nocand = fused && ctx->prm.init_mode == FS_INIT_VOXEL;
+    const int ub = grid1d(S.total, 256);
+    if (with_J && nocand)
+        k_solve_unpack<true, true><<<ub, 256, 0, st>>>(ctx->G, I, N, S.total, d_xq, d_pose, ctx->srec, d_xc, d_conv, d_Jinv, d_iters);
+    else if (with_J)
+        k_solve_unpack<true, false><<<ub, 256, 0, st>>>(ctx->G, I, N, S.total, d_xq, d_pose, ctx->srec, d_xc, d_conv, d_Jinv, d_iters);
+    else if (nocand)
+        k_solve_unpack<false, true><<<ub, 256, 0, st>>>(ctx->G, I, N, S.total, d_xq, d_pose, ctx->srec, d_xc, d_conv, d_Jinv, d_iters);
     else
-        k_solve_unpack<false><<<grid1d(S.total, 256), 256, 0, st>>>(N, S.total, ctx->srec, d_xc, d_conv, d_Jinv, d_iters);
+        k_solve_unpack<false, false><<<ub, 256, 0, st>>>(ctx->G, I, N, S.total, d_xq, d_pose, ctx->srec, d_xc, d_conv, d_Jinv, d_iters);
     return launch_status(ctx, "fs_solve");
 }
 

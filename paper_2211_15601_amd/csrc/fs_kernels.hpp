@@ -392,6 +392,8 @@ struct SolveP {
     int refill_min;      // refill when at least this many SIMD lanes are idle
     int max_iters;
     float tol2, div2;
+    int K;
+    int point_major;     // order in which pairs are handed out
 };
 
 // What the fused variant needs to compute initial states itself (same arithmetic as k_init_*).
@@ -419,16 +421,53 @@ __device__ __forceinline__ void write_record(float4 *__restrict__ rec, long long
     }
 }
 
-// records -> caller's layout: one thread per pair q = k*N + n, consecutive threads consecutive n
-template <bool WITH_J>
-__global__ __launch_bounds__(256) void k_solve_unpack(long long N, long long total, const float4 *__restrict__ rec,
-                                                      float *__restrict__ o_x, uint8_t *__restrict__ o_conv,
-                                                      float *__restrict__ o_J, uint8_t *__restrict__ o_it)
+// Voxel-based initial states leave most lanes without a candidate (a ray sample in empty space has
+// none).  Pre-pass for the fused solve: candidates per point, prefix sum, then the list of pairs
+// that do have one, so that the solve kernel draws only those.
+__global__ __launch_bounds__(256) void k_voxel_count(GridP G, InitP I, long long N, const float *__restrict__ xq,
+                                                     const int32_t *__restrict__ pose, int *__restrict__ cnt)
+{
+    const long long n = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= N) return;
+    const int p = pose_of(pose, n, G.P);
+    const float xp[3] = {xq[n], xq[N + n], xq[2 * N + n]};
+    const int32_t *c = I.cand + ((long long)p * I.C.ncell + cell_index(I.C, I.bbox + p * 6, xp)) * I.C.ck;
+    int m = 0;
+    for (int k = 0; k < I.C.ck; ++k) m += c[k] >= 0 ? 1 : 0;     // candidates are packed at the front
+    cnt[n] = m;
+}
+
+__global__ __launch_bounds__(256) void k_voxel_expand(long long N, int K, const int *__restrict__ offs,
+                                                      int *__restrict__ list)
+{
+    const long long n = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= N) return;
+    const int b = offs[n], e = offs[n + 1];
+    for (int j = b; j < e; ++j) list[j] = (int)(n * K + (j - b));
+}
+
+// records -> caller's layout: one thread per pair q = k*N + n, consecutive threads consecutive n.
+// NOCAND: the solve ran with fused voxel-based initial states and wrote no record for lanes whose
+// cell holds no k-th candidate; those get the answer of an invalid lane (x0 = 0, J~ = 0, not converged).
+template <bool WITH_J, bool NOCAND>
+__global__ __launch_bounds__(256) void k_solve_unpack(GridP G, InitP I, long long N, long long total,
+                                                      const float *__restrict__ xq, const int32_t *__restrict__ pose,
+                                                      const float4 *__restrict__ rec, float *__restrict__ o_x,
+                                                      uint8_t *__restrict__ o_conv, float *__restrict__ o_J,
+                                                      uint8_t *__restrict__ o_it)
 {
     const long long pq = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (pq >= total) return;
     const long long k = pq / N, n = pq - k * N;
-    const float4 a = WITH_J ? rec[pq * 4] : rec[pq];
+    bool have = true;
+    if (NOCAND) {
+        const int p = pose_of(pose, n, G.P);
+        const float xp[3] = {xq[n], xq[N + n], xq[2 * N + n]};
+        const int cidx = cell_index(I.C, I.bbox + p * 6, xp);
+        have = I.cand[((long long)p * I.C.ncell + cidx) * I.C.ck + k] >= 0;
+    }
+    float4 a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    if (have) a = WITH_J ? rec[pq * 4] : rec[pq];
     o_x[(k * 3 + 0) * N + n] = a.x;
     o_x[(k * 3 + 1) * N + n] = a.y;
     o_x[(k * 3 + 2) * N + n] = a.z;
@@ -436,8 +475,11 @@ __global__ __launch_bounds__(256) void k_solve_unpack(long long N, long long tot
     o_conv[pq] = (uint8_t)(flags & 1);
     if (o_it) o_it[pq] = (uint8_t)(flags >> 8);
     if (WITH_J) {
-        const float4 b = rec[pq * 4 + 1], c = rec[pq * 4 + 2], d = rec[pq * 4 + 3];
-        const float J[9] = {b.x, b.y, b.z, b.w, c.x, c.y, c.z, c.w, d.x};
+        float J[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+        if (have) {
+            const float4 b = rec[pq * 4 + 1], c = rec[pq * 4 + 2], d = rec[pq * 4 + 3];
+            J[0] = b.x; J[1] = b.y; J[2] = b.z; J[3] = b.w; J[4] = c.x; J[5] = c.y; J[6] = c.z; J[7] = c.w; J[8] = d.x;
+        }
 #pragma unroll
         for (int e = 0; e < 9; ++e) o_J[(k * 9 + e) * N + n] = J[e];
     }
@@ -463,8 +505,11 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const
                                                const float *__restrict__ xq, const int32_t *__restrict__ pose,
                                                const float *__restrict__ x0, const float *__restrict__ J0,
                                                const uint8_t *__restrict__ valid0, float4 *__restrict__ rec,
-                                               unsigned *__restrict__ cursor)
+                                               unsigned *__restrict__ cursor, const int *__restrict__ list,
+                                               const int *__restrict__ list_len)
 {
+    // with a list only the pairs list[0 .. *list_len) (encoded n*K + k) are solved
+    const long long total = list ? (long long)*list_len : S.total;
     const int lane = threadIdx.x & 63;
     long long next = 0, c1 = 0;      // wave-uniform: the wave's current chunk is [next, c1)
     bool exhausted = false;          // wave-uniform: the global cursor has run past the end
@@ -489,24 +534,33 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const
                 unsigned b = 0;
                 if (lane == 0) b = atomicAdd(cursor, (unsigned)S.chunk);
                 b = (unsigned)__shfl((int)b, 0);
-                if ((long long)b >= S.total) {
+                if ((long long)b >= total) {
                     exhausted = true;
                 } else {
                     next = b;
-                    c1 = min(S.total, (long long)b + S.chunk);
+                    c1 = min(total, (long long)b + S.chunk);
                 }
             }
             if (!exhausted) {
                 const int rank = __popcll(idle & ((1ull << lane) - 1ull));
                 const long long pq = next + rank;
                 if (!active && pq < c1) {
-                    k = (int)(pq / N);
-                    n = pq - (long long)k * N;
+                    if (list) {
+                        const long long e = list[pq];
+                        n = e / S.K;
+                        k = (int)(e - n * S.K);
+                    } else if (S.point_major) {   // consecutive SIMD lanes: the K initial states of one point
+                        n = pq / S.K;
+                        k = (int)(pq - n * S.K);
+                    } else {                      // consecutive SIMD lanes: consecutive points, same initial state
+                        k = (int)(pq / N);
+                        n = pq - (long long)k * N;
+                    }
                     const int p = pose_of(pose, n, G.P);
                     Tp = T + (long long)p * G.V * 12;
                     it = 0;
                     held = -1;
-                    bool ok;
+                    bool ok, norec = false;     // norec: no record needed, k_solve_unpack knows the answer
 #pragma unroll
                     for (int r = 0; r < 3; ++r) xp[r] = xq[r * N + n];
                     if (FUSED) {
@@ -527,6 +581,7 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const
                             const int cidx = cell_index(I.C, I.bbox + p * 6, xp);
                             const int v = I.cand[((long long)p * I.C.ncell + cidx) * I.C.ck + k];
                             ok = v >= 0;
+                            norec = !ok;
                             if (ok) node_pos(G, v, xt);
                         }
                         if (ok) {
@@ -552,7 +607,7 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const
                     if (ok) {
                         active = true;
                         fresh = true;
-                    } else {
+                    } else if (!norec) {
                         write_record<WITH_J>(rec, (long long)k * N + n, xt, J, 0);
                     }
                 }
