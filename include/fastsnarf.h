@@ -88,8 +88,10 @@ fs_status fs_set_params(fs_ctx *ctx, const fs_params *params);
  * (1..64), blocks_per_cu = resident 256-thread blocks per compute unit (capped by what the occupancy
  * query reports); for these a value of 0 keeps the current setting.  point_major = 1: consecutive SIMD
  * lanes take the K initial states of one point, 0: consecutive points with the same initial state,
- * -1: keep. */
-fs_status fs_set_tuning(fs_ctx *ctx, int32_t chunk, int32_t refill_min, int32_t blocks_per_cu, int32_t point_major);
+ * -1: keep.  lds_grid = 1: transform grids of at most 64 KiB (all poses) are copied into LDS by every
+ * block of the solve and read from there, 0: always read through the caches, -1: keep. */
+fs_status fs_set_tuning(fs_ctx *ctx, int32_t chunk, int32_t refill_min, int32_t blocks_per_cu, int32_t point_major,
+                        int32_t lds_grid);
 
 /* Pre-compute linear blend skinning on the grid nodes, Eq. (13) / Sec. 3.1 "Pre-computing
  * LBS": T[p][v] = sum_b W[v][b] * B[p][b], bones accumulated in index order with fused

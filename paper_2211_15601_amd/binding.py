@@ -69,7 +69,7 @@ def load():
     L.fs_last_error.restype = ctypes.c_char_p
     L.fs_version.argtypes = []
     L.fs_version.restype = ctypes.c_char_p
-    L.fs_set_tuning.argtypes = [vp, i32, i32, i32, i32]
+    L.fs_set_tuning.argtypes = [vp, i32, i32, i32, i32, i32]
     L.fs_microbench.argtypes = [i32, i64, ctypes.POINTER(ctypes.c_double)]
     L.fs_set_timing.argtypes = [vp, i32]
     L.fs_get_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
@@ -139,9 +139,9 @@ class Context:
         if grad_mode is not None: p.grad_mode = int(grad_mode)
         return self._ret(self._L.fs_set_params(self._h, ctypes.byref(p)), check)
 
-    def set_tuning(self, chunk=0, refill_min=0, blocks_per_cu=0, point_major=-1, check=True):
+    def set_tuning(self, chunk=0, refill_min=0, blocks_per_cu=0, point_major=-1, lds_grid=-1, check=True):
         return self._ret(self._L.fs_set_tuning(self._h, int(chunk), int(refill_min), int(blocks_per_cu),
-                                               int(point_major)), check)
+                                               int(point_major), int(lds_grid)), check)
 
     def precompute(self, W, B, check=True):
         return self._ret(self._L.fs_precompute(self._h, _ptr(W), _ptr(B)), check)

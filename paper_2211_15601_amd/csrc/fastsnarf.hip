@@ -53,7 +53,7 @@ struct fs_ctx {
     int *vlist;        // [K*N] pairs that have a candidate
     size_t vcap;       // points voffs / vlist can hold
     int scan_cap;      // tiles scan_sums can hold
-    int n_cus, occ_blocks_per_cu, chunk, refill_min, blocks_per_cu, point_major;
+    int n_cus, occ_blocks_per_cu, chunk, refill_min, blocks_per_cu, point_major, lds_grid;
     // optional timing of the Broyden kernel alone (events on the context's stream)
     bool timing;
     std::vector<std::pair<hipEvent_t, hipEvent_t>> *timed;
@@ -154,6 +154,8 @@ fs_status scan_exclusive(fs_ctx *c, int n, int *a)
     return FS_OK;
 }
 
+constexpr size_t FS_LDS_GRID_MAX = 64 * 1024;   // largest transform grid (all poses) kept in LDS by the solve
+
 int lanes_K(const fs_ctx *c) { return c->prm.init_mode == FS_INIT_BONE ? c->desc.n_bones : c->prm.corr_k; }
 
 }  // namespace
@@ -215,9 +217,10 @@ fs_status fs_create(const fs_grid_desc *desc, const fs_params *params, void *hip
               dev_alloc(&c->Bok, P * nb) && dev_alloc(&c->cursor, 4);
     {
         int per_cu = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_solve<true, true>, 256, 0) != hipSuccess || per_cu < 1) per_cu = 2;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_solve<true, true, false>, 256, 0) != hipSuccess || per_cu < 1) per_cu = 2;
         c->blocks_per_cu = 2;
-        c->point_major = 1;   /* the kernel is bound by the vector-memory path: more waves only thrash the L1 */
+        c->point_major = 1;
+        c->lds_grid = 1;   /* the kernel is bound by the vector-memory path: more waves only thrash the L1 */
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
         (void)hipGetLastError();
         c->n_cus = cus;
@@ -271,16 +274,17 @@ fs_status fs_set_params(fs_ctx *ctx, const fs_params *params)
     return FS_OK;
 }
 
-fs_status fs_set_tuning(fs_ctx *ctx, int32_t chunk, int32_t refill_min, int32_t blocks_per_cu, int32_t point_major)
+fs_status fs_set_tuning(fs_ctx *ctx, int32_t chunk, int32_t refill_min, int32_t blocks_per_cu, int32_t point_major, int32_t lds_grid)
 {
     if (!ctx) return FS_E_ARG;
     if ((chunk != 0 && (chunk < 64 || chunk > 65536)) || (refill_min != 0 && (refill_min < 1 || refill_min > 64)) ||
-        blocks_per_cu < 0 || blocks_per_cu > 32 || point_major < -1 || point_major > 1)
+        blocks_per_cu < 0 || blocks_per_cu > 32 || point_major < -1 || point_major > 1 || lds_grid < -1 || lds_grid > 1)
         return fail(ctx, FS_E_ARG, "fs_set_tuning: value out of range");
     if (chunk) ctx->chunk = chunk;
     if (refill_min) ctx->refill_min = refill_min;
     if (blocks_per_cu) ctx->blocks_per_cu = blocks_per_cu;
     if (point_major >= 0) ctx->point_major = point_major;
+    if (lds_grid >= 0) ctx->lds_grid = lds_grid;
     return FS_OK;
 }
 
@@ -373,7 +377,12 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     S.refill_min = ctx->refill_min;
     const long long chunks = (S.total + S.chunk - 1) / S.chunk;
     const int wpb = 4;
-    const int per_cu = std::max(1, std::min(ctx->blocks_per_cu, ctx->occ_blocks_per_cu));
+    const size_t grid_bytes = (size_t)ctx->G.P * ctx->G.V * 48;
+    const bool lds = ctx->lds_grid && grid_bytes <= FS_LDS_GRID_MAX;
+    // reading through the caches the kernel is bound by the vector-memory path and more waves only thrash
+    // the L1; with the grid in LDS it is latency / ALU bound and wants every wave the registers allow
+    const int want_blocks = lds ? std::max(ctx->blocks_per_cu, 3) : ctx->blocks_per_cu;
+    const int per_cu = std::max(1, std::min(want_blocks, ctx->occ_blocks_per_cu));
     const int blocks = (int)std::min<long long>(grid1d(chunks, wpb), (long long)per_cu * ctx->n_cus);
     InitP I;
     I.mode = ctx->prm.init_mode;
@@ -415,14 +424,22 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     const dim3 grd(blocks), blk(wpb * WAVE);
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     if (ctx->timing && hipEventCreate(&ev0) == hipSuccess && hipEventCreate(&ev1) == hipSuccess) (void)hipEventRecord(ev0, st);
-    if (fused && with_J)
-        k_solve<true, true><<<grd, blk, 0, st>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, nullptr, nullptr, nullptr, ctx->srec, ctx->cursor, list, list_len);
-    else if (fused)
-        k_solve<true, false><<<grd, blk, 0, st>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, nullptr, nullptr, nullptr, ctx->srec, ctx->cursor, list, list_len);
-    else if (with_J)
-        k_solve<false, true><<<grd, blk, 0, st>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, d_x0, d_Jinv0, d_valid0, ctx->srec, ctx->cursor, list, list_len);
-    else
-        k_solve<false, false><<<grd, blk, 0, st>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, d_x0, d_Jinv0, d_valid0, ctx->srec, ctx->cursor, list, list_len);
+    const size_t shm = lds ? grid_bytes : 0;
+#define FS_LAUNCH_SOLVE(F, J, L)                                                                                      \
+    k_solve<F, J, L><<<grd, blk, shm, st>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, d_x0, d_Jinv0, d_valid0, ctx->srec, \
+                                            ctx->cursor, list, list_len)
+    if (lds) {
+        if (fused && with_J) FS_LAUNCH_SOLVE(true, true, true);
+        else if (fused) FS_LAUNCH_SOLVE(true, false, true);
+        else if (with_J) FS_LAUNCH_SOLVE(false, true, true);
+        else FS_LAUNCH_SOLVE(false, false, true);
+    } else {
+        if (fused && with_J) FS_LAUNCH_SOLVE(true, true, false);
+        else if (fused) FS_LAUNCH_SOLVE(true, false, false);
+        else if (with_J) FS_LAUNCH_SOLVE(false, true, false);
+        else FS_LAUNCH_SOLVE(false, false, false);
+    }
+#undef FS_LAUNCH_SOLVE
     if (ev0 && ev1) {
         (void)hipEventRecord(ev1, st);
         ctx->timed->emplace_back(ev0, ev1);

@@ -27,16 +27,34 @@ __global__ __launch_bounds__(256) void k_precompute(GridP G, const float *__rest
     const long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (v >= G.V) return;
     const float *w = W + v * G.nb;
+    const bool vec = (G.nb & 3) == 0;        // weight rows are 16-byte aligned: read them four at a time
     for (int p = 0; p < G.P; ++p) {
         const float *Bp = B + (long long)p * G.nb * 12;
         float acc[12];
-        const float w0 = w[0];
+        if (vec) {
+            for (int b0 = 0; b0 < G.nb; b0 += 4) {
+                const float4 w4 = *reinterpret_cast<const float4 *>(w + b0);
+                const float wv[4] = {w4.x, w4.y, w4.z, w4.w};
 #pragma unroll
-        for (int e = 0; e < 12; ++e) acc[e] = w0 * Bp[e];
-        for (int b = 1; b < G.nb; ++b) {
-            const float wb = w[b];
+                for (int j = 0; j < 4; ++j) {
+                    if (b0 == 0 && j == 0) {
 #pragma unroll
-            for (int e = 0; e < 12; ++e) acc[e] = FS_FMA(wb, Bp[b * 12 + e], acc[e]);
+                        for (int e = 0; e < 12; ++e) acc[e] = wv[0] * Bp[e];
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 12; ++e) acc[e] = FS_FMA(wv[j], Bp[(b0 + j) * 12 + e], acc[e]);
+                    }
+                }
+            }
+        } else {
+            const float w0 = w[0];
+#pragma unroll
+            for (int e = 0; e < 12; ++e) acc[e] = w0 * Bp[e];
+            for (int b = 1; b < G.nb; ++b) {
+                const float wb = w[b];
+#pragma unroll
+                for (int e = 0; e < 12; ++e) acc[e] = FS_FMA(wb, Bp[b * 12 + e], acc[e]);
+            }
         }
         float4 *o = reinterpret_cast<float4 *>(T + ((long long)p * G.V + v) * 12);
         o[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
@@ -500,14 +518,26 @@ __global__ void k_reset_cursor(unsigned *__restrict__ cursor)
 // 4 bytes each); k_solve_unpack then moves the records into that layout with coalesced stores.
 // Record: WITH_J ? 16 floats {x*[3], flags, J~[9], pad[3]} : 4 floats {x*[3], flags};
 // flags = conv | iters << 8 (as an integer bit pattern).
-template <bool FUSED, bool WITH_J>
-__global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const float *__restrict__ T,
+// LDSGRID: the whole transform grid (all poses) fits in LDS; every block copies it there first and all
+// corner records are then read from LDS, where per-lane addresses cost far less than in the vector
+// memory path.
+template <bool FUSED, bool WITH_J, bool LDSGRID>
+__global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const float *__restrict__ Tglobal,
                                                const float *__restrict__ xq, const int32_t *__restrict__ pose,
                                                const float *__restrict__ x0, const float *__restrict__ J0,
                                                const uint8_t *__restrict__ valid0, float4 *__restrict__ rec,
                                                unsigned *__restrict__ cursor, const int *__restrict__ list,
                                                const int *__restrict__ list_len)
 {
+    extern __shared__ float4 s_grid[];
+    const float *T = Tglobal;
+    if (LDSGRID) {
+        const int n4 = (int)((long long)G.P * G.V * 3);      // float4 per record: 3
+        const float4 *src = reinterpret_cast<const float4 *>(Tglobal);
+        for (int i = threadIdx.x; i < n4; i += blockDim.x) s_grid[i] = src[i];
+        __syncthreads();
+        T = reinterpret_cast<const float *>(s_grid);
+    }
     // with a list only the pairs list[0 .. *list_len) (encoded n*K + k) are solved
     const long long total = list ? (long long)*list_len : S.total;
     const int lane = threadIdx.x & 63;
