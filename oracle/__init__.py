@@ -180,6 +180,19 @@ def grad(dims, lo, hi, T, W, B, xc, Jinv, conv, gxc, pose=None, mode=0, prec="f6
     return (gW, gB, gxq, GT) if want_GT else (gW, gB, gxq)
 
 
+def dedupe(xc, conv, min_dist, prec="f32"):
+    """Sec. 3.1 "Remove Duplicate Correspondences": greedy in lane order.  Returns keep [K,N], count [N]."""
+    dt = _dt(prec)
+    xc = _c(xc, dt)
+    conv = _c(conv, np.uint8)
+    K, _, N = xc.shape
+    keep = np.empty((K, N), dtype=np.uint8)
+    count = np.empty(N, dtype=np.int32)
+    _fn("orc_dedupe", prec)(_p(xc), _p(conv), ctypes.c_int64(N), ctypes.c_int32(K),
+                            ctypes.c_double(float(np.float32(min_dist))), _p(keep), _p(count))
+    return keep, count
+
+
 def brute_roots(dims, lo, hi, T, xq, starts_per_axis=8, merge_tol=1e-6, max_roots=16):
     """Exhaustive in-box root list per query (float64 checker).  T is one pose [V,12]."""
     T = _c(T, np.float64).reshape(-1, 12)

@@ -24,6 +24,7 @@
  *                      "Approximated Gradient", Eq. (15) (Broyden's last J~)
  *   orc_corr_build / orc_init_voxel -- the voxel-based initialisation; the paper
  *                      does not define it, the rule is this project's own.
+ *   orc_dedupe      -- Sec. 3.1 "Remove Duplicate Correspondences" (greedy rule of this project)
  *   orc_brute_roots -- exhaustive dense search + Newton polish, a checker only.
  *
  * Parity pins: every function here is pinned by tests/test_oracle_*.py (closed forms,
@@ -541,6 +542,38 @@ void NAME(orc_init_voxel)(const int32_t *dims, const double *box, const real *T,
             for (int e = 0; e < 9; ++e) Jinv0[((int64_t)k * 9 + e) * N + i] = Ji[e];
             valid0[(int64_t)k * N + i] = (uint8_t)ok;
         }
+    }
+}
+
+/* ---- Duplicate removal (Sec. 3.1 "Remove Duplicate Correspondences") ----
+ * Different initial states often reach the same root.  The paper detects duplicates "by their
+ * relative distances in canonical space" without giving the rule; here: per point the lanes are
+ * visited in increasing k, and a converged lane is kept iff no lane kept before it lies closer than
+ * min_dist (Euclidean, strict <).  keep [K][N] 0/1, count [N]. */
+void NAME(orc_dedupe)(const real *xc, const uint8_t *conv, int64_t N, int32_t K, double min_dist,
+                      uint8_t *keep, int32_t *count)
+{
+    const real md = (real)min_dist, md2 = md * md;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < N; ++i) {
+        int c = 0;
+        for (int k = 0; k < K; ++k) {
+            int kp = 0;
+            if (conv[(int64_t)k * N + i]) {
+                kp = 1;
+                for (int j = 0; j < k && kp; ++j) {
+                    if (!keep[(int64_t)j * N + i]) continue;
+                    real e0 = xc[((int64_t)k * 3 + 0) * N + i] - xc[((int64_t)j * 3 + 0) * N + i];
+                    real e1 = xc[((int64_t)k * 3 + 1) * N + i] - xc[((int64_t)j * 3 + 1) * N + i];
+                    real e2 = xc[((int64_t)k * 3 + 2) * N + i] - xc[((int64_t)j * 3 + 2) * N + i];
+                    real d2 = FMA(e2, e2, FMA(e1, e1, e0 * e0));
+                    if (d2 < md2) kp = 0;
+                }
+            }
+            keep[(int64_t)k * N + i] = (uint8_t)kp;
+            c += kp;
+        }
+        count[i] = c;
     }
 }
 
