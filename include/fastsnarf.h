@@ -138,6 +138,19 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
                   const uint8_t *d_conv, const float *d_gxc, const int32_t *d_pose, int64_t N, int32_t K,
                   float *d_gW, float *d_gB, float *d_gxq);
 
+/* Duplicate removal, Sec. 3.1 "Remove Duplicate Correspondences": different initial states often reach
+ * the same root, and the canonical field should be queried once per distinct root.  The paper detects
+ * duplicates by distance in canonical space without stating the rule; here, per point, lanes are
+ * visited in increasing k and a converged lane is kept iff no lane kept before it lies closer than
+ * min_dist (Euclidean, strict <).
+ *   in : d_xc [K][3][N], d_conv [K][N]
+ *   out: d_keep [K][N] 0/1; d_offsets [N+1]: point n owns packed entries offsets[n] .. offsets[n+1],
+ *        offsets[N] = number of kept roots; d_roots [cap][3] and d_lane [cap] (either may be NULL): the
+ *        kept roots and their lane index k in that order.  Entries beyond cap are not written, so the
+ *        caller compares offsets[N] with cap.  K <= 64.  N == 0 writes offsets[0] = 0. */
+fs_status fs_dedupe(fs_ctx *ctx, const float *d_xc, const uint8_t *d_conv, int64_t N, int32_t K, float min_dist,
+                    uint8_t *d_keep, int32_t *d_offsets, float *d_roots, int32_t *d_lane, int64_t cap);
+
 /* Timing of the Broyden kernel alone (k_solve, without the unpacking of its results): while enabled,
  * every fs_solve brackets that kernel with two HIP events on the context's stream.  fs_get_timing
  * synchronises the stream, returns the summed elapsed milliseconds and the number of launches since

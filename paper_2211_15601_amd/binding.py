@@ -21,7 +21,8 @@ FS_INIT_BONE, FS_INIT_VOXEL = 0, 1
 FS_GRAD_BROYDEN_J, FS_GRAD_EXACT_J = 0, 1
 
 EXPORTS = ["fs_create", "fs_destroy", "fs_set_params", "fs_set_tuning", "fs_precompute", "fs_init", "fs_solve", "fs_grad",
-           "fs_get_transforms", "fs_get_corr", "fs_microbench", "fs_set_timing", "fs_get_timing", "fs_last_error", "fs_version"]
+           "fs_dedupe", "fs_get_transforms", "fs_get_corr", "fs_microbench", "fs_set_timing", "fs_get_timing", "fs_last_error",
+           "fs_version"]
 
 
 class GridDesc(ctypes.Structure):
@@ -73,7 +74,8 @@ def load():
     L.fs_microbench.argtypes = [i32, i64, ctypes.POINTER(ctypes.c_double)]
     L.fs_set_timing.argtypes = [vp, i32]
     L.fs_get_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
-    for name in EXPORTS[:13]:
+    L.fs_dedupe.argtypes = [vp, vp, vp, i64, i32, ctypes.c_float, vp, vp, vp, vp, i64]
+    for name in EXPORTS[:14]:
         getattr(L, name).restype = ctypes.c_int
     _lib = L
     return L
@@ -156,6 +158,10 @@ class Context:
     def grad(self, W, xc, Jinv, conv, gxc, pose, N, K, gW, gB, gxq=None, check=True):
         return self._ret(self._L.fs_grad(self._h, _ptr(W), _ptr(xc), _ptr(Jinv), _ptr(conv), _ptr(gxc), _ptr(pose),
                                          N, K, _ptr(gW), _ptr(gB), _ptr(gxq)), check)
+
+    def dedupe(self, xc, conv, N, K, min_dist, keep, offsets, roots=None, lane=None, cap=0, check=True):
+        return self._ret(self._L.fs_dedupe(self._h, _ptr(xc), _ptr(conv), N, K, float(min_dist), _ptr(keep),
+                                           _ptr(offsets), _ptr(roots), _ptr(lane), cap), check)
 
     def set_timing(self, enable=True, check=True):
         return self._ret(self._L.fs_set_timing(self._h, int(bool(enable))), check)

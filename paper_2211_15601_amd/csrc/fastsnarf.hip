@@ -140,6 +140,10 @@ void free_all(fs_ctx *c)
 // exclusive scan of a[0..n) in place on the context's stream, a[n] = total
 fs_status scan_exclusive(fs_ctx *c, int n, int *a)
 {
+    if (n <= 0) {
+        k_fill_zero_i32<<<1, 64, 0, c->stream>>>(1, a);
+        return FS_OK;
+    }
     const int m = (n + SCAN_TILE - 1) / SCAN_TILE;
     if (m + 1 > c->scan_cap) {
         (void)hipStreamSynchronize(c->stream);
@@ -515,6 +519,30 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
     k_grad_bones_partial<<<dim3(ctx->gb_blocks, G.P), 256, sizeof(float) * GB_TILE * (G.nb + 12), st>>>(G, d_W, ctx->GT, ctx->gpart);
     k_grad_bones_final<<<G.P * nout, 64, 0, st>>>(G.P, ctx->gb_blocks, nout, ctx->gpart, d_gB);
     return launch_status(ctx, "fs_grad");
+}
+
+fs_status fs_dedupe(fs_ctx *ctx, const float *d_xc, const uint8_t *d_conv, int64_t N, int32_t K, float min_dist,
+                    uint8_t *d_keep, int32_t *d_offsets, float *d_roots, int32_t *d_lane, int64_t cap)
+{
+    if (!ctx) return FS_E_ARG;
+    if (K < 1 || K > FS_MAX_BONES) return fail(ctx, FS_E_SHAPE, "fs_dedupe: K must be in 1..%d", (int)FS_MAX_BONES);
+    if (N < 0 || (long long)N * K >= (1ll << 31)) return fail(ctx, FS_E_SHAPE, "fs_dedupe: need 0 <= N and K*N < 2^31");
+    if (!(min_dist >= 0.0f) || !std::isfinite(min_dist)) return fail(ctx, FS_E_ARG, "fs_dedupe: min_dist must be finite and >= 0");
+    if (cap < 0) return fail(ctx, FS_E_SHAPE, "fs_dedupe: cap must be >= 0");
+    FS_CHECK_PTR(ctx, d_offsets, false);
+    FS_CHECK_PTR(ctx, d_roots, true);
+    FS_CHECK_PTR(ctx, d_lane, true);
+    hipStream_t st = ctx->stream;
+    if (N > 0) {
+        FS_CHECK_PTR(ctx, d_xc, false);
+        FS_CHECK_PTR(ctx, d_conv, false);
+        FS_CHECK_PTR(ctx, d_keep, false);
+        k_dedupe<<<grid1d(N, 256), 256, 0, st>>>(N, K, min_dist * min_dist, d_xc, d_conv, d_keep, d_offsets);
+    }
+    { fs_status ss = scan_exclusive(ctx, (int)N, d_offsets); if (ss != FS_OK) return ss; }
+    if (N > 0 && (d_roots || d_lane))
+        k_pack_roots<<<grid1d(N, 256), 256, 0, st>>>(N, K, cap, d_xc, d_keep, d_offsets, d_roots, d_lane);
+    return launch_status(ctx, "fs_dedupe");
 }
 
 fs_status fs_set_timing(fs_ctx *ctx, int32_t enable)

@@ -1009,4 +1009,59 @@ __global__ __launch_bounds__(64) void k_grad_bones_final(int P, int nblk, int no
     if (threadIdx.x == 0) gB[i] = a;
 }
 
+// ------------------------------------------------------------------------------------------------
+// Duplicate removal (Sec. 3.1 "Remove Duplicate Correspondences") and packing of the surviving roots.
+// One thread per point; lanes in increasing k; a converged lane is kept iff no lane kept before it is
+// closer than min_dist.  The kept set lives in a 64-bit mask; kept roots are re-read when needed.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_dedupe(long long N, int K, float md2, const float *__restrict__ xc,
+                                                const uint8_t *__restrict__ conv, uint8_t *__restrict__ keep,
+                                                int *__restrict__ count)
+{
+    const long long n = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= N) return;
+    unsigned long long kept = 0ull;
+    for (int k = 0; k < K; ++k) {
+        bool kp = conv[(long long)k * N + n] != 0;
+        if (kp) {
+            const float x0 = xc[((long long)k * 3 + 0) * N + n], x1 = xc[((long long)k * 3 + 1) * N + n],
+                        x2 = xc[((long long)k * 3 + 2) * N + n];
+            unsigned long long m = kept;
+            while (m && kp) {
+                const int j = __builtin_ctzll(m);
+                m &= m - 1ull;
+                const float e0 = x0 - xc[((long long)j * 3 + 0) * N + n], e1 = x1 - xc[((long long)j * 3 + 1) * N + n],
+                            e2 = x2 - xc[((long long)j * 3 + 2) * N + n];
+                const float d2 = FS_FMA(e2, e2, FS_FMA(e1, e1, e0 * e0));
+                if (d2 < md2) kp = false;
+            }
+        }
+        if (kp) kept |= 1ull << k;
+        keep[(long long)k * N + n] = kp ? 1 : 0;
+    }
+    count[n] = __popcll(kept);
+}
+
+// packed list: roots [total][3] and lane index k, point n owns entries offsets[n] .. offsets[n+1]
+__global__ __launch_bounds__(256) void k_pack_roots(long long N, int K, long long cap, const float *__restrict__ xc,
+                                                    const uint8_t *__restrict__ keep, const int *__restrict__ offsets,
+                                                    float *__restrict__ roots, int32_t *__restrict__ lane)
+{
+    const long long n = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= N) return;
+    long long o = offsets[n];
+    for (int k = 0; k < K; ++k) {
+        if (!keep[(long long)k * N + n]) continue;
+        if (o < cap) {
+            if (roots) {
+                roots[o * 3 + 0] = xc[((long long)k * 3 + 0) * N + n];
+                roots[o * 3 + 1] = xc[((long long)k * 3 + 1) * N + n];
+                roots[o * 3 + 2] = xc[((long long)k * 3 + 2) * N + n];
+            }
+            if (lane) lane[o] = k;
+        }
+        ++o;
+    }
+}
+
 }  // namespace fs

@@ -102,6 +102,47 @@ def test_grad_parity(lib, case, mode):
     assert np.linalg.norm(gB2.astype(np.float64) - rB) / np.linalg.norm(rB) < 2e-5
 
 
+@pytest.mark.parametrize("case", [(2, 5003, (32, 32, 8), None), (3, 16 * 250, (32, 32, 8), None), (1, 4096, None, None)], ids=_ids)
+def test_dedupe_parity(lib, case):
+    # Sec. 3.1 "Remove Duplicate Correspondences": keep mask, offsets, packed roots and lane ids, bit for bit
+    cfg, n, dims, P = case
+    w = wl.make_config(cfg, n_points=n, dims=dims, n_poses=P)
+    T_ref = oracle.precompute(w.dims, w.W, w.B, prec="f32")
+    x0, J0, v0 = gu.oracle_inits(w, T_ref)
+    xc, cv, Jo, it = gu.oracle_solve(w, T_ref, x0, J0, v0)
+    md = 1e-3
+    keep_ref, count_ref = oracle.dedupe(xc, cv, md, prec="f32")
+    run = gu.GpuRun(w)
+    N, K = w.N, w.K
+    total = int(count_ref.sum())
+    for cap in (N * K, max(total // 2, 1)):
+        keep = torch.full((K, N), 9, dtype=torch.uint8, device=gu.DEV)
+        offs = torch.full((N + 1,), -1, dtype=torch.int32, device=gu.DEV)
+        roots = torch.full((cap, 3), float("nan"), dtype=torch.float32, device=gu.DEV)
+        lane = torch.full((cap,), -1, dtype=torch.int32, device=gu.DEV)
+        run.ctx.dedupe(gu.dev(xc), gu.dev(cv), N, K, md, keep, offs, roots, lane, cap)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(keep.cpu().numpy(), keep_ref)
+        offs_h = offs.cpu().numpy()
+        np.testing.assert_array_equal(offs_h, np.concatenate([[0], np.cumsum(count_ref)]).astype(np.int32))
+        assert offs_h[-1] == total and 0 < total < cv.sum()
+        kk, nn = np.nonzero(keep_ref.T.astype(bool).T)              # reference packing: point-major, k increasing
+        order = np.lexsort((kk, nn))
+        ref_lane = kk[order][:cap]
+        ref_roots = xc[kk[order], :, nn[order]][:cap]
+        m = min(cap, total)
+        np.testing.assert_array_equal(lane.cpu().numpy()[:m], ref_lane[:m])
+        np.testing.assert_array_equal(roots.cpu().numpy()[:m].view(np.uint32), ref_roots[:m].view(np.uint32))
+        if cap > total:
+            assert (lane.cpu().numpy()[total:] == -1).all()        # nothing written past the end
+    # empty input
+    offs = torch.full((1,), -1, dtype=torch.int32, device=gu.DEV)
+    run.ctx.dedupe(None, None, 0, K, md, None, offs, None, None, 0)
+    torch.cuda.synchronize()
+    assert offs.item() == 0
+    assert run.ctx.dedupe(gu.dev(xc), gu.dev(cv), N, 65, md, keep, offs, None, None, 0, check=False) == binding.FS_E_SHAPE
+
+
 def test_one_hot_weights_closed_form_on_gpu(lib):
     # one-hot weights: root = B_k^{-1} x' for every lane, at most two steps
     s = wl.random_affine_scene(41, dims=(5, 4, 3), n_bones=4, n_points=333)
