@@ -37,6 +37,39 @@ PEAK_FP32_UNPACKED_TFLOPS = 78.6    # 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.
 SOLVE_TRAFFIC_BYTES = {2: 204.6e6}
 
 
+def resolution_sweep(torch, binding, wl, dev):
+    """Articulation time (fs_precompute + fs_solve, fused initial states, roots + masks only) against the
+    resolution of the weight grid, 200k points of the SMPL-scale scene."""
+    for dims in ((16, 16, 4), (32, 32, 8), (64, 64, 16), (128, 128, 32)):
+        w = wl.make_config(2, n_points=200000, dims=dims)
+        N, K = w.N, w.K
+        ctx = binding.Context(w.dims, w.n_bones, w.lo, w.hi, tol=w.tol, div_thresh=w.div_thresh, max_iters=w.max_iters)
+        up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+        W, B, xq = up(w.W), up(w.B), up(w.xq)
+        xc = torch.empty((K, 3, N), dtype=torch.float32, device=dev)
+        cv = torch.empty((K, N), dtype=torch.uint8, device=dev)
+        it = torch.empty((K, N), dtype=torch.uint8, device=dev)
+
+        def run():
+            ctx.precompute(W, B)
+            ctx.solve(xq, None, N, K, None, None, None, xc, cv, None, it)
+        for _ in range(3):
+            run()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 10
+        print(json.dumps({"sweep": "grid resolution", "grid": list(dims), "grid_bytes": dims[0] * dims[1] * dims[2] * 48,
+                          "points": N, "inits": K, "articulation_ms": ms, "points_per_s": N / (ms * 1e-3),
+                          "converged_pairs": int(cv.sum().item()),
+                          "lane_iterations": int(it.to(torch.int64).sum().item()) + N * K}))
+        ctx.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -48,6 +81,10 @@ def main():
     ap.add_argument("--probe-copy-mib", type=int, default=0,
                     help="after the timed region copy this many MiB device to device once (a kernel of known "
                          "traffic, for calibrating the FETCH_SIZE / WRITE_SIZE counters under rocprofv3)")
+    ap.add_argument("--resolution-sweep", action="store_true",
+                    help="instead of the benchmark: time fs_precompute + fs_solve for 200k posed points x 24 inits on "
+                         "weight grids of 16x16x4 .. 128x128x32 (the shape of the paper's grid-resolution ablation, "
+                         "Table 2) and print one JSON line per grid")
     ap.add_argument("--unfused", action="store_true",
                     help="materialise the initial states with fs_init instead of computing them inside fs_solve")
     args = ap.parse_args()
@@ -65,6 +102,10 @@ def main():
     binding.load()
     dev = "cuda:0"
     torch.cuda.set_device(0)
+
+    if args.resolution_sweep:
+        resolution_sweep(torch, binding, wl, dev)
+        return
 
     w = wl.make_config(args.config)
     N, K = w.N, w.K

@@ -143,6 +143,29 @@ def test_dedupe_parity(lib, case):
     assert run.ctx.dedupe(gu.dev(xc), gu.dev(cv), N, 65, md, keep, offs, None, None, 0, check=False) == binding.FS_E_SHAPE
 
 
+def test_autograd_hook_matches_oracle_gradient(lib):
+    # loss = sum over converged lanes of c . x*; its gradient through the autograd.Function equals the
+    # float64 oracle's implicit gradient (Broyden-J mode) on the strict-fp32 oracle's roots
+    from paper_2211_15601_amd.autograd import CorrespondenceSearch
+    w = wl.make_config(1, n_points=1500, dims=(16, 16, 4))
+    run = gu.GpuRun(w)
+    Wt = run.W.clone().requires_grad_(True)
+    Bt = run.B.clone().requires_grad_(True)
+    qt = run.xq.clone().requires_grad_(True)
+    xc, conv = CorrespondenceSearch.apply(run.ctx, Wt, Bt, qt, None)
+    c = gu.dev(w.upstream_grads())
+    loss = (xc * c * conv[:, None, :].float()).sum()
+    loss.backward()
+    T_ref = oracle.precompute(w.dims, w.W, w.B, prec="f32")
+    x0, J0, v0 = gu.oracle_inits(w, T_ref)
+    oxc, ocv, oJ, _ = gu.oracle_solve(w, T_ref, x0, J0, v0)
+    np.testing.assert_array_equal(conv.cpu().numpy(), ocv)
+    rW, rB, rq = oracle.grad(w.dims, w.lo, w.hi, T_ref, w.W, w.B, oxc, oJ, ocv, w.upstream_grads(), mode=0, prec="f64")
+    for a, b in ((Wt.grad, rW), (Bt.grad, rB), (qt.grad, rq)):
+        a = a.cpu().numpy().astype(np.float64)
+        assert np.linalg.norm(a - b) / np.linalg.norm(b) < 2e-5
+
+
 def test_one_hot_weights_closed_form_on_gpu(lib):
     # one-hot weights: root = B_k^{-1} x' for every lane, at most two steps
     s = wl.random_affine_scene(41, dims=(5, 4, 3), n_bones=4, n_points=333)
