@@ -21,7 +21,7 @@ SMALL = [
     (3, 16 * 255, (32, 32, 8), None),
     (5, 8 * 1003, (32, 32, 16), 8),
 ]
-FULL = [(1, None, None, None), (2, None, None, None), (3, None, None, None)]
+FULL = [(1, None, None, None), (2, None, None, None), (3, None, None, None), (4, None, None, None), (5, None, None, None)]
 
 
 def _ids(c):
@@ -76,8 +76,8 @@ def test_precompute_init_solve_parity(lib, case):
 
 
 @pytest.mark.parametrize("mode", [binding.FS_GRAD_BROYDEN_J, binding.FS_GRAD_EXACT_J])
-@pytest.mark.parametrize("case", [(1, 2048, None, None), (4, 16 * 256, (32, 32, 8), None), (5, 4 * 1000, (16, 16, 8), 4)],
-                         ids=_ids)
+@pytest.mark.parametrize("case", [(1, 2048, None, None), (4, 16 * 256, (32, 32, 8), None), (5, 4 * 1000, (16, 16, 8), 4),
+                                  (2, None, None, None), (4, None, None, None)], ids=_ids)
 def test_grad_parity(lib, case, mode):
     cfg, n, dims, P = case
     w = wl.make_config(cfg, n_points=n, dims=dims, n_poses=P)
@@ -90,12 +90,26 @@ def test_grad_parity(lib, case, mode):
     run = gu.GpuRun(w, grad_mode=mode)
     run.precompute()
     gW, gB, gxq = run.grad(xc, Jo, cv, gxc)
-    rW, rB, rq = oracle.grad(w.dims, w.lo, w.hi, T_ref, w.W, w.B, xc, Jo, cv, gxc, pose=pose, mode=mode, prec="f64")
+    # Reference: Broyden-J mode against the float64 oracle (lambda = -J~^T g is a plain 3x3 product, fp32
+    # rounding stays ~1e-7).  Exact-J mode inverts the analytic Jacobian in fp32; a few lanes have
+    # |det J| ~ 1e-4 and gradient entries ~1e4, so fp32 and float64 disagree by ~cond(J) 6e-8 on exactly
+    # the lanes that dominate the norm (the strict-fp32 oracle itself is 4e-3 from float64 on config 2).
+    # There the GPU is held to the strict-fp32 oracle, whose lambda it reproduces operation by
+    # operation (only the order of the sums differs), and its distance to float64 is reported.
+    ref_prec = "f64" if mode == binding.FS_GRAD_BROYDEN_J else "f32"
+    rW, rB, rq = oracle.grad(w.dims, w.lo, w.hi, T_ref, w.W, w.B, xc, Jo, cv, gxc, pose=pose, mode=mode, prec=ref_prec)
     for name, a, b in (("gW", gW, rW), ("gB", gB, rB), ("gxq", gxq, rq)):
         assert np.isfinite(a).all(), name
-        rel = np.linalg.norm(a.astype(np.float64) - b) / max(np.linalg.norm(b), 1e-30)
-        print(f"{w.name} mode {mode} {name}: relative L2 {rel:.2e}")
+        rel = np.linalg.norm(a.astype(np.float64) - b) / max(np.linalg.norm(b.astype(np.float64)), 1e-30)
+        print(f"{w.name} mode {mode} {name}: relative L2 vs {ref_prec} oracle {rel:.2e}")
         assert rel < 2e-5, (name, rel)
+    if mode == binding.FS_GRAD_EXACT_J:
+        r64 = oracle.grad(w.dims, w.lo, w.hi, T_ref, w.W, w.B, xc, Jo, cv, gxc, pose=pose, mode=mode, prec="f64")
+        for name, a, b in zip(("gW", "gB", "gxq"), (gW, gB, gxq), r64):
+            rel = np.linalg.norm(a.astype(np.float64) - b) / np.linalg.norm(b)
+            print(f"{w.name} mode {mode} {name}: relative L2 vs f64 oracle {rel:.2e} (conditioning of J, reported)")
+            assert rel < 5e-2
+    rW, rB = rW.astype(np.float64), rB.astype(np.float64)
     # a second call overwrites (does not accumulate into) its outputs
     gW2, gB2, gxq2 = run.grad(xc, Jo, cv, gxc)
     assert np.linalg.norm(gW2.astype(np.float64) - rW) / np.linalg.norm(rW) < 2e-5
