@@ -78,6 +78,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload configuration 1..5 (default 2: SMPL-scale)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-grad", action="store_true", help="leave fs_grad out of the step")
+    ap.add_argument("--no-slots", action="store_true",
+                    help="fs_grad counts lanes per cell itself instead of reusing fs_solve's counts")
     ap.add_argument("--probe-copy-mib", type=int, default=0,
                     help="after the timed region copy this many MiB device to device once (a kernel of known "
                          "traffic, for calibrating the FETCH_SIZE / WRITE_SIZE counters under rocprofv3)")
@@ -127,6 +129,7 @@ def main():
     gW = torch.empty(w.W.shape, dtype=f32, device=dev)
     gB = torch.empty(w.B.shape, dtype=f32, device=dev)
     gxq = torch.empty((3, N), dtype=f32, device=dev)
+    slot = None if args.no_slots else torch.empty((K, N), dtype=torch.int32, device=dev)
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
     marks = []
@@ -140,12 +143,12 @@ def main():
             ctx.init(xq, pose, N, x0, J0, v0)
         if record: e[2].record()
         if args.unfused:
-            ctx.solve(xq, pose, N, K, x0, J0, v0, xc, cv, Jo, it)
+            ctx.solve(xq, pose, N, K, x0, J0, v0, xc, cv, Jo, it, slot)
         else:
-            ctx.solve(xq, pose, N, K, None, None, None, xc, cv, Jo, it)
+            ctx.solve(xq, pose, N, K, None, None, None, xc, cv, Jo, it, slot)
         if record: e[3].record()
         if not args.no_grad:
-            ctx.grad(W, xc, Jo, cv, gxc, pose, N, K, gW, gB, gxq)
+            ctx.grad(W, xc, Jo, cv, gxc, pose, N, K, gW, gB, gxq, slot)
         if record: e[4].record()
         if record: marks.append(e)
 

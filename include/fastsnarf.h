@@ -121,22 +121,31 @@ fs_status fs_init(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_t
  *   d_x0, d_Jinv0, d_valid0 all NULL: the kernel computes the initial states of the context's
  *   init_mode itself (same arithmetic as fs_init, bit-identical results) and fs_init is not needed.
  *   out: d_xc [K][3][N] last iterate; d_conv [K][N] 1 = converged; d_Jinv [K][9][N] last J~ (may be
- *   NULL); d_iters [K][N] steps taken (may be NULL).  Lanes with valid0 == 0 return x0, conv 0. */
+ *   NULL); d_iters [K][N] steps taken (may be NULL).  Lanes with valid0 == 0 return x0, conv 0.
+ *   d_slot [K][N] (may be NULL; needs d_Jinv): bookkeeping for fs_grad.  The kernel counts its
+ *   converged lanes per grid cell of x* as they finish and writes each lane's arrival position in
+ *   its cell (-1 where conv == 0); the counts stay in the context.  The positions depend on the
+ *   order in which lanes finish, so they differ from run to run; any run's set is a valid input of
+ *   fs_grad. */
 fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_t N, int32_t K,
                    const float *d_x0, const float *d_Jinv0, const uint8_t *d_valid0,
-                   float *d_xc, uint8_t *d_conv, float *d_Jinv, uint8_t *d_iters);
+                   float *d_xc, uint8_t *d_conv, float *d_Jinv, uint8_t *d_iters, int32_t *d_slot);
 
 /* Backward by implicit differentiation, Eq. (11)/(12); with FS_GRAD_BROYDEN_J the inverse
  * Jacobian is Broyden's last J~ (Sec. 3.2 "Approximated Gradient", Eq. (15)), with
  * FS_GRAD_EXACT_J it is recomputed analytically at x*.  Only lanes with conv == 1 contribute.
  *   in : d_xc, d_Jinv (may be NULL for FS_GRAD_EXACT_J), d_conv, d_gxc [K][3][N] = dL/dx*,
  *        d_W as given to fs_precompute
+ *        d_slot: NULL, or the array the last fs_solve on this context wrote (same N, K, and d_xc,
+ *        d_conv, d_pose as that call left them; FS_E_STATE otherwise where it can be told): the
+ *        pass that sorts the lanes by grid cell then reuses the solve's counts instead of counting
+ *        again.  The sums are the same up to the order of the fp32 additions.
  *   out: d_gW [nx][ny][nz][n_bones] = dL/dW (summed over poses), d_gB [n_poses][n_bones][12],
  *        d_gxq [3][N] = dL/dx' (may be NULL).  Outputs are overwritten.  Accumulation uses fp32
  *        atomics, so results vary in the last bits from run to run. */
 fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float *d_Jinv,
                   const uint8_t *d_conv, const float *d_gxc, const int32_t *d_pose, int64_t N, int32_t K,
-                  float *d_gW, float *d_gB, float *d_gxq);
+                  const int32_t *d_slot, float *d_gW, float *d_gB, float *d_gxq);
 
 /* Duplicate removal, Sec. 3.1 "Remove Duplicate Correspondences": different initial states often reach
  * the same root, and the canonical field should be queried once per distinct root.  The paper detects

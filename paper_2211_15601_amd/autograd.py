@@ -27,8 +27,10 @@ class CorrespondenceSearch(torch.autograd.Function):
         Jinv = torch.empty((K, 9, N), dtype=torch.float32, device=xq.device)
         W, B, xq = W.contiguous(), B.contiguous(), xq.contiguous()
         fs.precompute(W, B)
-        fs.solve(xq, pose, N, K, None, None, None, xc, conv, Jinv, None)
+        slot = torch.empty((K, N), dtype=torch.int32, device=xq.device)
+        fs.solve(xq, pose, N, K, None, None, None, xc, conv, Jinv, None, slot)
         ctx.fs = fs
+        ctx.slot, ctx.serial = slot, fs.solve_serial
         ctx.pose = pose
         ctx.save_for_backward(W, xc, Jinv, conv)
         ctx.shapes = (W.shape, B.shape)
@@ -43,5 +45,7 @@ class CorrespondenceSearch(torch.autograd.Function):
         gW = torch.empty(ctx.shapes[0], dtype=torch.float32, device=xc.device)
         gB = torch.empty(ctx.shapes[1], dtype=torch.float32, device=xc.device)
         gxq = torch.empty((3, N), dtype=torch.float32, device=xc.device)
-        fs.grad(W, xc, Jinv, conv, g_xc.contiguous(), ctx.pose, N, K, gW, gB, gxq)
+        # the solve's per-cell bookkeeping is reusable only while no other solve ran on the context
+        slot = ctx.slot if (N > 0 and fs.solve_serial == ctx.serial) else None
+        fs.grad(W, xc, Jinv, conv, g_xc.contiguous(), ctx.pose, N, K, gW, gB, gxq, slot)
         return None, gW, gB, gxq, None

@@ -62,8 +62,8 @@ def load():
     L.fs_set_params.argtypes = [vp, ctypes.POINTER(Params)]
     L.fs_precompute.argtypes = [vp, vp, vp]
     L.fs_init.argtypes = [vp, vp, vp, i64, vp, vp, vp]
-    L.fs_solve.argtypes = [vp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp]
-    L.fs_grad.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, vp, vp, vp]
+    L.fs_solve.argtypes = [vp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+    L.fs_grad.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, vp, vp, vp, vp]
     L.fs_get_transforms.argtypes = [vp, vp]
     L.fs_get_corr.argtypes = [vp, vp, vp]
     L.fs_last_error.argtypes = [vp]
@@ -151,13 +151,14 @@ class Context:
     def init(self, xq, pose, N, x0, Jinv0, valid0, check=True):
         return self._ret(self._L.fs_init(self._h, _ptr(xq), _ptr(pose), N, _ptr(x0), _ptr(Jinv0), _ptr(valid0)), check)
 
-    def solve(self, xq, pose, N, K, x0, Jinv0, valid0, xc, conv, Jinv=None, iters=None, check=True):
+    def solve(self, xq, pose, N, K, x0, Jinv0, valid0, xc, conv, Jinv=None, iters=None, slot=None, check=True):
+        self.solve_serial = getattr(self, "solve_serial", 0) + 1      # lets a caller tell whether `slot` is still the last one
         return self._ret(self._L.fs_solve(self._h, _ptr(xq), _ptr(pose), N, K, _ptr(x0), _ptr(Jinv0), _ptr(valid0),
-                                          _ptr(xc), _ptr(conv), _ptr(Jinv), _ptr(iters)), check)
+                                          _ptr(xc), _ptr(conv), _ptr(Jinv), _ptr(iters), _ptr(slot)), check)
 
-    def grad(self, W, xc, Jinv, conv, gxc, pose, N, K, gW, gB, gxq=None, check=True):
+    def grad(self, W, xc, Jinv, conv, gxc, pose, N, K, gW, gB, gxq=None, slot=None, check=True):
         return self._ret(self._L.fs_grad(self._h, _ptr(W), _ptr(xc), _ptr(Jinv), _ptr(conv), _ptr(gxc), _ptr(pose),
-                                         N, K, _ptr(gW), _ptr(gB), _ptr(gxq)), check)
+                                         N, K, _ptr(slot), _ptr(gW), _ptr(gB), _ptr(gxq)), check)
 
     def dedupe(self, xc, conv, N, K, min_dist, keep, offsets, roots=None, lane=None, cap=0, check=True):
         return self._ret(self._L.fs_dedupe(self._h, _ptr(xc), _ptr(conv), N, K, float(min_dist), _ptr(keep),

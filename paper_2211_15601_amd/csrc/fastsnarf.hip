@@ -40,6 +40,9 @@ struct fs_ctx {
     int32_t *cand;     // [P][ncell][ck]
     unsigned *cursor;  // work cursor of the solve kernel
     int *gcount;       // [P*ncells + 1] per-cell lane counts, then offsets (backward)
+    int *gcount_solve; // [P*ncells + 1] per-cell counts of converged lanes written by the last fs_solve that gave slots
+    long long slots_N; // N of that fs_solve (0: none)
+    int slots_K;
     int *gpos;         // [K*N] position of a lane inside its cell's list (grows on demand)
     float *grec;       // [K*N][6] cell-sorted {x*, lambda} records (grows on demand)
     size_t gcap;       // lanes gpos / grec can hold
@@ -132,7 +135,7 @@ int grid1d(long long n, int block) { return (int)((n + block - 1) / block); }
 void free_all(fs_ctx *c)
 {
     void *ptrs[] = {c->T, c->Bdev, c->Binv, c->Bok, c->GT, c->Y, c->bb_ord, c->bbox,
-                    c->cell_of, c->count, c->fill, c->order, c->cand, c->cursor, c->gcount, c->gpos, c->grec, c->scan_sums, c->srec, c->glist, c->gpart, c->voffs, c->vlist};
+                    c->cell_of, c->count, c->fill, c->order, c->cand, c->cursor, c->gcount, c->gcount_solve, c->gpos, c->grec, c->scan_sums, c->srec, c->glist, c->gpart, c->voffs, c->vlist};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
 }
@@ -347,7 +350,7 @@ fs_status fs_init(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_t
 
 fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_t N, int32_t K, const float *d_x0,
                    const float *d_Jinv0, const uint8_t *d_valid0, float *d_xc, uint8_t *d_conv, float *d_Jinv,
-                   uint8_t *d_iters)
+                   uint8_t *d_iters, int32_t *d_slot)
 {
     if (!ctx) return FS_E_ARG;
     if (!ctx->have_T) return fail(ctx, FS_E_STATE, "fs_solve: call fs_precompute first");
@@ -369,6 +372,8 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     FS_CHECK_PTR(ctx, d_conv, false);
     FS_CHECK_PTR(ctx, d_Jinv, true);
     FS_CHECK_PTR(ctx, d_iters, true);
+    FS_CHECK_PTR(ctx, d_slot, true);
+    if (d_slot && !d_Jinv) return fail(ctx, FS_E_ARG, "fs_solve: d_slot needs d_Jinv (both serve fs_grad)");
     SolveP S;
     S.N = N;
     S.total = (long long)N * K;
@@ -424,6 +429,16 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
         list = ctx->vlist;
         list_len = ctx->voffs + N;
     }
+    const int ncell = (ctx->G.nx - 1) * (ctx->G.ny - 1) * (ctx->G.nz - 1);
+    int *cell_count = nullptr;
+    ctx->slots_N = 0;
+    if (d_slot) {
+        const long long ncp = (long long)ctx->G.P * ncell;
+        if (ncp + 1 >= (1ll << 31)) return fail(ctx, FS_E_SHAPE, "fs_solve: too many grid cells for d_slot");
+        if (!ctx->gcount_solve && !dev_alloc(&ctx->gcount_solve, (size_t)ncp + 1)) return fail(ctx, FS_E_ALLOC, "fs_solve: out of device memory");
+        k_fill_zero_i32<<<(int)std::min<long long>(grid1d(ncp + 1, 256), 4096), 256, 0, st>>>(ncp + 1, ctx->gcount_solve);
+        cell_count = ctx->gcount_solve;
+    }
     k_reset_cursor<<<1, 64, 0, st>>>(ctx->cursor);
     const dim3 grd(blocks), blk(wpb * WAVE);
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
@@ -431,7 +446,7 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     const size_t shm = lds ? grid_bytes : 0;
 #define FS_LAUNCH_SOLVE(F, J, L)                                                                                      \
     k_solve<F, J, L><<<grd, blk, shm, st>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, d_x0, d_Jinv0, d_valid0, ctx->srec, \
-                                            ctx->cursor, list, list_len)
+                                            ctx->cursor, list, list_len, cell_count, ncell)
     if (lds) {
         if (fused && with_J) FS_LAUNCH_SOLVE(true, true, true);
         else if (fused) FS_LAUNCH_SOLVE(true, false, true);
@@ -451,19 +466,24 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     const bool nocand = fused && ctx->prm.init_mode == FS_INIT_VOXEL;
     const int ub = grid1d(S.total, 256);
     if (with_J && nocand)
-        k_solve_unpack<true, true><<<ub, 256, 0, st>>>(ctx->G, I, N, S.total, d_xq, d_pose, ctx->srec, d_xc, d_conv, d_Jinv, d_iters);
+        k_solve_unpack<true, true><<<ub, 256, 0, st>>>(ctx->G, I, N, S.total, d_xq, d_pose, ctx->srec, d_xc, d_conv, d_Jinv, d_iters, d_slot);
     else if (with_J)
-        k_solve_unpack<true, false><<<ub, 256, 0, st>>>(ctx->G, I, N, S.total, d_xq, d_pose, ctx->srec, d_xc, d_conv, d_Jinv, d_iters);
+        k_solve_unpack<true, false><<<ub, 256, 0, st>>>(ctx->G, I, N, S.total, d_xq, d_pose, ctx->srec, d_xc, d_conv, d_Jinv, d_iters, d_slot);
     else if (nocand)
-        k_solve_unpack<false, true><<<ub, 256, 0, st>>>(ctx->G, I, N, S.total, d_xq, d_pose, ctx->srec, d_xc, d_conv, d_Jinv, d_iters);
+        k_solve_unpack<false, true><<<ub, 256, 0, st>>>(ctx->G, I, N, S.total, d_xq, d_pose, ctx->srec, d_xc, d_conv, d_Jinv, d_iters, d_slot);
     else
-        k_solve_unpack<false, false><<<ub, 256, 0, st>>>(ctx->G, I, N, S.total, d_xq, d_pose, ctx->srec, d_xc, d_conv, d_Jinv, d_iters);
-    return launch_status(ctx, "fs_solve");
+        k_solve_unpack<false, false><<<ub, 256, 0, st>>>(ctx->G, I, N, S.total, d_xq, d_pose, ctx->srec, d_xc, d_conv, d_Jinv, d_iters, d_slot);
+    fs_status lst = launch_status(ctx, "fs_solve");
+    if (lst == FS_OK && d_slot) {
+        ctx->slots_N = N;
+        ctx->slots_K = K;
+    }
+    return lst;
 }
 
 fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float *d_Jinv, const uint8_t *d_conv,
-                  const float *d_gxc, const int32_t *d_pose, int64_t N, int32_t K, float *d_gW, float *d_gB,
-                  float *d_gxq)
+                  const float *d_gxc, const int32_t *d_pose, int64_t N, int32_t K, const int32_t *d_slot, float *d_gW,
+                  float *d_gB, float *d_gxq)
 {
     if (!ctx) return FS_E_ARG;
     if (!ctx->have_T) return fail(ctx, FS_E_STATE, "fs_grad: call fs_precompute first");
@@ -482,6 +502,9 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
         FS_CHECK_PTR(ctx, d_gxc, false);
         FS_CHECK_PTR(ctx, d_pose, true);
     }
+    FS_CHECK_PTR(ctx, d_slot, true);
+    if (d_slot && (ctx->slots_N != N || ctx->slots_K != K || N == 0))
+        return fail(ctx, FS_E_STATE, "fs_grad: d_slot must come from the last fs_solve on this context with the same N and K");
     const GridP &G = ctx->G;
     const int ncell = (G.nx - 1) * (G.ny - 1) * (G.nz - 1);
     const long long ncp = (long long)G.P * ncell;
@@ -504,13 +527,21 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
         ctx->gcap = lanes;
     }
     hipStream_t st = ctx->stream;
-    k_fill_zero_i32<<<(int)std::min<long long>(grid1d(ncp + 1, 256), 4096), 256, 0, st>>>(ncp + 1, ctx->gcount);
+    const int *pos = ctx->gpos;
+    if (d_slot) {
+        // the solve already counted its converged lanes per cell and gave each its slot
+        if (hipMemcpyAsync(ctx->gcount, ctx->gcount_solve, sizeof(int) * (size_t)(ncp + 1), hipMemcpyDeviceToDevice, st) != hipSuccess)
+            return launch_status(ctx, "fs_grad: copy of cell counts");
+        pos = d_slot;
+    } else {
+        k_fill_zero_i32<<<(int)std::min<long long>(grid1d(ncp + 1, 256), 4096), 256, 0, st>>>(ncp + 1, ctx->gcount);
+        if (N > 0) k_grad_count<<<grid1d((long long)N * K, 256), 256, 0, st>>>(G, d_xc, d_conv, d_pose, N, K, ncell, ctx->gcount, ctx->gpos);
+    }
     k_fill_zero_i32<<<1, 64, 0, st>>>(1, ctx->glist);
-    if (N > 0) k_grad_count<<<grid1d((long long)N * K, 256), 256, 0, st>>>(G, d_xc, d_conv, d_pose, N, K, ncell, ctx->gcount, ctx->gpos);
     { fs_status ss = scan_exclusive(ctx, (int)ncp, ctx->gcount); if (ss != FS_OK) return ss; }
     if (N > 0)
         k_grad_records<<<grid1d(N, 256), 256, 0, st>>>(G, mode, ctx->T, d_xc, d_Jinv, d_conv, d_gxc, d_pose, N, K, ncell,
-                                                       ctx->gcount, ctx->gpos, ctx->grec, d_gxq);
+                                                       ctx->gcount, pos, ctx->grec, d_gxq);
     k_grad_nodes<<<grid1d((long long)G.P * G.V, 256), 256, 0, st>>>(G, ncell, ctx->gcount, ctx->grec, ctx->GT, ctx->glist, ctx->glist + 1);
     k_grad_gather<<<ctx->n_cus * 8, 256, 0, st>>>(G, ncell, ctx->gcount, ctx->grec, ctx->glist, ctx->glist + 1, ctx->GT);
     const size_t shB = sizeof(float) * G.P * G.nb * 12;

@@ -414,6 +414,14 @@ struct SolveP {
     int point_major;     // order in which pairs are handed out
 };
 
+__device__ __forceinline__ int cell_linear(const GridP &G, const Cell &c)
+{
+    // c.base = ((ix*ny + iy)*nz + iz)*12 in node strides; recover the cell's own linear index
+    const int ix = c.base / G.sx, rem = c.base - ix * G.sx;
+    const int iy = rem / G.sy, iz = (rem - iy * G.sy) / 12;
+    return (ix * (G.ny - 1) + iy) * (G.nz - 1) + iz;
+}
+
 // What the fused variant needs to compute initial states itself (same arithmetic as k_init_*).
 struct InitP {
     int mode;                 // 0: one state per bone (Eq. (8)); 1: candidates of the correspondence grid
@@ -426,14 +434,14 @@ struct InitP {
 
 template <bool WITH_J>
 __device__ __forceinline__ void write_record(float4 *__restrict__ rec, long long pq, const float x[3], const float J[9],
-                                             int flags)
+                                             int flags, int slot = -1)
 {
     if (WITH_J) {
         float4 *o = rec + pq * 4;
         o[0] = make_float4(x[0], x[1], x[2], __int_as_float(flags));
         o[1] = make_float4(J[0], J[1], J[2], J[3]);
         o[2] = make_float4(J[4], J[5], J[6], J[7]);
-        o[3] = make_float4(J[8], 0.0f, 0.0f, 0.0f);
+        o[3] = make_float4(J[8], __int_as_float(slot), 0.0f, 0.0f);
     } else {
         rec[pq] = make_float4(x[0], x[1], x[2], __int_as_float(flags));
     }
@@ -472,7 +480,7 @@ __global__ __launch_bounds__(256) void k_solve_unpack(GridP G, InitP I, long lon
                                                       const float *__restrict__ xq, const int32_t *__restrict__ pose,
                                                       const float4 *__restrict__ rec, float *__restrict__ o_x,
                                                       uint8_t *__restrict__ o_conv, float *__restrict__ o_J,
-                                                      uint8_t *__restrict__ o_it)
+                                                      uint8_t *__restrict__ o_it, int32_t *__restrict__ o_slot)
 {
     const long long pq = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (pq >= total) return;
@@ -497,6 +505,9 @@ __global__ __launch_bounds__(256) void k_solve_unpack(GridP G, InitP I, long lon
         if (have) {
             const float4 b = rec[pq * 4 + 1], c = rec[pq * 4 + 2], d = rec[pq * 4 + 3];
             J[0] = b.x; J[1] = b.y; J[2] = b.z; J[3] = b.w; J[4] = c.x; J[5] = c.y; J[6] = c.z; J[7] = c.w; J[8] = d.x;
+            if (o_slot) o_slot[pq] = (flags & 1) ? __float_as_int(d.y) : -1;
+        } else if (o_slot) {
+            o_slot[pq] = -1;
         }
 #pragma unroll
         for (int e = 0; e < 9; ++e) o_J[(k * 9 + e) * N + n] = J[e];
@@ -516,7 +527,7 @@ __global__ void k_reset_cursor(unsigned *__restrict__ cursor)
 // Results leave the kernel as one contiguous record per pair (lanes finish at different times, so
 // writing the caller's structure-of-arrays layout from here would touch 14 cache lines per pair with
 // 4 bytes each); k_solve_unpack then moves the records into that layout with coalesced stores.
-// Record: WITH_J ? 16 floats {x*[3], flags, J~[9], pad[3]} : 4 floats {x*[3], flags};
+// Record: WITH_J ? 16 floats {x*[3], flags, J~[9], slot, pad[2]} : 4 floats {x*[3], flags};
 // flags = conv | iters << 8 (as an integer bit pattern).
 // LDSGRID: the whole transform grid (all poses) fits in LDS; every block copies it there first and all
 // corner records are then read from LDS, where per-lane addresses cost far less than in the vector
@@ -527,7 +538,8 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const
                                                const float *__restrict__ x0, const float *__restrict__ J0,
                                                const uint8_t *__restrict__ valid0, float4 *__restrict__ rec,
                                                unsigned *__restrict__ cursor, const int *__restrict__ list,
-                                               const int *__restrict__ list_len)
+                                               const int *__restrict__ list_len, int *__restrict__ cell_count,
+                                               int ncell)
 {
     extern __shared__ float4 s_grid[];
     const float *T = Tglobal;
@@ -547,7 +559,7 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const
 
     bool active = false, fresh = false;
     long long n = 0;
-    int k = 0, it = 0;
+    int k = 0, it = 0, pz = 0;
     const float *Tp = T;
     float xp[3] = {0, 0, 0}, x[3] = {0, 0, 0}, xt[3] = {0, 0, 0}, g[3] = {0, 0, 0}, dx[3] = {0, 0, 0};
     float J[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
@@ -587,6 +599,7 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const
                         n = pq - (long long)k * N;
                     }
                     const int p = pose_of(pose, n, G.P);
+                    pz = p;
                     Tp = T + (long long)p * G.V * 12;
                     it = 0;
                     held = -1;
@@ -692,7 +705,10 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const
             const bool conv = r2 < S.tol2;
             const bool done = conv || !(r2 < S.div2) || it >= S.max_iters;
             if (done) {
-                write_record<WITH_J>(rec, (long long)k * N + n, x, J, (conv ? 1 : 0) | (it << 8));
+                // for the backward: the arrival position of a converged lane in the list of its grid cell
+                int slot = -1;
+                if (WITH_J && cell_count && conv) slot = atomicAdd(cell_count + pz * ncell + cell_linear(G, cell), 1);
+                write_record<WITH_J>(rec, (long long)k * N + n, x, J, (conv ? 1 : 0) | (it << 8), slot);
                 active = false;
             } else {
 #pragma unroll
@@ -725,14 +741,6 @@ __global__ void k_fill_zero_i32(long long n, int *__restrict__ a)
     long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     const long long stride = (long long)gridDim.x * blockDim.x;
     for (; i < n; i += stride) a[i] = 0;
-}
-
-__device__ __forceinline__ int cell_linear(const GridP &G, const Cell &c)
-{
-    // c.base = ((ix*ny + iy)*nz + iz)*12 in node strides; recover the cell's own linear index
-    const int ix = c.base / G.sx, rem = c.base - ix * G.sx;
-    const int iy = rem / G.sy, iz = (rem - iy * G.sy) / 12;
-    return (ix * (G.ny - 1) + iy) * (G.nz - 1) + iz;
 }
 
 // pass 1: one thread per lane; position of the lane inside its cell's list (arrival order)

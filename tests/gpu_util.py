@@ -57,7 +57,7 @@ class GpuRun:
         torch.cuda.synchronize()
         return self.x0.cpu().numpy(), self.J0.cpu().numpy(), self.v0.cpu().numpy()
 
-    def solve(self, x0=None, J0=None, v0=None, want_J=True, fused=False):
+    def solve(self, x0=None, J0=None, v0=None, want_J=True, fused=False, slots=False):
         """fused=True passes NULL initial states: the solve kernel computes them itself."""
         N, K = self.N, self.K
         if fused:
@@ -70,18 +70,19 @@ class GpuRun:
         self.cv = torch.full((K, N), 77, dtype=torch.uint8, device=DEV)
         self.Jo = torch.full((K, 9, N), float("nan"), dtype=torch.float32, device=DEV) if want_J else None
         self.it = torch.full((K, N), 255, dtype=torch.uint8, device=DEV)
-        self.ctx.solve(self.xq, self.pose, N, K, x0, J0, v0, self.xc, self.cv, self.Jo, self.it)
+        self.slot = torch.full((K, N), -7, dtype=torch.int32, device=DEV) if slots else None
+        self.ctx.solve(self.xq, self.pose, N, K, x0, J0, v0, self.xc, self.cv, self.Jo, self.it, self.slot)
         torch.cuda.synchronize()
         return (self.xc.cpu().numpy(), self.cv.cpu().numpy(),
                 self.Jo.cpu().numpy() if want_J else None, self.it.cpu().numpy())
 
-    def grad(self, xc, Jo, cv, gxc, want_gxq=True):
+    def grad(self, xc, Jo, cv, gxc, want_gxq=True, slot=None):
         w = self.w
         gW = torch.full(w.W.shape, float("nan"), dtype=torch.float32, device=DEV)
         gB = torch.full(w.B.shape, float("nan"), dtype=torch.float32, device=DEV)
         gxq = torch.full((3, self.N), float("nan"), dtype=torch.float32, device=DEV) if want_gxq else None
         self.ctx.grad(self.W, dev(xc), None if Jo is None else dev(Jo), dev(cv), dev(gxc), self.pose, self.N, self.K,
-                      gW, gB, gxq)
+                      gW, gB, gxq, slot)
         torch.cuda.synchronize()
         return gW.cpu().numpy(), gB.cpu().numpy(), gxq.cpu().numpy() if want_gxq else None
 

@@ -81,7 +81,8 @@ def test_create_rejects_bad_shapes_before_touching_the_device():
 def test_null_context_is_an_argument_error():
     L = binding.load()
     assert L.fs_precompute(None, None, None) == binding.FS_E_ARG
-    assert L.fs_solve(None, None, None, 0, 24, None, None, None, None, None, None, None) == binding.FS_E_ARG
+    assert L.fs_solve(None, None, None, 0, 24, None, None, None, None, None, None, None, None) == binding.FS_E_ARG
+    assert L.fs_grad(None, None, None, None, None, None, None, 0, 24, None, None, None, None) == binding.FS_E_ARG
     assert L.fs_destroy(None) == binding.FS_OK
     assert L.fs_last_error(None) == b"null context"
 

@@ -116,6 +116,46 @@ def test_grad_parity(lib, case, mode):
     assert np.linalg.norm(gB2.astype(np.float64) - rB) / np.linalg.norm(rB) < 2e-5
 
 
+@pytest.mark.parametrize("case", [(2, 5003, (32, 32, 8), None), (3, 16 * 255, (32, 32, 8), None), (5, 8 * 1003, (32, 32, 16), 8),
+                                  (2, None, None, None)], ids=_ids)
+def test_grad_with_slots_from_solve(lib, case):
+    # fs_solve's d_slot output (arrival position of each converged lane in its grid cell, counted by the
+    # Broyden kernel) replaces fs_grad's own counting pass; the gradient must not change beyond summation order
+    cfg, n, dims, P = case
+    w = wl.make_config(cfg, n_points=n, dims=dims, n_poses=P)
+    pose = w.pose if w.n_poses > 1 else None
+    run = gu.GpuRun(w, grad_mode=binding.FS_GRAD_BROYDEN_J)
+    T = run.precompute()
+    xc, cv, Jo, it = run.solve(fused=True, slots=True)
+    slot = run.slot.cpu().numpy()
+    assert ((slot == -1) == (cv == 0)).all()
+    assert slot.min() >= -1 and slot.max() < max(int(cv.sum()), 1)
+    gxc = w.upstream_grads()
+    rW, rB, rq = oracle.grad(w.dims, w.lo, w.hi, T, w.W, w.B, xc, Jo, cv, gxc, pose=pose, mode=0, prec="f64")
+    for rep in range(2):            # the context keeps the solve's counts: a second backward works as the first
+        gW, gB, gxq = run.grad(xc, Jo, cv, gxc, slot=run.slot)
+        for name, a, b in (("gW", gW, rW), ("gB", gB, rB), ("gxq", gxq, rq)):
+            assert np.isfinite(a).all(), name
+            rel = np.linalg.norm(a.astype(np.float64) - b) / max(np.linalg.norm(b), 1e-30)
+            print(f"{w.name} slots rep {rep} {name}: relative L2 vs f64 oracle {rel:.2e}")
+            assert rel < 2e-5, (name, rel)
+    # and the counting path gives the same result on the same inputs
+    cW, cB, cq = run.grad(xc, Jo, cv, gxc)
+    assert np.linalg.norm(cW.astype(np.float64) - rW) / np.linalg.norm(rW) < 2e-5
+    # slots of another solve (different N) are refused
+    small = wl.make_config(cfg, n_points=64, dims=w.dims, n_poses=P)
+    xq2 = gu.dev(small.xq)
+    pz2 = gu.dev(small.pose) if small.n_poses > 1 else None
+    o = [torch.empty(sh, dtype=dt, device=gu.DEV) for sh, dt in (((w.K, 3, 64), torch.float32), ((w.K, 64), torch.uint8),
+                                                                   ((w.K, 9, 64), torch.float32))]
+    run.ctx.solve(xq2, pz2, 64, w.K, None, None, None, o[0], o[1], o[2], None, None)
+    gWt = torch.empty(w.W.shape, dtype=torch.float32, device=gu.DEV)
+    gBt = torch.empty(w.B.shape, dtype=torch.float32, device=gu.DEV)
+    st = run.ctx.grad(run.W, gu.dev(xc), gu.dev(Jo), gu.dev(cv), gu.dev(gxc), run.pose, w.N, w.K, gWt, gBt, None, run.slot,
+                      check=False)
+    assert st == binding.FS_E_STATE
+
+
 @pytest.mark.parametrize("case", [(2, 5003, (32, 32, 8), None), (3, 16 * 250, (32, 32, 8), None), (1, 4096, None, None)], ids=_ids)
 def test_dedupe_parity(lib, case):
     # Sec. 3.1 "Remove Duplicate Correspondences": keep mask, offsets, packed roots and lane ids, bit for bit
@@ -218,7 +258,7 @@ def test_edge_cases(lib):
     # fused initial states: all three NULL or none
     assert ctx.solve(run.xq, None, N, K, None, J0, v0, xc, cv, check=False) == binding.FS_E_ARG
     # empty input is a no-op, also with null pointers
-    assert ctx._L.fs_solve(ctx._h, None, None, 0, K, None, None, None, None, None, None, None) == binding.FS_OK
+    assert ctx._L.fs_solve(ctx._h, None, None, 0, K, None, None, None, None, None, None, None, None) == binding.FS_OK
     assert ctx._L.fs_init(ctx._h, None, None, 0, None, None, None) == binding.FS_OK
     # pointers: null, misaligned, host memory
     assert ctx.solve(None, None, N, K, x0, J0, v0, xc, cv, check=False) == binding.FS_E_ARG
