@@ -140,11 +140,12 @@ void free_all(fs_ctx *c)
         if (p) (void)hipFree(p);
 }
 
-// exclusive scan of a[0..n) in place on the context's stream, a[n] = total
-fs_status scan_exclusive(fs_ctx *c, int n, int *a)
+// exclusive scan of src[0..n) into a[0..n) (src == nullptr: in place) on the context's stream,
+// a[n] = total; *also_zero (may be null) is cleared on the way
+fs_status scan_exclusive(fs_ctx *c, int n, int *a, const int *src = nullptr, int *also_zero = nullptr)
 {
     if (n <= 0) {
-        k_fill_zero_i32<<<1, 64, 0, c->stream>>>(1, a);
+        k_fill_zero_i32<<<1, 64, 0, c->stream>>>(1, a, reinterpret_cast<unsigned *>(also_zero));
         return FS_OK;
     }
     const int m = (n + SCAN_TILE - 1) / SCAN_TILE;
@@ -155,9 +156,9 @@ fs_status scan_exclusive(fs_ctx *c, int n, int *a)
         if (!dev_alloc(&c->scan_sums, (size_t)m + 1)) return fail(c, FS_E_ALLOC, "out of device memory (scan)");
         c->scan_cap = m + 1;
     }
-    k_scan_tile_sums<<<m, 1024, 0, c->stream>>>(n, a, c->scan_sums);
-    k_scan_sums<<<1, 1024, 0, c->stream>>>(m, c->scan_sums);
-    k_scan_tiles<<<m, 1024, 0, c->stream>>>(n, a, c->scan_sums, m);
+    k_scan_tile_sums<<<m, 1024, 0, c->stream>>>(n, src ? src : a, c->scan_sums);
+    k_scan_sums<<<1, 1024, 0, c->stream>>>(m, c->scan_sums, also_zero);
+    k_scan_tiles<<<m, 1024, 0, c->stream>>>(n, src ? src : a, a, c->scan_sums, m);
     return FS_OK;
 }
 
@@ -284,7 +285,7 @@ fs_status fs_set_params(fs_ctx *ctx, const fs_params *params)
 fs_status fs_set_tuning(fs_ctx *ctx, int32_t chunk, int32_t refill_min, int32_t blocks_per_cu, int32_t point_major, int32_t lds_grid)
 {
     if (!ctx) return FS_E_ARG;
-    if ((chunk != 0 && (chunk < 64 || chunk > 65536)) || (refill_min != 0 && (refill_min < 1 || refill_min > 64)) ||
+    if ((chunk != 0 && (chunk < 8 || chunk > 65536)) || (refill_min != 0 && (refill_min < 1 || refill_min > 64)) ||
         blocks_per_cu < 0 || blocks_per_cu > 32 || point_major < -1 || point_major > 1 || lds_grid < -1 || lds_grid > 1)
         return fail(ctx, FS_E_ARG, "fs_set_tuning: value out of range");
     if (chunk) ctx->chunk = chunk;
@@ -301,12 +302,8 @@ fs_status fs_precompute(fs_ctx *ctx, const float *d_W, const float *d_B)
     FS_CHECK_PTR(ctx, d_W, false);
     FS_CHECK_PTR(ctx, d_B, false);
     const GridP &G = ctx->G;
-    const int nB = G.P * G.nb * 12;
     hipStream_t st = ctx->stream;
-    if (hipMemcpyAsync(ctx->Bdev, d_B, sizeof(float) * nB, hipMemcpyDeviceToDevice, st) != hipSuccess)
-        return launch_status(ctx, "fs_precompute: copy of bone transforms");
-    k_bone_inverse<<<grid1d(G.P * G.nb, 64), 64, 0, st>>>(G.P * G.nb, d_B, ctx->Binv, ctx->Bok);
-    k_precompute<<<grid1d(G.V, 256), 256, 0, st>>>(G, d_W, d_B, ctx->T);
+    k_precompute<<<grid1d(G.V, 256), 256, 0, st>>>(G, d_W, d_B, ctx->T, ctx->Bdev, ctx->Binv, ctx->Bok);
     if (ctx->prm.init_mode == FS_INIT_VOXEL) {
         const CorrP &C = ctx->C;
         const int ncp = G.P * C.ncell;
@@ -436,10 +433,11 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
         const long long ncp = (long long)ctx->G.P * ncell;
         if (ncp + 1 >= (1ll << 31)) return fail(ctx, FS_E_SHAPE, "fs_solve: too many grid cells for d_slot");
         if (!ctx->gcount_solve && !dev_alloc(&ctx->gcount_solve, (size_t)ncp + 1)) return fail(ctx, FS_E_ALLOC, "fs_solve: out of device memory");
-        k_fill_zero_i32<<<(int)std::min<long long>(grid1d(ncp + 1, 256), 4096), 256, 0, st>>>(ncp + 1, ctx->gcount_solve);
+        k_fill_zero_i32<<<(int)std::min<long long>(grid1d(ncp + 1, 256), 4096), 256, 0, st>>>(ncp + 1, ctx->gcount_solve, ctx->cursor);
         cell_count = ctx->gcount_solve;
+    } else {
+        k_reset_cursor<<<1, 64, 0, st>>>(ctx->cursor);
     }
-    k_reset_cursor<<<1, 64, 0, st>>>(ctx->cursor);
     const dim3 grd(blocks), blk(wpb * WAVE);
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     if (ctx->timing && hipEventCreate(&ev0) == hipSuccess && hipEventCreate(&ev1) == hipSuccess) (void)hipEventRecord(ev0, st);
@@ -527,18 +525,17 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
         ctx->gcap = lanes;
     }
     hipStream_t st = ctx->stream;
-    const int *pos = ctx->gpos;
+    const int *pos = ctx->gpos, *counts = nullptr;
     if (d_slot) {
-        // the solve already counted its converged lanes per cell and gave each its slot
-        if (hipMemcpyAsync(ctx->gcount, ctx->gcount_solve, sizeof(int) * (size_t)(ncp + 1), hipMemcpyDeviceToDevice, st) != hipSuccess)
-            return launch_status(ctx, "fs_grad: copy of cell counts");
+        // the solve already counted its converged lanes per cell and gave each its slot; its counts are
+        // left as they are, so the backward can be repeated
         pos = d_slot;
+        counts = ctx->gcount_solve;
     } else {
         k_fill_zero_i32<<<(int)std::min<long long>(grid1d(ncp + 1, 256), 4096), 256, 0, st>>>(ncp + 1, ctx->gcount);
         if (N > 0) k_grad_count<<<grid1d((long long)N * K, 256), 256, 0, st>>>(G, d_xc, d_conv, d_pose, N, K, ncell, ctx->gcount, ctx->gpos);
     }
-    k_fill_zero_i32<<<1, 64, 0, st>>>(1, ctx->glist);
-    { fs_status ss = scan_exclusive(ctx, (int)ncp, ctx->gcount); if (ss != FS_OK) return ss; }
+    { fs_status ss = scan_exclusive(ctx, (int)ncp, ctx->gcount, counts, ctx->glist); if (ss != FS_OK) return ss; }
     if (N > 0)
         k_grad_records<<<grid1d(N, 256), 256, 0, st>>>(G, mode, ctx->T, d_xc, d_Jinv, d_conv, d_gxc, d_pose, N, K, ncell,
                                                        ctx->gcount, pos, ctx->grec, d_gxq);

@@ -21,10 +21,19 @@ constexpr int FS_MAX_CORR_K_DEV = 8;
 // wave-uniform addresses, i.e. through the scalar cache into SGPR operands of the multiply-adds.
 // Reads W once (96 B / node for 24 bones), writes 48 B per node and pose.
 // ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ void bone_inverse(int i, const float *__restrict__ B, float *__restrict__ Bcopy,
+                                             float *__restrict__ Binv, uint8_t *__restrict__ ok);
+
+// The first n_poses*n_bones threads also invert their bone's linear part for Eq. (8) and keep a copy
+// of the bone transforms for the backward.
 __global__ __launch_bounds__(256) void k_precompute(GridP G, const float *__restrict__ W,
-                                                    const float *__restrict__ B, float *__restrict__ T)
+                                                    const float *__restrict__ B, float *__restrict__ T,
+                                                    float *__restrict__ Bcopy, float *__restrict__ Binv,
+                                                    uint8_t *__restrict__ Bok)
 {
     const long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    for (long long i = v; i < (long long)G.P * G.nb; i += (long long)gridDim.x * blockDim.x)
+        bone_inverse((int)i, B, Bcopy, Binv, Bok);
     if (v >= G.V) return;
     const float *w = W + v * G.nb;
     const bool vec = (G.nb & 3) == 0;        // weight rows are 16-byte aligned: read them four at a time
@@ -63,13 +72,12 @@ __global__ __launch_bounds__(256) void k_precompute(GridP G, const float *__rest
     }
 }
 
-// Inverse of every bone's linear part for Eq. (8): Binv [P][nb][12] = 9 inverse entries + t, ok flag.
-__global__ void k_bone_inverse(int n, const float *__restrict__ B, float *__restrict__ Binv,
-                               uint8_t *__restrict__ ok)
+// Inverse of one bone's linear part for Eq. (8): Binv [P][nb][12] = 9 inverse entries + t, ok flag.
+__device__ __forceinline__ void bone_inverse(int i, const float *__restrict__ B, float *__restrict__ Bcopy,
+                                             float *__restrict__ Binv, uint8_t *__restrict__ ok)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
     const float *b = B + i * 12;
+    for (int e = 0; e < 12; ++e) Bcopy[i * 12 + e] = b[e];
     const float R[9] = {b[0], b[1], b[2], b[4], b[5], b[6], b[8], b[9], b[10]};
     float Ri[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
     const bool good = inv3(R, Ri);
@@ -293,9 +301,11 @@ __global__ __launch_bounds__(1024) void k_scan_tile_sums(int n, const int *__res
     if (threadIdx.x == 0) sums[blockIdx.x] = tot;
 }
 
-// sums[0..m) -> exclusive scan in place, sums[m] = total (one block, loops over m in steps of 1024)
-__global__ __launch_bounds__(1024) void k_scan_sums(int m, int *__restrict__ sums)
+// sums[0..m) -> exclusive scan in place, sums[m] = total (one block, loops over m in steps of 1024);
+// also clears *also_zero when given (saves the caller a launch)
+__global__ __launch_bounds__(1024) void k_scan_sums(int m, int *__restrict__ sums, int *__restrict__ also_zero)
 {
+    if (also_zero && threadIdx.x == 0) *also_zero = 0;
     int run = 0;
     for (int s0 = 0; s0 < m; s0 += 1024) {
         const int i = s0 + threadIdx.x;
@@ -308,7 +318,8 @@ __global__ __launch_bounds__(1024) void k_scan_sums(int m, int *__restrict__ sum
     if (threadIdx.x == 0) sums[m] = run;
 }
 
-__global__ __launch_bounds__(1024) void k_scan_tiles(int n, int *__restrict__ a, const int *__restrict__ sums, int m)
+// out[i] = exclusive prefix of a (out may be a itself), out[n] = total
+__global__ __launch_bounds__(1024) void k_scan_tiles(int n, const int *a, int *out, const int *__restrict__ sums, int m)
 {
     const long long base = (long long)blockIdx.x * SCAN_TILE + threadIdx.x * 4;
     int e4[4], v = 0;
@@ -321,10 +332,10 @@ __global__ __launch_bounds__(1024) void k_scan_tiles(int n, int *__restrict__ a,
     int run = sums[blockIdx.x] + block_exclusive_scan_1024(v, &tot);
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-        if (base + e < n) a[base + e] = run;
+        if (base + e < n) out[base + e] = run;
         run += e4[e];
     }
-    if (blockIdx.x == 0 && threadIdx.x == 0) a[n] = sums[m];
+    if (blockIdx.x == 0 && threadIdx.x == 0) out[n] = sums[m];
 }
 
 __global__ __launch_bounds__(256) void k_corr_scatter(GridP G, CorrP C, const int *__restrict__ cell_of,
@@ -736,10 +747,11 @@ __global__ void k_fill_zero(long long n, float *__restrict__ a)
 // atomics leave the L2 on this chip and are slow): converged lanes are counting-sorted by the grid
 // cell of x*, then one wave per grid node sums the contributions of the lanes in its 8 adjacent cells.
 
-__global__ void k_fill_zero_i32(long long n, int *__restrict__ a)
+__global__ void k_fill_zero_i32(long long n, int *__restrict__ a, unsigned *__restrict__ also_zero = nullptr)
 {
     long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     const long long stride = (long long)gridDim.x * blockDim.x;
+    if (also_zero && i == 0) *also_zero = 0u;
     for (; i < n; i += stride) a[i] = 0;
 }
 
