@@ -44,9 +44,8 @@ struct fs_ctx {
     long long slots_N; // N of that fs_solve (0: none)
     int slots_K;
     int *gpos;         // [K*N] position of a lane inside its cell's list (grows on demand)
-    float *grec;       // [K*N][6] cell-sorted {x*, lambda} records (grows on demand)
+    float *grec;       // [K*N][8] cell-sorted {x*, lambda, cell} records (grows on demand)
     size_t gcap;       // lanes gpos / grec can hold
-    int *glist;        // [1 + P*V] number of grid nodes with work, then their indices (backward)
     float *gpart;      // [P][gb_blocks][nb*12] partial sums of dL/dB
     int gb_blocks;
     float4 *srec;      // per-pair result records of the solve kernel (grows on demand)
@@ -135,7 +134,7 @@ int grid1d(long long n, int block) { return (int)((n + block - 1) / block); }
 void free_all(fs_ctx *c)
 {
     void *ptrs[] = {c->T, c->Bdev, c->Binv, c->Bok, c->GT, c->Y, c->bb_ord, c->bbox,
-                    c->cell_of, c->count, c->fill, c->order, c->cand, c->cursor, c->gcount, c->gcount_solve, c->gpos, c->grec, c->scan_sums, c->srec, c->glist, c->gpart, c->voffs, c->vlist};
+                    c->cell_of, c->count, c->fill, c->order, c->cand, c->cursor, c->gcount, c->gcount_solve, c->gpos, c->grec, c->scan_sums, c->srec, c->gpart, c->voffs, c->vlist};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
 }
@@ -509,7 +508,6 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
     if (ncp + 1 >= (1ll << 31)) return fail(ctx, FS_E_SHAPE, "fs_grad: too many grid cells");
     if (!ctx->GT && !dev_alloc(&ctx->GT, (size_t)G.P * G.V * 12)) return fail(ctx, FS_E_ALLOC, "fs_grad: out of device memory");
     if (!ctx->gcount && !dev_alloc(&ctx->gcount, (size_t)ncp + 1)) return fail(ctx, FS_E_ALLOC, "fs_grad: out of device memory");
-    if (!ctx->glist && !dev_alloc(&ctx->glist, (size_t)G.P * G.V + 1)) return fail(ctx, FS_E_ALLOC, "fs_grad: out of device memory");
     if (!ctx->gpart) {
         ctx->gb_blocks = (int)std::min<long long>(grid1d(G.V, GB_TILE), 256);
         if (!dev_alloc(&ctx->gpart, (size_t)G.P * ctx->gb_blocks * G.nb * 12)) return fail(ctx, FS_E_ALLOC, "fs_grad: out of device memory");
@@ -520,7 +518,7 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
         if (ctx->gpos) (void)hipFree(ctx->gpos);
         if (ctx->grec) (void)hipFree(ctx->grec);
         ctx->gpos = nullptr; ctx->grec = nullptr; ctx->gcap = 0;
-        if (!dev_alloc(&ctx->gpos, lanes) || !dev_alloc(&ctx->grec, lanes * 6))
+        if (!dev_alloc(&ctx->gpos, lanes) || !dev_alloc(&ctx->grec, std::max<size_t>(lanes, PIECE_MIN) * GREC))
             return fail(ctx, FS_E_ALLOC, "fs_grad: out of device memory for %zu lanes", lanes);
         ctx->gcap = lanes;
     }
@@ -535,12 +533,17 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
         k_fill_zero_i32<<<(int)std::min<long long>(grid1d(ncp + 1, 256), 4096), 256, 0, st>>>(ncp + 1, ctx->gcount);
         if (N > 0) k_grad_count<<<grid1d((long long)N * K, 256), 256, 0, st>>>(G, d_xc, d_conv, d_pose, N, K, ncell, ctx->gcount, ctx->gpos);
     }
-    { fs_status ss = scan_exclusive(ctx, (int)ncp, ctx->gcount, counts, ctx->glist); if (ss != FS_OK) return ss; }
+    { fs_status ss = scan_exclusive(ctx, (int)ncp, ctx->gcount, counts); if (ss != FS_OK) return ss; }
     if (N > 0)
         k_grad_records<<<grid1d(N, 256), 256, 0, st>>>(G, mode, ctx->T, d_xc, d_Jinv, d_conv, d_gxc, d_pose, N, K, ncell,
-                                                       ctx->gcount, pos, ctx->grec, d_gxq);
-    k_grad_nodes<<<grid1d((long long)G.P * G.V, 256), 256, 0, st>>>(G, ncell, ctx->gcount, ctx->grec, ctx->GT, ctx->glist, ctx->glist + 1);
-    k_grad_gather<<<ctx->n_cus * 8, 256, 0, st>>>(G, ncell, ctx->gcount, ctx->grec, ctx->glist, ctx->glist + 1, ctx->GT);
+                                                       ctx->gcount, pos, reinterpret_cast<float4 *>(ctx->grec), d_gxq);
+    if (N > 0) k_grad_pieces<<<grid1d((long long)lanes, PIECE_R), 64, 0, st>>>(G, ncp, ctx->gcount, ctx->grec);
+    // crowded grids: one thread per (node, adjacent cell); sparse ones: one thread per node
+    const long long nodes = (long long)G.P * G.V;
+    if ((long long)lanes >= 8 * nodes)
+        k_grad_nodes_p<8><<<grid1d(nodes * 8, 256), 256, 0, st>>>(G, ncell, ctx->gcount, ctx->grec, ctx->GT);
+    else
+        k_grad_nodes_p<1><<<grid1d(nodes, 256), 256, 0, st>>>(G, ncell, ctx->gcount, ctx->grec, ctx->GT);
     const size_t shB = sizeof(float) * G.P * G.nb * 12;
     k_grad_weights<<<grid1d(G.V * G.nb, 256), 256, shB, st>>>(G, ctx->GT, ctx->Bdev, d_gW);
     const int nout = G.nb * 12;

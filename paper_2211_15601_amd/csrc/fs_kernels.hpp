@@ -773,14 +773,16 @@ __global__ __launch_bounds__(256) void k_grad_count(GridP G, const float *__rest
     pos[q] = atomicAdd(count + p * ncell + cell_linear(G, c), 1);
 }
 
-// pass 2: one thread per point, all its lanes: lambda = -M^T g_x, record {x*, lambda} written to the
-// lane's slot of the cell-sorted list; dL/dx' = sum_k M^T g_x without atomics.
+// pass 2: one thread per point, all its lanes: lambda = -M^T g_x; the 32-byte record {x*[3], lambda[3],
+// cell, 0} goes to the lane's slot of the cell-sorted list (one aligned sector per record);
+// dL/dx' = sum_k M^T g_x without atomics.
+constexpr int GREC = 8;           // floats per record
 __global__ __launch_bounds__(256) void k_grad_records(GridP G, int mode, const float *__restrict__ T,
                                                       const float *__restrict__ xc, const float *__restrict__ Jinv,
                                                       const uint8_t *__restrict__ conv, const float *__restrict__ gxc,
                                                       const int32_t *__restrict__ pose, long long N, int K, int ncell,
                                                       const int *__restrict__ offset, const int *__restrict__ pos,
-                                                      float *__restrict__ rec, float *__restrict__ gxq)
+                                                      float4 *__restrict__ rec, float *__restrict__ gxq)
 {
     const long long n = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (n >= N) return;
@@ -813,11 +815,10 @@ __global__ __launch_bounds__(256) void k_grad_records(GridP G, int mode, const f
             }
         }
         const Cell c = locate(G, x);
-        const long long slot = (long long)offset[p * ncell + cell_linear(G, c)] + pos[q];
-        float2 *o = reinterpret_cast<float2 *>(rec + slot * 6);
-        o[0] = make_float2(x[0], x[1]);
-        o[1] = make_float2(x[2], lam[0]);
-        o[2] = make_float2(lam[1], lam[2]);
+        const int cl = p * ncell + cell_linear(G, c);
+        const long long slot = (long long)offset[cl] + pos[q];
+        rec[slot * 2] = make_float4(x[0], x[1], x[2], lam[0]);
+        rec[slot * 2 + 1] = make_float4(lam[1], lam[2], __int_as_float(cl), 0.0f);
     }
     if (gxq) {
 #pragma unroll
@@ -825,18 +826,14 @@ __global__ __launch_bounds__(256) void k_grad_records(GridP G, int mode, const f
     }
 }
 
-// pass 3a: one thread per (pose, node): nodes none of whose adjacent cells holds a lane get zeros at
-// once, nodes with a few lanes around them are summed by the thread itself, the others are appended
-// to a work list (one atomic per wave).
-constexpr int GRAD_LIGHT = 32;
-
+// contribution of sorted record s to the node that is corner (da, db, dc) of the record's cell
 __device__ __forceinline__ void grad_accumulate(const GridP &G, const float *__restrict__ rec, int s, int da, int db,
                                                 int dc, float (&acc)[12])
 {
-    const float2 *r = reinterpret_cast<const float2 *>(rec + (long long)s * 6);
-    const float2 r0 = r[0], r1 = r[1], r2 = r[2];
-    const float x[3] = {r0.x, r0.y, r1.x};
-    const float lam[3] = {r1.y, r2.x, r2.y};
+    const float4 *r = reinterpret_cast<const float4 *>(rec + (long long)s * GREC);
+    const float4 r0 = r[0], r1 = r[1];
+    const float x[3] = {r0.x, r0.y, r0.z};
+    const float lam[3] = {r0.w, r1.x, r1.y};
     const Cell c = locate(G, x);
     const float wx = da ? c.f[0] : 1.0f - c.f[0];
     const float wy = db ? c.f[1] : 1.0f - c.f[1];
@@ -859,97 +856,171 @@ __device__ __forceinline__ int adjacent_cell(const GridP &G, int ncell, int p, i
     return p * ncell + (cx * (G.ny - 1) + cy) * (G.nz - 1) + cz;
 }
 
-__global__ __launch_bounds__(256) void k_grad_nodes(GridP G, int ncell, const int *__restrict__ offset,
-                                                    const float *__restrict__ rec, float *__restrict__ GT,
-                                                    int *__restrict__ nactive, int *__restrict__ list)
+// pass 3.  The cell-sorted record list is cut at every multiple of PIECE_R; a piece is what one cell owns
+// of one such range.  A piece of at least PIECE_MIN records is replaced, in place, by its sums for the
+// 8 corners of the cell (8 x 12 floats = the storage of 12 records), so that a node later reads 12
+// floats per piece instead of every record of a crowded cell; shorter pieces stay as records.
+constexpr int PIECE_R = 256;
+constexpr int PIECE_MIN = 96 / GREC;
+constexpr int PIECE_RPL = PIECE_R / 64;   // records per SIMD lane when a wave scans its range
+
+// One wave per range.  Every record of the range is expanded once (SIMD lane = record) into its 8 corner
+// weights omega_c and its 12 products lambda_r [x*; 1]_j, staged in LDS; the sums of a piece are then the
+// matrix product  S[c][rj] = sum_t omega_c(t) * (lambda_r [x;1]_j)(t),  an 8 x len by len x 12 contraction,
+// taken four records at a time by the 16x16x4 fp32 MFMA (rows 8..15 and columns 12..15 are zero padding).
+// Operand layout of that instruction: lane 16k+i supplies A[i][k] and B[k][i]; lane 16g+j receives
+// D[4g+q][j] in accumulator register q.
+constexpr int PIECE_ROW = 20;     // floats per staged record: 8 weights + 12 products
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(64) void k_grad_pieces(GridP G, long long ncp, const int *__restrict__ offset, float *rec)
 {
-    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    const int lane = threadIdx.x & 63;
-    bool act = false;
-    if (i < (long long)G.P * G.V) {
-        const int p = (int)(i / G.V);
-        const long long v = i - (long long)p * G.V;
-        const int iz = (int)(v % G.nz), iy = (int)((v / G.nz) % G.ny), ix = (int)(v / ((long long)G.nz * G.ny));
-        int total = 0;
+    __shared__ float4 sm4[PIECE_R * PIECE_ROW / 4];
+    float *sm = reinterpret_cast<float *>(sm4);
+    const int lane = threadIdx.x;
+    const long long total = offset[ncp];
+    const long long s = (long long)blockIdx.x * PIECE_R;
+    if (s >= total) return;
+    const int e = (int)min((long long)PIECE_R, total - s);
+    // lane l looks at PIECE_RPL consecutive records of the range; a record starts a piece if its cell differs from
+    // the one before it (the first record of the range always does)
+    int c[PIECE_RPL];
 #pragma unroll
-        for (int cn = 0; cn < 8; ++cn) {
-            const int c = adjacent_cell(G, ncell, p, ix, iy, iz, cn);
-            if (c >= 0) total += offset[c + 1] - offset[c];
-        }
-        act = total > GRAD_LIGHT;
-        if (!act) {
-            float acc[12];
+    for (int i = 0; i < PIECE_RPL; ++i) c[i] = PIECE_RPL * lane + i < e ? __float_as_int(rec[(s + PIECE_RPL * lane + i) * GREC + 6]) : -1;
+    int prev = __shfl_up(c[PIECE_RPL - 1], 1);
+    if (lane == 0) prev = -2;
+    bool f[PIECE_RPL];
+    f[0] = PIECE_RPL * lane < e && c[0] != prev;
 #pragma unroll
-            for (int e = 0; e < 12; ++e) acc[e] = 0.0f;
-            if (total > 0) {
-                for (int cn = 0; cn < 8; ++cn) {
-                    const int c = adjacent_cell(G, ncell, p, ix, iy, iz, cn);
-                    if (c < 0) continue;
-                    const int end = offset[c + 1];
-                    for (int s = offset[c]; s < end; ++s) grad_accumulate(G, rec, s, cn & 1, (cn >> 1) & 1, (cn >> 2) & 1, acc);
-                }
-            }
-            float4 *o = reinterpret_cast<float4 *>(GT + i * 12);
-            o[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
-            o[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
-            o[2] = make_float4(acc[8], acc[9], acc[10], acc[11]);
-        }
+    for (int i = 1; i < PIECE_RPL; ++i) f[i] = PIECE_RPL * lane + i < e && c[i] != c[i - 1];
+    int first = e;
+#pragma unroll
+    for (int i = PIECE_RPL - 1; i >= 0; --i)
+        if (f[i]) first = PIECE_RPL * lane + i;
+    int suf = first;                    // first piece start in lanes >= this one
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int o = __shfl_down(suf, d);
+        if (lane + d < 64) suf = min(suf, o);
     }
-    const unsigned long long m = __ballot(act);
-    if (m) {
-        int base = 0;
-        if (lane == 0) base = atomicAdd(nactive, __popcll(m));
-        base = __shfl(base, 0);
-        if (act) list[base + __popcll(m & ((1ull << lane) - 1ull))] = (int)i;
+    int nxt = __shfl_down(suf, 1);      // ... in lanes after this one
+    if (lane == 63) nxt = e;
+    int len[PIECE_RPL];
+    bool any_long = false;
+#pragma unroll
+    for (int i = PIECE_RPL - 1; i >= 0; --i) {
+        len[i] = f[i] ? nxt - (PIECE_RPL * lane + i) : 0;
+        if (f[i]) nxt = PIECE_RPL * lane + i;
+        any_long = any_long || len[i] >= PIECE_MIN;
+    }
+    if (!__any(any_long)) return;       // nothing to summarise here (sparse lists end here)
+    // expand the records
+#pragma unroll
+    for (int b = 0; b < PIECE_R / 64; ++b) {
+        const int t = 64 * b + lane;
+        float4 o[5];
+#pragma unroll
+        for (int h = 0; h < 5; ++h) o[h] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (t < e) {
+            const float4 *r = reinterpret_cast<const float4 *>(rec + (s + t) * GREC);
+            const float4 r0 = r[0], r1 = r[1];
+            const float x[3] = {r0.x, r0.y, r0.z};
+            const float lam[3] = {r0.w, r1.x, r1.y};
+            const Cell cl = locate(G, x);
+            float om[8];
+            corner_weights(cl, om);
+            o[0] = make_float4(om[0], om[1], om[2], om[3]);
+            o[1] = make_float4(om[4], om[5], om[6], om[7]);
+#pragma unroll
+            for (int rr = 0; rr < 3; ++rr) o[2 + rr] = make_float4(lam[rr] * x[0], lam[rr] * x[1], lam[rr] * x[2], lam[rr]);
+        }
+#pragma unroll
+        for (int h = 0; h < 5; ++h) sm4[t * (PIECE_ROW / 4) + h] = o[h];
+    }
+    __syncthreads();
+    const int col = lane & 15, kq = lane >> 4;
+#pragma unroll
+    for (int i = 0; i < PIECE_RPL; ++i) {
+        unsigned long long m = __ballot(len[i] >= PIECE_MIN);
+        while (m) {
+            const int src = __ffsll((long long)m) - 1;
+            m &= m - 1ull;
+            const int ps = PIECE_RPL * src + i, pe = ps + __shfl(len[i], src);
+            // two accumulators so that consecutive MFMAs do not wait for each other
+            v4f acc = {0.0f, 0.0f, 0.0f, 0.0f}, acc2 = {0.0f, 0.0f, 0.0f, 0.0f};
+            const int g1 = (pe - 1) >> 2;
+            for (int g = ps >> 2; g <= g1; g += 2) {
+                const int t = 4 * g + kq, t2 = t + 4;
+                const bool in = t >= ps && t < pe, in2 = t2 >= ps && t2 < pe;      // t2 < pe <= PIECE_R
+                const float av = (in && col < 8) ? sm[t * PIECE_ROW + col] : 0.0f;
+                const float bv = (in && col < 12) ? sm[t * PIECE_ROW + 8 + col] : 0.0f;
+                const float av2 = (in2 && col < 8) ? sm[t2 * PIECE_ROW + col] : 0.0f;
+                const float bv2 = (in2 && col < 12) ? sm[t2 * PIECE_ROW + 8 + col] : 0.0f;
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bv, acc, 0, 0, 0);
+                acc2 = __builtin_amdgcn_mfma_f32_16x16x4f32(av2, bv2, acc2, 0, 0, 0);
+            }
+            acc += acc2;
+            if (kq < 2 && col < 12) {
+                float *o = rec + (s + ps) * GREC + (4 * kq) * 12 + col;
+                o[0] = acc[0];
+                o[12] = acc[1];
+                o[24] = acc[2];
+                o[36] = acc[3];
+            }
+        }
     }
 }
 
-// pass 3b: waves stride over the work list.  A node with few lanes around it is handled with 8 SIMD
-// lanes per adjacent cell (all 8 cells at once); one with many, cell after cell with the whole wave.
-// A butterfly reduction over the wave follows.
-__global__ __launch_bounds__(256) void k_grad_gather(GridP G, int ncell, const int *__restrict__ offset,
-                                                     const float *__restrict__ rec, const int *__restrict__ nactive,
-                                                     const int *__restrict__ list, float *__restrict__ GT)
+// G_T of every node from the pieces of its 8 adjacent cells; TPN threads share a node (1, or 8 = one
+// per adjacent cell followed by a butterfly sum).
+template <int TPN>
+__global__ __launch_bounds__(256) void k_grad_nodes_p(GridP G, int ncell, const int *__restrict__ offset,
+                                                      const float *__restrict__ rec, float *__restrict__ GT)
 {
-    const int lane = threadIdx.x & 63;
-    const int nwaves = (gridDim.x * blockDim.x) >> 6;
-    const int n = *nactive;
-    for (int w = (blockIdx.x * blockDim.x + threadIdx.x) >> 6; w < n; w += nwaves) {
-        const long long i = list[w];
-        const int p = (int)(i / G.V);
-        const long long v = i - (long long)p * G.V;
-        const int iz = (int)(v % G.nz), iy = (int)((v / G.nz) % G.ny), ix = (int)(v / ((long long)G.nz * G.ny));
-        float acc[12];
+    const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long i = t / TPN;
+    const int sub = (int)(t - i * TPN);
+    if (i >= (long long)G.P * G.V) return;
+    const int p = (int)(i / G.V);
+    const long long v = i - (long long)p * G.V;
+    const int iz = (int)(v % G.nz), iy = (int)((v / G.nz) % G.ny), ix = (int)(v / ((long long)G.nz * G.ny));
+    float acc[12];
 #pragma unroll
-        for (int e = 0; e < 12; ++e) acc[e] = 0.0f;
-        // lane 8c+j looks at adjacent cell c
-        const int mycn = lane >> 3;
-        const int mycell = adjacent_cell(G, ncell, p, ix, iy, iz, mycn);
-        const int mybeg = mycell >= 0 ? offset[mycell] : 0, myend = mycell >= 0 ? offset[mycell + 1] : 0;
-        int longest = myend - mybeg;
+    for (int e = 0; e < 12; ++e) acc[e] = 0.0f;
+    for (int cn = sub; cn < 8; cn += TPN) {
+        const int c = adjacent_cell(G, ncell, p, ix, iy, iz, cn);
+        if (c < 0) continue;
+        const int a = offset[c], b = offset[c + 1];
+        if (a == b) continue;
+        for (int j = a / PIECE_R; j <= (b - 1) / PIECE_R; ++j) {
+            const int ps = max(a, j * PIECE_R), pe = min(b, (j + 1) * PIECE_R);
+            if (pe - ps >= PIECE_MIN) {
+                const float4 *q = reinterpret_cast<const float4 *>(rec + (long long)ps * GREC + cn * 12);
 #pragma unroll
-        for (int s = 32; s >= 8; s >>= 1) longest = max(longest, __shfl_xor(longest, s));
-        if (longest <= 256) {
-            for (int s = mybeg + (lane & 7); s < myend; s += 8)
-                grad_accumulate(G, rec, s, mycn & 1, (mycn >> 1) & 1, (mycn >> 2) & 1, acc);
-        } else {
-            for (int cn = 0; cn < 8; ++cn) {
-                const int beg = __shfl(mybeg, cn * 8), end = __shfl(myend, cn * 8);
-                for (int s = beg + lane; s < end; s += WAVE)
-                    grad_accumulate(G, rec, s, cn & 1, (cn >> 1) & 1, (cn >> 2) & 1, acc);
+                for (int h = 0; h < 3; ++h) {
+                    const float4 u = q[h];
+                    acc[4 * h] += u.x;
+                    acc[4 * h + 1] += u.y;
+                    acc[4 * h + 2] += u.z;
+                    acc[4 * h + 3] += u.w;
+                }
+            } else {
+                for (int s = ps; s < pe; ++s) grad_accumulate(G, rec, s, cn & 1, (cn >> 1) & 1, (cn >> 2) & 1, acc);
             }
         }
+    }
+    if (TPN > 1) {
 #pragma unroll
         for (int e = 0; e < 12; ++e) {
 #pragma unroll
-            for (int s = 32; s >= 1; s >>= 1) acc[e] += __shfl_xor(acc[e], s);
+            for (int d = TPN >> 1; d >= 1; d >>= 1) acc[e] += __shfl_xor(acc[e], d);
         }
-        if (lane == 0) {
-            float4 *o = reinterpret_cast<float4 *>(GT + i * 12);
-            o[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
-            o[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
-            o[2] = make_float4(acc[8], acc[9], acc[10], acc[11]);
-        }
+    }
+    if (sub == 0) {
+        float4 *o = reinterpret_cast<float4 *>(GT + i * 12);
+        o[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        o[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+        o[2] = make_float4(acc[8], acc[9], acc[10], acc[11]);
     }
 }
 
