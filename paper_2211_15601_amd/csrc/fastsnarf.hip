@@ -534,9 +534,12 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
         if (N > 0) k_grad_count<<<grid1d((long long)N * K, 256), 256, 0, st>>>(G, d_xc, d_conv, d_pose, N, K, ncell, ctx->gcount, ctx->gpos);
     }
     { fs_status ss = scan_exclusive(ctx, (int)ncp, ctx->gcount, counts); if (ss != FS_OK) return ss; }
-    if (N > 0)
-        k_grad_records<<<grid1d(N, 256), 256, 0, st>>>(G, mode, ctx->T, d_xc, d_Jinv, d_conv, d_gxc, d_pose, N, K, ncell,
-                                                       ctx->gcount, pos, reinterpret_cast<float4 *>(ctx->grec), d_gxq);
+    if (N > 0) {
+        // small batches: several threads share a point's lanes so that the chip has enough threads in flight
+        const int groups = N >= (1 << 19) ? 1 : (K >= 8 ? 8 : (K >= 4 ? 4 : (K >= 2 ? 2 : 1)));
+        k_grad_records<<<grid1d(N, 256 / groups), 256, 0, st>>>(G, mode, ctx->T, d_xc, d_Jinv, d_conv, d_gxc, d_pose, N, K, ncell,
+                                                                ctx->gcount, pos, reinterpret_cast<float4 *>(ctx->grec), d_gxq, groups);
+    }
     if (N > 0) k_grad_pieces<<<grid1d((long long)lanes, PIECE_R), 64, 0, st>>>(G, ncp, ctx->gcount, ctx->grec);
     // crowded grids: one thread per (node, adjacent cell); sparse ones: one thread per node
     const long long nodes = (long long)G.P * G.V;

@@ -773,7 +773,7 @@ __global__ __launch_bounds__(256) void k_grad_count(GridP G, const float *__rest
     pos[q] = atomicAdd(count + p * ncell + cell_linear(G, c), 1);
 }
 
-// pass 2: one thread per point, all its lanes: lambda = -M^T g_x; the 32-byte record {x*[3], lambda[3],
+// pass 2: a few threads per point share its lanes: lambda = -M^T g_x; the 32-byte record {x*[3], lambda[3],
 // cell, 0} goes to the lane's slot of the cell-sorted list (one aligned sector per record);
 // dL/dx' = sum_k M^T g_x without atomics.
 constexpr int GREC = 8;           // floats per record
@@ -782,45 +782,58 @@ __global__ __launch_bounds__(256) void k_grad_records(GridP G, int mode, const f
                                                       const uint8_t *__restrict__ conv, const float *__restrict__ gxc,
                                                       const int32_t *__restrict__ pose, long long N, int K, int ncell,
                                                       const int *__restrict__ offset, const int *__restrict__ pos,
-                                                      float4 *__restrict__ rec, float *__restrict__ gxq)
+                                                      float4 *__restrict__ rec, float *__restrict__ gxq, int groups)
 {
-    const long long n = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (n >= N) return;
-    const int p = pose_of(pose, n, G.P);
+    // `groups` (a power of two <= 8) threads share a point and take its lanes k = g, g + groups, ...;
+    // consecutive threads of a group are consecutive points, so every load is coalesced
+    __shared__ float s_gq[256 * 3];
+    const int ppb = 256 / groups;                 // points per block
+    const int g = threadIdx.x / ppb, i = threadIdx.x - g * ppb;
+    const long long n = (long long)blockIdx.x * ppb + i;
     float gq[3] = {0.0f, 0.0f, 0.0f};
-    for (int k = 0; k < K; ++k) {
-        const long long q = (long long)k * N + n;
-        if (!conv[q]) continue;
-        float x[3], gx[3], M[9];
-#pragma unroll
-        for (int r = 0; r < 3; ++r) {
-            x[r] = xc[((long long)k * 3 + r) * N + n];
-            gx[r] = gxc[((long long)k * 3 + r) * N + n];
-        }
-        bool ok = true;
-        if (mode == 0) {
-#pragma unroll
-            for (int e = 0; e < 9; ++e) M[e] = Jinv[((long long)k * 9 + e) * N + n];
-        } else {
-            float d[3], J[9];
-            field_dJ(T + (long long)p * G.V * 12, G, x, d, J);
-            ok = inv3(J, M);
-        }
-        float lam[3] = {0.0f, 0.0f, 0.0f};
-        if (ok) {
+    if (n < N) {
+        const int p = pose_of(pose, n, G.P);
+        for (int k = g; k < K; k += groups) {
+            const long long q = (long long)k * N + n;
+            if (!conv[q]) continue;
+            float x[3], gx[3], M[9];
 #pragma unroll
             for (int r = 0; r < 3; ++r) {
-                lam[r] = -FS_FMA(M[6 + r], gx[2], FS_FMA(M[3 + r], gx[1], M[r] * gx[0]));
-                gq[r] -= lam[r];
+                x[r] = xc[((long long)k * 3 + r) * N + n];
+                gx[r] = gxc[((long long)k * 3 + r) * N + n];
             }
+            bool ok = true;
+            if (mode == 0) {
+#pragma unroll
+                for (int e = 0; e < 9; ++e) M[e] = Jinv[((long long)k * 9 + e) * N + n];
+            } else {
+                float d[3], J[9];
+                field_dJ(T + (long long)p * G.V * 12, G, x, d, J);
+                ok = inv3(J, M);
+            }
+            float lam[3] = {0.0f, 0.0f, 0.0f};
+            if (ok) {
+#pragma unroll
+                for (int r = 0; r < 3; ++r) {
+                    lam[r] = -FS_FMA(M[6 + r], gx[2], FS_FMA(M[3 + r], gx[1], M[r] * gx[0]));
+                    gq[r] -= lam[r];
+                }
+            }
+            const Cell c = locate(G, x);
+            const int cl = p * ncell + cell_linear(G, c);
+            const long long slot = (long long)offset[cl] + pos[q];
+            rec[slot * 2] = make_float4(x[0], x[1], x[2], lam[0]);
+            rec[slot * 2 + 1] = make_float4(lam[1], lam[2], __int_as_float(cl), 0.0f);
         }
-        const Cell c = locate(G, x);
-        const int cl = p * ncell + cell_linear(G, c);
-        const long long slot = (long long)offset[cl] + pos[q];
-        rec[slot * 2] = make_float4(x[0], x[1], x[2], lam[0]);
-        rec[slot * 2 + 1] = make_float4(lam[1], lam[2], __int_as_float(cl), 0.0f);
     }
-    if (gxq) {
+    if (!gxq) return;
+#pragma unroll
+    for (int r = 0; r < 3; ++r) s_gq[threadIdx.x * 3 + r] = gq[r];
+    __syncthreads();
+    if (g == 0 && n < N) {
+        for (int h = 1; h < groups; ++h)
+#pragma unroll
+            for (int r = 0; r < 3; ++r) gq[r] += s_gq[(h * ppb + i) * 3 + r];
 #pragma unroll
         for (int r = 0; r < 3; ++r) gxq[r * N + n] = gq[r];
     }
