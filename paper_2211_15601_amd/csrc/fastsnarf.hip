@@ -46,7 +46,7 @@ struct fs_ctx {
     int *gpos;         // [K*N] position of a lane inside its cell's list (grows on demand)
     float *grec;       // [K*N][8] cell-sorted {x*, lambda, cell} records (grows on demand)
     size_t gcap;       // lanes gpos / grec can hold
-    float *gpart;      // [P][gb_blocks][nb*12] partial sums of dL/dB
+    float *gpart;      // [P][gb_blocks][nb*12] partial sums of dL/dB, one per block of k_grad_bones_mfma
     int gb_blocks;
     float4 *srec;      // per-pair result records of the solve kernel (grows on demand)
     size_t srec_cap;   // float4 entries srec can hold
@@ -509,7 +509,7 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
     if (!ctx->GT && !dev_alloc(&ctx->GT, (size_t)G.P * G.V * 12)) return fail(ctx, FS_E_ALLOC, "fs_grad: out of device memory");
     if (!ctx->gcount && !dev_alloc(&ctx->gcount, (size_t)ncp + 1)) return fail(ctx, FS_E_ALLOC, "fs_grad: out of device memory");
     if (!ctx->gpart) {
-        ctx->gb_blocks = (int)std::min<long long>(grid1d(G.V, GB_TILE), 256);
+        ctx->gb_blocks = (int)std::min<long long>(grid1d(G.V, 256), 1024);      // 4 waves each, >= 16 node quads per wave
         if (!dev_alloc(&ctx->gpart, (size_t)G.P * ctx->gb_blocks * G.nb * 12)) return fail(ctx, FS_E_ALLOC, "fs_grad: out of device memory");
     }
     const size_t lanes = (size_t)N * K;
@@ -547,10 +547,15 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
         k_grad_nodes_p<8><<<grid1d(nodes * 8, 256), 256, 0, st>>>(G, ncell, ctx->gcount, ctx->grec, ctx->GT);
     else
         k_grad_nodes_p<1><<<grid1d(nodes, 256), 256, 0, st>>>(G, ncell, ctx->gcount, ctx->grec, ctx->GT);
-    const size_t shB = sizeof(float) * G.P * G.nb * 12;
-    k_grad_weights<<<grid1d(G.V * G.nb, 256), 256, shB, st>>>(G, ctx->GT, ctx->Bdev, d_gW);
-    const int nout = G.nb * 12;
-    k_grad_bones_partial<<<dim3(ctx->gb_blocks, G.P), 256, sizeof(float) * GB_TILE * (G.nb + 12), st>>>(G, d_W, ctx->GT, ctx->gpart);
+    k_grad_weights_node<<<grid1d(G.V * ((G.nb + 7) / 8), 256), 256, sizeof(float) * G.P * G.nb * 12, st>>>(G, ctx->GT, ctx->Bdev, d_gW);
+    const int nout = G.nb * 12, nparts = ctx->gb_blocks * 4;
+    const dim3 gbg(ctx->gb_blocks, (G.P + GB_POSES - 1) / GB_POSES);
+    switch ((G.nb + 15) / 16) {
+    case 1: k_grad_bones_mfma<1><<<gbg, 256, 0, st>>>(G, d_W, ctx->GT, ctx->gpart, nparts); break;
+    case 2: k_grad_bones_mfma<2><<<gbg, 256, 0, st>>>(G, d_W, ctx->GT, ctx->gpart, nparts); break;
+    case 3: k_grad_bones_mfma<3><<<gbg, 256, 0, st>>>(G, d_W, ctx->GT, ctx->gpart, nparts); break;
+    default: k_grad_bones_mfma<4><<<gbg, 256, 0, st>>>(G, d_W, ctx->GT, ctx->gpart, nparts); break;
+    }
     k_grad_bones_final<<<G.P * nout, 64, 0, st>>>(G.P, ctx->gb_blocks, nout, ctx->gpart, d_gB);
     return launch_status(ctx, "fs_grad");
 }

@@ -1037,69 +1037,125 @@ __global__ __launch_bounds__(256) void k_grad_nodes_p(GridP G, int ncell, const 
     }
 }
 
-// gW[v][b] = sum_p sum_e G_T[p][v][e] B[p][b][e]; one thread per output, bones fastest so that the
-// threads of a node share its G_T record through the cache and the store is coalesced.
-__global__ __launch_bounds__(256) void k_grad_weights(GridP G, const float *__restrict__ GT,
-                                                      const float *__restrict__ B, float *__restrict__ gW)
+// gW[v][b] = sum_p sum_e G_T[p][v][e] B[p][b][e]: one thread per node and group of 8 bones (groups of a node
+// in neighbouring threads, so the node's G_T records come from the same cache lines and the stores are
+// contiguous); the bone transforms are staged in LDS.
+__global__ __launch_bounds__(256) void k_grad_weights_node(GridP G, const float *__restrict__ GT,
+                                                           const float *__restrict__ B, float *__restrict__ gW)
 {
     extern __shared__ float sB[];
     const int nB = G.P * G.nb * 12;
     for (int i = threadIdx.x; i < nB; i += blockDim.x) sB[i] = B[i];
     __syncthreads();
-    const long long o = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (o >= G.V * G.nb) return;
-    const long long v = o / G.nb;
-    const int b = (int)(o - v * G.nb);
-    float acc = 0.0f;
+    const int nch = (G.nb + 7) / 8;
+    const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long v = t / nch;
+    const int b0 = (int)(t - v * nch) * 8;
+    if (v >= G.V) return;
+    float acc[8];
+#pragma unroll
+    for (int bb = 0; bb < 8; ++bb) acc[bb] = 0.0f;
     for (int p = 0; p < G.P; ++p) {
         float gt[12];
         load12(GT + ((long long)p * G.V + v) * 12, gt);
 #pragma unroll
-        for (int e = 0; e < 12; ++e) acc = FS_FMA(gt[e], sB[(p * G.nb + b) * 12 + e], acc);
-    }
-    gW[o] = acc;
-}
-
-// gB[p][b][e] = sum_v W[v][b] G_T[p][v][e] in two stages without atomics: blocks stride over tiles of
-// nodes and write one partial sum per output, then one thread per output adds the partials.
-constexpr int GB_TILE = 128;
-constexpr int GB_MAX_OUT = 3;     // outputs per thread: n_bones * 12 <= 768 = 3 * 256
-__global__ __launch_bounds__(256) void k_grad_bones_partial(GridP G, const float *__restrict__ W,
-                                                            const float *__restrict__ GT, float *__restrict__ part)
-{
-    extern __shared__ float sm[];              // sW [GB_TILE][nb] then sG [GB_TILE][12]
-    float *sW = sm;
-    float *sG = sm + GB_TILE * G.nb;
-    const int p = blockIdx.y;
-    const int nout = G.nb * 12;
-    const int ntiles = (int)((G.V + GB_TILE - 1) / GB_TILE);
-    float acc[GB_MAX_OUT] = {0.0f, 0.0f, 0.0f};
-    for (int t = blockIdx.x; t < ntiles; t += gridDim.x) {
-        const long long v0 = (long long)t * GB_TILE;
-        const int cnt = (int)min((long long)GB_TILE, G.V - v0);
-        __syncthreads();
-        for (int i = threadIdx.x; i < cnt * G.nb; i += blockDim.x) sW[i] = W[v0 * G.nb + i];
-        for (int i = threadIdx.x; i < cnt * 12; i += blockDim.x) sG[i] = GT[((long long)p * G.V + v0) * 12 + i];
-        __syncthreads();
+        for (int bb = 0; bb < 8; ++bb) {
+            if (b0 + bb < G.nb) {
+                const float4 *Bp = reinterpret_cast<const float4 *>(sB + ((long long)p * G.nb + b0 + bb) * 12);
+                const float4 u0 = Bp[0], u1 = Bp[1], u2 = Bp[2];
+                const float bq[12] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w, u2.x, u2.y, u2.z, u2.w};
 #pragma unroll
-        for (int u = 0; u < GB_MAX_OUT; ++u) {
-            const int o = threadIdx.x + u * 256;
-            if (o < nout) {
-                const int b = o / 12, e = o - b * 12;
-                float a = acc[u];
-                for (int i = 0; i < cnt; ++i) a = FS_FMA(sW[i * G.nb + b], sG[i * 12 + e], a);
-                acc[u] = a;
+                for (int e = 0; e < 12; ++e) acc[bb] = FS_FMA(gt[e], bq[e], acc[bb]);
             }
         }
     }
+    float *o = gW + v * G.nb + b0;
+    if ((G.nb & 3) == 0 && b0 + 8 <= G.nb) {
+        reinterpret_cast<float4 *>(o)[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        reinterpret_cast<float4 *>(o)[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+    } else {
 #pragma unroll
-    for (int u = 0; u < GB_MAX_OUT; ++u) {
-        const int o = threadIdx.x + u * 256;
-        if (o < nout) part[((long long)p * gridDim.x + blockIdx.x) * nout + o] = acc[u];
+        for (int bb = 0; bb < 8; ++bb)
+            if (b0 + bb < G.nb) o[bb] = acc[bb];
     }
 }
 
-// one wave per output adds that output's partial sums
+// gB[p][b][e] = sum_v W[v][b] G_T[p][v][e]: per pose an n_b x V by V x 12 product with a long inner dimension.
+// Each wave walks its share of the nodes four at a time with the 16x16x4 fp32 MFMA (A = 16 bones x 4 nodes of
+// W^T, B = 4 nodes x 12 entries of G_T), up to 8 poses against the same weights; a block of 4 waves writes one
+// partial result [n_b][12] per pose (part[p][block]) and k_grad_bones_final adds the partials.  MT = number of 16-bone tiles.
+constexpr int GB_POSES = 8;
+template <int MT>
+__global__ __launch_bounds__(256) void k_grad_bones_mfma(GridP G, const float *__restrict__ W,
+                                                         const float *__restrict__ GT, float *__restrict__ part,
+                                                         int nparts)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;      // < nparts
+    const int p0 = blockIdx.y * GB_POSES;
+    const int np = min(GB_POSES, G.P - p0);
+    const int col = lane & 15, kq = lane >> 4;
+    const long long quads = (G.V + 3) / 4;
+    v4f acc[GB_POSES][MT];
+#pragma unroll
+    for (int pc = 0; pc < GB_POSES; ++pc)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[pc][mt] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+    // two node quads per pass: their loads are in flight together
+    for (long long q = wave; q < quads; q += 2ll * nparts) {
+        const long long v = q * 4 + kq, v2 = (q + nparts) * 4 + kq;
+        const bool inv = v < G.V, inv2 = v2 < G.V;
+        float a[MT], a2[MT], bv[GB_POSES], bv2[GB_POSES];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            a[mt] = (inv && mt * 16 + col < G.nb) ? W[v * G.nb + mt * 16 + col] : 0.0f;
+            a2[mt] = (inv2 && mt * 16 + col < G.nb) ? W[v2 * G.nb + mt * 16 + col] : 0.0f;
+        }
+#pragma unroll
+        for (int pc = 0; pc < GB_POSES; ++pc) {
+            bv[pc] = (pc < np && inv && col < 12) ? GT[((long long)(p0 + pc) * G.V + v) * 12 + col] : 0.0f;
+            bv2[pc] = (pc < np && inv2 && col < 12) ? GT[((long long)(p0 + pc) * G.V + v2) * 12 + col] : 0.0f;
+        }
+#pragma unroll
+        for (int pc = 0; pc < GB_POSES; ++pc) {
+            if (pc < np) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    acc[pc][mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[mt], bv[pc], acc[pc][mt], 0, 0, 0);
+                    acc[pc][mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[mt], bv2[pc], acc[pc][mt], 0, 0, 0);
+                }
+            }
+        }
+    }
+    // the block's 4 waves add their results in LDS, pose by pose; wave 0 writes the block's partial
+    __shared__ v4f s_acc[3][MT][64];
+    const int nout = G.nb * 12, wib = threadIdx.x >> 6;
+#pragma unroll
+    for (int pc = 0; pc < GB_POSES; ++pc) {
+        if (pc < np) {                                  // np is the same for the whole block
+            if (wib > 0) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) s_acc[wib - 1][mt][lane] = acc[pc][mt];
+            }
+            __syncthreads();
+            if (wib == 0) {
+                float *o = part + ((long long)(p0 + pc) * gridDim.x + blockIdx.x) * nout;
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    const v4f t = acc[pc][mt] + s_acc[0][mt][lane] + s_acc[1][mt][lane] + s_acc[2][mt][lane];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int b = mt * 16 + 4 * kq + r;
+                        if (b < G.nb && col < 12) o[b * 12 + col] = t[r];
+                    }
+                }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// sum of the per-block partial results of k_grad_bones_mfma: one wave per output
 __global__ __launch_bounds__(64) void k_grad_bones_final(int P, int nblk, int nout, const float *__restrict__ part,
                                                          float *__restrict__ gB)
 {
