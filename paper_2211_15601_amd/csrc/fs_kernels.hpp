@@ -891,54 +891,66 @@ __global__ __launch_bounds__(64) void k_grad_pieces(GridP G, long long ncp, cons
     __shared__ float4 sm4[PIECE_R * PIECE_ROW / 4];
     float *sm = reinterpret_cast<float *>(sm4);
     const int lane = threadIdx.x;
-    const long long total = offset[ncp];
     const long long s = (long long)blockIdx.x * PIECE_R;
+    const long long total = offset[ncp];
     if (s >= total) return;
     const int e = (int)min((long long)PIECE_R, total - s);
-    // lane l looks at PIECE_RPL consecutive records of the range; a record starts a piece if its cell differs from
-    // the one before it (the first record of the range always does)
-    int c[PIECE_RPL];
+    // SIMD lane l holds records l, 64 + l, 128 + l, ... of the range
+    float4 r0[PIECE_RPL], r1[PIECE_RPL];
 #pragma unroll
-    for (int i = 0; i < PIECE_RPL; ++i) c[i] = PIECE_RPL * lane + i < e ? __float_as_int(rec[(s + PIECE_RPL * lane + i) * GREC + 6]) : -1;
-    int prev = __shfl_up(c[PIECE_RPL - 1], 1);
-    if (lane == 0) prev = -2;
-    bool f[PIECE_RPL];
-    f[0] = PIECE_RPL * lane < e && c[0] != prev;
-#pragma unroll
-    for (int i = 1; i < PIECE_RPL; ++i) f[i] = PIECE_RPL * lane + i < e && c[i] != c[i - 1];
-    int first = e;
-#pragma unroll
-    for (int i = PIECE_RPL - 1; i >= 0; --i)
-        if (f[i]) first = PIECE_RPL * lane + i;
-    int suf = first;                    // first piece start in lanes >= this one
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const int o = __shfl_down(suf, d);
-        if (lane + d < 64) suf = min(suf, o);
+    for (int b = 0; b < PIECE_RPL; ++b) {
+        r0[b] = r1[b] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (64 * b + lane < e) {
+            const float4 *r = reinterpret_cast<const float4 *>(rec + (s + 64 * b + lane) * GREC);
+            r0[b] = r[0];
+            r1[b] = r[1];
+        }
     }
-    int nxt = __shfl_down(suf, 1);      // ... in lanes after this one
-    if (lane == 63) nxt = e;
+    // a record starts a piece if its cell differs from the one before it (the first of the range always does)
+    int c[PIECE_RPL];
+    bool f[PIECE_RPL];
+#pragma unroll
+    for (int b = 0; b < PIECE_RPL; ++b) c[b] = 64 * b + lane < e ? __float_as_int(r1[b].z) : -1;
+#pragma unroll
+    for (int b = 0; b < PIECE_RPL; ++b) {
+        int prev = __shfl_up(c[b], 1);
+        if (lane == 0) prev = -2;
+        if (b > 0) {
+            const int last = __shfl(c[b - 1], 63);
+            if (lane == 0) prev = last;
+        }
+        f[b] = 64 * b + lane < e && c[b] != prev;
+    }
+    // next piece start after each record: suffix minimum of the start positions, batch by batch from the end
     int len[PIECE_RPL];
+    int later = e;                       // first piece start in later batches
     bool any_long = false;
 #pragma unroll
-    for (int i = PIECE_RPL - 1; i >= 0; --i) {
-        len[i] = f[i] ? nxt - (PIECE_RPL * lane + i) : 0;
-        if (f[i]) nxt = PIECE_RPL * lane + i;
-        any_long = any_long || len[i] >= PIECE_MIN;
+    for (int b = PIECE_RPL - 1; b >= 0; --b) {
+        int suf = f[b] ? 64 * b + lane : e;          // first start in lanes >= this one of batch b
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int o = __shfl_down(suf, d);
+            if (lane + d < 64) suf = min(suf, o);
+        }
+        int nxt = __shfl_down(suf, 1);               // ... in lanes after this one
+        if (lane == 63) nxt = e;
+        nxt = min(nxt, later);
+        len[b] = f[b] ? nxt - (64 * b + lane) : 0;
+        any_long = any_long || len[b] >= PIECE_MIN;
+        later = min(later, __shfl(suf, 0));
     }
     if (!__any(any_long)) return;       // nothing to summarise here (sparse lists end here)
     // expand the records
 #pragma unroll
-    for (int b = 0; b < PIECE_R / 64; ++b) {
+    for (int b = 0; b < PIECE_RPL; ++b) {
         const int t = 64 * b + lane;
         float4 o[5];
 #pragma unroll
         for (int h = 0; h < 5; ++h) o[h] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         if (t < e) {
-            const float4 *r = reinterpret_cast<const float4 *>(rec + (s + t) * GREC);
-            const float4 r0 = r[0], r1 = r[1];
-            const float x[3] = {r0.x, r0.y, r0.z};
-            const float lam[3] = {r0.w, r1.x, r1.y};
+            const float x[3] = {r0[b].x, r0[b].y, r0[b].z};
+            const float lam[3] = {r0[b].w, r1[b].x, r1[b].y};
             const Cell cl = locate(G, x);
             float om[8];
             corner_weights(cl, om);
@@ -958,21 +970,26 @@ __global__ __launch_bounds__(64) void k_grad_pieces(GridP G, long long ncp, cons
         while (m) {
             const int src = __ffsll((long long)m) - 1;
             m &= m - 1ull;
-            const int ps = PIECE_RPL * src + i, pe = ps + __shfl(len[i], src);
-            // two accumulators so that consecutive MFMAs do not wait for each other
-            v4f acc = {0.0f, 0.0f, 0.0f, 0.0f}, acc2 = {0.0f, 0.0f, 0.0f, 0.0f};
+            const int ps = 64 * i + src, pe = ps + __shfl(len[i], src);
+            // four groups per pass into four accumulators: their LDS reads are in flight together and no
+            // MFMA waits for the one before it; records outside the piece enter as zeros
+            v4f acc4[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc4[u] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
             const int g1 = (pe - 1) >> 2;
-            for (int g = ps >> 2; g <= g1; g += 2) {
-                const int t = 4 * g + kq, t2 = t + 4;
-                const bool in = t >= ps && t < pe, in2 = t2 >= ps && t2 < pe;      // t2 < pe <= PIECE_R
-                const float av = (in && col < 8) ? sm[t * PIECE_ROW + col] : 0.0f;
-                const float bv = (in && col < 12) ? sm[t * PIECE_ROW + 8 + col] : 0.0f;
-                const float av2 = (in2 && col < 8) ? sm[t2 * PIECE_ROW + col] : 0.0f;
-                const float bv2 = (in2 && col < 12) ? sm[t2 * PIECE_ROW + 8 + col] : 0.0f;
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bv, acc, 0, 0, 0);
-                acc2 = __builtin_amdgcn_mfma_f32_16x16x4f32(av2, bv2, acc2, 0, 0, 0);
+            for (int g = ps >> 2; g <= g1; g += 4) {
+                float av[4], bv[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int t = 4 * (g + u) + kq;
+                    const bool in = t >= ps && t < pe;          // pe <= PIECE_R
+                    av[u] = (in && col < 8) ? sm[t * PIECE_ROW + col] : 0.0f;
+                    bv[u] = (in && col < 12) ? sm[t * PIECE_ROW + 8 + col] : 0.0f;
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) acc4[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u], bv[u], acc4[u], 0, 0, 0);
             }
-            acc += acc2;
+            const v4f acc = (acc4[0] + acc4[1]) + (acc4[2] + acc4[3]);
             if (kq < 2 && col < 12) {
                 float *o = rec + (s + ps) * GREC + (4 * kq) * 12 + col;
                 o[0] = acc[0];
