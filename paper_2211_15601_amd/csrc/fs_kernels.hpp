@@ -247,18 +247,41 @@ __global__ void k_corr_bbox(int P, const unsigned *__restrict__ bb_ord, float *_
     if (i < P * 6) bbox[i] = ord2f(bb_ord[i]);
 }
 
+// Neighbouring nodes have neighbouring images, so the 64 nodes of a wave fall into a handful of cells: the
+// lanes of a wave that share a cell are counted together and one of them adds the group to the cell's
+// counter (device-scope atomics are executed outside the L2 and are the cost of this kernel).
 __global__ __launch_bounds__(256) void k_corr_count(GridP G, CorrP C, const float *__restrict__ Y,
                                                     const float *__restrict__ bbox, int *__restrict__ cell_of,
                                                     int *__restrict__ count, int *__restrict__ slot)
 {
     const long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     const int p = blockIdx.y;
-    if (v >= G.V) return;
-    const float *yp = Y + ((long long)p * G.V + v) * 3;
-    const float y[3] = {yp[0], yp[1], yp[2]};
-    const int c = cell_index(C, bbox + p * 6, y);
-    cell_of[(long long)p * G.V + v] = c;
-    slot[(long long)p * G.V + v] = atomicAdd(count + p * C.ncell + c, 1);    // arrival order inside the cell
+    const int lane = threadIdx.x & 63;
+    const bool valid = v < G.V;
+    int c = -1;
+    if (valid) {
+        const float *yp = Y + ((long long)p * G.V + v) * 3;
+        const float y[3] = {yp[0], yp[1], yp[2]};
+        c = cell_index(C, bbox + p * 6, y);
+        cell_of[(long long)p * G.V + v] = c;
+    }
+    int leader = lane, rank = 0, members = 1;
+    unsigned long long todo = __ballot(valid);
+    while (todo) {
+        const int first = __ffsll((long long)todo) - 1;
+        const int key = __shfl(c, first);
+        const unsigned long long same = __ballot(valid && c == key);
+        if (valid && c == key) {
+            leader = first;
+            rank = __popcll(same & ((1ull << lane) - 1ull));
+            members = __popcll(same);
+        }
+        todo &= ~same;
+    }
+    int base = 0;
+    if (valid && leader == lane) base = atomicAdd(count + p * C.ncell + c, members);
+    base = __shfl(base, leader);
+    if (valid) slot[(long long)p * G.V + v] = base + rank;      // a position inside the cell's list
 }
 
 // Exclusive prefix sum of a[0..n) in place, a[n] = total.  Three launches: per-tile sums (tile = 4096
