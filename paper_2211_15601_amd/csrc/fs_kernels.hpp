@@ -37,38 +37,49 @@ __global__ __launch_bounds__(256) void k_precompute(GridP G, const float *__rest
     if (v >= G.V) return;
     const float *w = W + v * G.nb;
     const bool vec = (G.nb & 3) == 0;        // weight rows are 16-byte aligned: read them four at a time
-    for (int p = 0; p < G.P; ++p) {
-        const float *Bp = B + (long long)p * G.nb * 12;
-        float acc[12];
-        if (vec) {
-            for (int b0 = 0; b0 < G.nb; b0 += 4) {
+    // four poses share one pass over the node's weights; per pose the sum runs over the bones in order,
+    // first term a product, the rest fused multiply-adds
+    for (int p0 = 0; p0 < G.P; p0 += 4) {
+        const int np = min(4, G.P - p0);
+        float acc[4][12];
+        for (int b0 = 0; b0 < G.nb; b0 += 4) {
+            float wv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (vec) {
                 const float4 w4 = *reinterpret_cast<const float4 *>(w + b0);
-                const float wv[4] = {w4.x, w4.y, w4.z, w4.w};
+                wv[0] = w4.x; wv[1] = w4.y; wv[2] = w4.z; wv[3] = w4.w;
+            } else {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    if (b0 == 0 && j == 0) {
+                for (int j = 0; j < 4; ++j)
+                    if (b0 + j < G.nb) wv[j] = w[b0 + j];
+            }
 #pragma unroll
-                        for (int e = 0; e < 12; ++e) acc[e] = wv[0] * Bp[e];
-                    } else {
+            for (int q = 0; q < 4; ++q) {
+                if (q < np) {
+                    const float *Bp = B + (long long)(p0 + q) * G.nb * 12;
 #pragma unroll
-                        for (int e = 0; e < 12; ++e) acc[e] = FS_FMA(wv[j], Bp[(b0 + j) * 12 + e], acc[e]);
+                    for (int j = 0; j < 4; ++j) {
+                        if (b0 + j < G.nb) {
+                            if (b0 == 0 && j == 0) {
+#pragma unroll
+                                for (int e = 0; e < 12; ++e) acc[q][e] = wv[0] * Bp[e];
+                            } else {
+#pragma unroll
+                                for (int e = 0; e < 12; ++e) acc[q][e] = FS_FMA(wv[j], Bp[(b0 + j) * 12 + e], acc[q][e]);
+                            }
+                        }
                     }
                 }
             }
-        } else {
-            const float w0 = w[0];
+        }
 #pragma unroll
-            for (int e = 0; e < 12; ++e) acc[e] = w0 * Bp[e];
-            for (int b = 1; b < G.nb; ++b) {
-                const float wb = w[b];
-#pragma unroll
-                for (int e = 0; e < 12; ++e) acc[e] = FS_FMA(wb, Bp[b * 12 + e], acc[e]);
+        for (int q = 0; q < 4; ++q) {
+            if (q < np) {
+                float4 *o = reinterpret_cast<float4 *>(T + ((long long)(p0 + q) * G.V + v) * 12);
+                o[0] = make_float4(acc[q][0], acc[q][1], acc[q][2], acc[q][3]);
+                o[1] = make_float4(acc[q][4], acc[q][5], acc[q][6], acc[q][7]);
+                o[2] = make_float4(acc[q][8], acc[q][9], acc[q][10], acc[q][11]);
             }
         }
-        float4 *o = reinterpret_cast<float4 *>(T + ((long long)p * G.V + v) * 12);
-        o[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
-        o[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
-        o[2] = make_float4(acc[8], acc[9], acc[10], acc[11]);
     }
 }
 
