@@ -220,6 +220,38 @@ def test_autograd_hook_matches_oracle_gradient(lib):
         assert np.linalg.norm(a - b) / np.linalg.norm(b) < 2e-5
 
 
+@pytest.mark.parametrize("shape", [((2, 2, 2), 1, 1, 40), ((5, 4, 3), 5, 3, 1000), ((7, 3, 9), 17, 2, 777),
+                                   ((4, 6, 5), 33, 1, 513), ((3, 3, 3), 64, 2, 300), ((9, 8, 7), 3, 4, 20011)],
+                         ids=lambda t: f"g{t[0]}-b{t[1]}-p{t[2]}-n{t[3]}")
+def test_odd_shapes_full_path(lib, shape):
+    # bone counts on both sides of the 16-bone MFMA tiles and of the 4-wide weight reads, grids down to one cell,
+    # several poses, ragged N: transform grid, solve and both gradient paths against the oracle
+    dims, nb, P, n = shape
+    s = wl.random_affine_scene(100 + nb, dims=dims, n_bones=nb, n_poses=P, n_points=n)
+    w = wl.Workload("odd", s["dims"], nb, P, s["lo"], s["hi"], s["W"], s["B"], s["x"], s["pose"], s["x"],
+                    1e-5, 10.0, 50, wl.INIT_BONE, nb, (4, 4, 4, 3))
+    pose = w.pose if P > 1 else None
+    run = gu.GpuRun(w)
+    T = run.precompute()
+    T_ref = oracle.precompute(w.dims, w.W, w.B, prec="f32")
+    np.testing.assert_array_equal(T.view(np.uint32), T_ref.view(np.uint32))
+    xc, cv, Jo, it = run.solve(fused=True, slots=True)
+    x0r, J0r, v0r = gu.oracle_inits(w, T_ref)
+    oxc, ocv, oJ, oit = gu.oracle_solve(w, T_ref, x0r, J0r, v0r)
+    np.testing.assert_array_equal(cv, ocv)
+    np.testing.assert_array_equal(it, oit)
+    np.testing.assert_array_equal(xc.view(np.uint32), oxc.view(np.uint32))
+    np.testing.assert_array_equal(Jo.view(np.uint32), oJ.view(np.uint32))
+    assert cv.sum() > 0
+    gxc = np.random.default_rng(5).standard_normal(xc.shape).astype(np.float32)
+    rW, rB, rq = oracle.grad(w.dims, w.lo, w.hi, T_ref, w.W, w.B, oxc, oJ, ocv, gxc, pose=pose, mode=0, prec="f64")
+    for slot in (run.slot, None):
+        gW, gB, gxq = run.grad(xc, Jo, cv, gxc, slot=slot)
+        for name, a, b in (("gW", gW, rW), ("gB", gB, rB), ("gxq", gxq, rq)):
+            rel = np.linalg.norm(a.astype(np.float64) - b) / max(np.linalg.norm(b), 1e-30)
+            assert np.isfinite(a).all() and rel < 2e-5, (name, rel, slot is None)
+
+
 def test_one_hot_weights_closed_form_on_gpu(lib):
     # one-hot weights: root = B_k^{-1} x' for every lane, at most two steps
     s = wl.random_affine_scene(41, dims=(5, 4, 3), n_bones=4, n_points=333)
