@@ -855,7 +855,11 @@ __global__ __launch_bounds__(256) void k_grad_records(GridP G, int mode, const f
             }
             const Cell c = locate(G, x);
             const int cl = p * ncell + cell_linear(G, c);
-            const long long slot = (long long)offset[cl] + pos[q];
+            const int pq = pos[q];
+            const long long slot = (long long)offset[cl] + pq;
+            // positions that do not belong to these roots (a caller mixing arrays of different solves)
+            // must not send the store outside the cell's part of the list
+            if (pq < 0 || slot >= offset[cl + 1]) continue;
             rec[slot * 2] = make_float4(x[0], x[1], x[2], lam[0]);
             rec[slot * 2 + 1] = make_float4(lam[1], lam[2], __int_as_float(cl), 0.0f);
         }

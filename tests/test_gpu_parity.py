@@ -142,6 +142,12 @@ def test_grad_with_slots_from_solve(lib, case):
     # and the counting path gives the same result on the same inputs
     cW, cB, cq = run.grad(xc, Jo, cv, gxc)
     assert np.linalg.norm(cW.astype(np.float64) - rW) / np.linalg.norm(rW) < 2e-5
+    # positions that do not belong to these roots (here: none at all) stay inside the library's buffers: the call
+    # completes, and the next correct call is unaffected
+    bad = torch.full_like(run.slot, -1)
+    run.grad(xc, Jo, cv, gxc, slot=bad)
+    gW, gB, gxq = run.grad(xc, Jo, cv, gxc, slot=run.slot)
+    assert np.linalg.norm(gW.astype(np.float64) - rW) / np.linalg.norm(rW) < 2e-5
     # slots of another solve (different N) are refused
     small = wl.make_config(cfg, n_points=64, dims=w.dims, n_poses=P)
     xq2 = gu.dev(small.xq)
