@@ -141,8 +141,9 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
  *        pass that sorts the lanes by grid cell then reuses the solve's counts instead of counting
  *        again.  The sums are the same up to the order of the fp32 additions.
  *   out: d_gW [nx][ny][nz][n_bones] = dL/dW (summed over poses), d_gB [n_poses][n_bones][12],
- *        d_gxq [3][N] = dL/dx' (may be NULL).  Outputs are overwritten.  Accumulation uses fp32
- *        atomics, so results vary in the last bits from run to run. */
+ *        d_gxq [3][N] = dL/dx' (may be NULL).  Outputs are overwritten.  No floating-point atomics are
+ *        used, but the order in which the lanes of a grid cell are added follows the order in which
+ *        they were counted (integer atomics), so dL/dW and dL/dB vary in the last bits from run to run. */
 fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float *d_Jinv,
                   const uint8_t *d_conv, const float *d_gxc, const int32_t *d_pose, int64_t N, int32_t K,
                   const int32_t *d_slot, float *d_gW, float *d_gB, float *d_gxq);

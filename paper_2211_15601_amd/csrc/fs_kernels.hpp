@@ -779,7 +779,8 @@ __global__ void k_fill_zero(long long n, float *__restrict__ a)
 // The gradient w.r.t. the transform grid, G_T[p][v] = sum over converged lanes of
 // omega_corner * lambda (x) [x*; 1], is accumulated without floating-point atomics (device-scope
 // atomics leave the L2 on this chip and are slow): converged lanes are counting-sorted by the grid
-// cell of x*, then one wave per grid node sums the contributions of the lanes in its 8 adjacent cells.
+// cell of x* (pass 1 below, or the positions k_solve hands out), crowded cells are summed once per
+// corner (k_grad_pieces), and every grid node then adds what its 8 adjacent cells hold (k_grad_nodes_p).
 
 __global__ void k_fill_zero_i32(long long n, int *__restrict__ a, unsigned *__restrict__ also_zero = nullptr)
 {
@@ -789,7 +790,8 @@ __global__ void k_fill_zero_i32(long long n, int *__restrict__ a, unsigned *__re
     for (; i < n; i += stride) a[i] = 0;
 }
 
-// pass 1: one thread per lane; position of the lane inside its cell's list (arrival order)
+// pass 1 (only when the solve did not hand out positions): one thread per lane; position of the lane
+// inside its cell's list (arrival order)
 __global__ __launch_bounds__(256) void k_grad_count(GridP G, const float *__restrict__ xc,
                                                     const uint8_t *__restrict__ conv, const int32_t *__restrict__ pose,
                                                     long long N, int K, int ncell, int *__restrict__ count,
