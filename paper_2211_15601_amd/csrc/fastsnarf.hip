@@ -284,7 +284,7 @@ fs_status fs_set_params(fs_ctx *ctx, const fs_params *params)
 fs_status fs_set_tuning(fs_ctx *ctx, int32_t chunk, int32_t refill_min, int32_t blocks_per_cu, int32_t point_major, int32_t lds_grid)
 {
     if (!ctx) return FS_E_ARG;
-    if ((chunk != 0 && (chunk < 8 || chunk > 65536)) || (refill_min != 0 && (refill_min < 1 || refill_min > 64)) ||
+    if ((chunk != 0 && (chunk < 8 || chunk > 4096)) || (refill_min != 0 && (refill_min < 1 || refill_min > 64)) ||
         blocks_per_cu < 0 || blocks_per_cu > 32 || point_major < -1 || point_major > 1 || lds_grid < -1 || lds_grid > 1)
         return fail(ctx, FS_E_ARG, "fs_set_tuning: value out of range");
     if (chunk) ctx->chunk = chunk;
@@ -428,14 +428,16 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     const int ncell = (ctx->G.nx - 1) * (ctx->G.ny - 1) * (ctx->G.nz - 1);
     int *cell_count = nullptr;
     ctx->slots_N = 0;
+    // every wave owns the chunk of its own number to begin with; the shared cursor starts behind those
+    const unsigned cursor0 = (unsigned)((long long)blocks * wpb * S.chunk);
     if (d_slot) {
         const long long ncp = (long long)ctx->G.P * ncell;
         if (ncp + 1 >= (1ll << 31)) return fail(ctx, FS_E_SHAPE, "fs_solve: too many grid cells for d_slot");
         if (!ctx->gcount_solve && !dev_alloc(&ctx->gcount_solve, (size_t)ncp + 1)) return fail(ctx, FS_E_ALLOC, "fs_solve: out of device memory");
-        k_fill_zero_i32<<<(int)std::min<long long>(grid1d(ncp + 1, 256), 4096), 256, 0, st>>>(ncp + 1, ctx->gcount_solve, ctx->cursor);
+        k_fill_zero_i32<<<(int)std::min<long long>(grid1d(ncp + 1, 256), 4096), 256, 0, st>>>(ncp + 1, ctx->gcount_solve, ctx->cursor, cursor0);
         cell_count = ctx->gcount_solve;
     } else {
-        k_reset_cursor<<<1, 64, 0, st>>>(ctx->cursor);
+        k_reset_cursor<<<1, 64, 0, st>>>(ctx->cursor, cursor0);
     }
     const dim3 grd(blocks), blk(wpb * WAVE);
     hipEvent_t ev0 = nullptr, ev1 = nullptr;

@@ -559,9 +559,9 @@ __global__ __launch_bounds__(256) void k_solve_unpack(GridP G, InitP I, long lon
     }
 }
 
-__global__ void k_reset_cursor(unsigned *__restrict__ cursor)
+__global__ void k_reset_cursor(unsigned *__restrict__ cursor, unsigned start)
 {
-    if (threadIdx.x == 0 && blockIdx.x == 0) *cursor = 0u;
+    if (threadIdx.x == 0 && blockIdx.x == 0) *cursor = start;
 }
 
 // FUSED = false: initial states are read from x0 / J0 / valid0.  FUSED = true: a lane computes its
@@ -598,7 +598,10 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const
     // with a list only the pairs list[0 .. *list_len) (encoded n*K + k) are solved
     const long long total = list ? (long long)*list_len : S.total;
     const int lane = threadIdx.x & 63;
-    long long next = 0, c1 = 0;      // wave-uniform: the wave's current chunk is [next, c1)
+    // wave-uniform: the wave's current chunk is [next, c1).  The first chunk of wave w is chunk w (the cursor
+    // starts behind these): 2048 waves asking one counter at once would wait 9 ns each, one after the other.
+    long long next = (long long)((blockIdx.x * blockDim.x + threadIdx.x) >> 6) * S.chunk;
+    long long c1 = min(total, next + S.chunk);
     bool exhausted = false;          // wave-uniform: the global cursor has run past the end
     const long long N = S.N;
 
@@ -782,11 +785,12 @@ __global__ void k_fill_zero(long long n, float *__restrict__ a)
 // cell of x* (pass 1 below, or the positions k_solve hands out), crowded cells are summed once per
 // corner (k_grad_pieces), and every grid node then adds what its 8 adjacent cells hold (k_grad_nodes_p).
 
-__global__ void k_fill_zero_i32(long long n, int *__restrict__ a, unsigned *__restrict__ also_zero = nullptr)
+__global__ void k_fill_zero_i32(long long n, int *__restrict__ a, unsigned *__restrict__ also_set = nullptr,
+                                unsigned value = 0u)
 {
     long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     const long long stride = (long long)gridDim.x * blockDim.x;
-    if (also_zero && i == 0) *also_zero = 0u;
+    if (also_set && i == 0) *also_set = value;
     for (; i < n; i += stride) a[i] = 0;
 }
 
