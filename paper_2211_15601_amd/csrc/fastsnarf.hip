@@ -156,8 +156,12 @@ fs_status scan_exclusive(fs_ctx *c, int n, int *a, const int *src = nullptr, int
         c->scan_cap = m + 1;
     }
     k_scan_tile_sums<<<m, 1024, 0, c->stream>>>(n, src ? src : a, c->scan_sums);
-    k_scan_sums<<<1, 1024, 0, c->stream>>>(m, c->scan_sums, also_zero);
-    k_scan_tiles<<<m, 1024, 0, c->stream>>>(n, src ? src : a, a, c->scan_sums, m);
+    if (m <= 4096) {
+        k_scan_tiles<false><<<m, 1024, 0, c->stream>>>(n, src ? src : a, a, c->scan_sums, m, also_zero);
+    } else {
+        k_scan_sums<<<1, 1024, 0, c->stream>>>(m, c->scan_sums, also_zero);
+        k_scan_tiles<true><<<m, 1024, 0, c->stream>>>(n, src ? src : a, a, c->scan_sums, m, nullptr);
+    }
     return FS_OK;
 }
 

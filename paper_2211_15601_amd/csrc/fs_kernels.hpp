@@ -352,8 +352,12 @@ __global__ __launch_bounds__(1024) void k_scan_sums(int m, int *__restrict__ sum
     if (threadIdx.x == 0) sums[m] = run;
 }
 
-// out[i] = exclusive prefix of a (out may be a itself), out[n] = total
-__global__ __launch_bounds__(1024) void k_scan_tiles(int n, const int *a, int *out, const int *__restrict__ sums, int m)
+// out[i] = exclusive prefix of a (out may be a itself), out[n] = total.  SCANNED: sums holds the exclusive scan
+// of the tile sums (k_scan_sums ran); otherwise it holds the raw tile sums and every block adds up the ones
+// before its own tile itself (worth it while there are few tiles: one launch less).
+template <bool SCANNED>
+__global__ __launch_bounds__(1024) void k_scan_tiles(int n, const int *a, int *out, const int *__restrict__ sums, int m,
+                                                     int *__restrict__ also_zero)
 {
     const long long base = (long long)blockIdx.x * SCAN_TILE + threadIdx.x * 4;
     int e4[4], v = 0;
@@ -362,14 +366,32 @@ __global__ __launch_bounds__(1024) void k_scan_tiles(int n, const int *a, int *o
         e4[e] = base + e < n ? a[base + e] : 0;
         v += e4[e];
     }
+    int carry_in, grand = 0;
+    if (SCANNED) {
+        carry_in = sums[blockIdx.x];
+        if (blockIdx.x == 0 && threadIdx.x == 0) grand = sums[m];
+    } else {
+        int before = 0, all = 0;
+        for (int j = threadIdx.x; j < m; j += 1024) {
+            const int x = sums[j];
+            all += x;
+            if (j < (int)blockIdx.x) before += x;
+        }
+        int t0, t1;
+        (void)block_exclusive_scan_1024(before, &t0);
+        (void)block_exclusive_scan_1024(all, &t1);
+        carry_in = t0;
+        grand = t1;
+        if (also_zero && blockIdx.x == 0 && threadIdx.x == 0) *also_zero = 0;
+    }
     int tot;
-    int run = sums[blockIdx.x] + block_exclusive_scan_1024(v, &tot);
+    int run = carry_in + block_exclusive_scan_1024(v, &tot);
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
         if (base + e < n) out[base + e] = run;
         run += e4[e];
     }
-    if (blockIdx.x == 0 && threadIdx.x == 0) out[n] = sums[m];
+    if (blockIdx.x == 0 && threadIdx.x == 0) out[n] = grand;
 }
 
 __global__ __launch_bounds__(256) void k_corr_scatter(GridP G, CorrP C, const int *__restrict__ cell_of,

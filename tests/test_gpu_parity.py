@@ -203,6 +203,26 @@ def test_dedupe_parity(lib, case):
     assert run.ctx.dedupe(gu.dev(xc), gu.dev(cv), N, 65, md, keep, offs, None, None, 0, check=False) == binding.FS_E_SHAPE
 
 
+def test_dedupe_offsets_over_a_very_long_list(lib):
+    # one lane per point: the keep mask is the convergence mask and the offsets are its prefix sums.  2^24 + 5 points
+    # need more than 4096 scan tiles, the case in which the tile sums are scanned by a pass of their own.
+    N = (1 << 24) + 5
+    w = wl.make_config(1, n_points=64, dims=(8, 8, 4))
+    run = gu.GpuRun(w)
+    g = torch.Generator(device=gu.DEV)
+    g.manual_seed(11)
+    conv = (torch.rand((1, N), device=gu.DEV, generator=g) < 0.37).to(torch.uint8)
+    xc = torch.zeros((1, 3, N), dtype=torch.float32, device=gu.DEV)
+    keep = torch.full((1, N), 9, dtype=torch.uint8, device=gu.DEV)
+    offs = torch.full((N + 1,), -1, dtype=torch.int32, device=gu.DEV)
+    run.ctx.dedupe(xc, conv, N, 1, 1e-3, keep, offs, None, None, 0)
+    torch.cuda.synchronize()
+    assert torch.equal(keep, conv)
+    ref = torch.zeros(N + 1, dtype=torch.int64, device=gu.DEV)
+    ref[1:] = torch.cumsum(conv[0].to(torch.int64), 0)
+    assert torch.equal(offs.to(torch.int64), ref)
+
+
 def test_autograd_hook_matches_oracle_gradient(lib):
     # loss = sum over converged lanes of c . x*; its gradient through the autograd.Function equals the
     # float64 oracle's implicit gradient (Broyden-J mode) on the strict-fp32 oracle's roots
