@@ -34,7 +34,7 @@ PEAK_FP32_TFLOPS = 157.3            # published fp32 vector peak (needs packed f
 PEAK_FP32_UNPACKED_TFLOPS = 78.6    # 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz: one FMA per lane per clock
 # HBM traffic of one k_solve launch on the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE
 # (profiles/k_solve_config2_hbm_traffic.md); None for other workloads
-SOLVE_TRAFFIC_BYTES = {2: 204.6e6}
+SOLVE_TRAFFIC_BYTES = {2: 286.0e6}
 
 
 def resolution_sweep(torch, binding, wl, dev):
