@@ -33,8 +33,10 @@ LOADS_EVAL = 24      # 8 corner records x 3 rows of 16 bytes
 PEAK_FP32_TFLOPS = 157.3            # published fp32 vector peak (needs packed fp32 instructions)
 PEAK_FP32_UNPACKED_TFLOPS = 78.6    # 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz: one FMA per lane per clock
 # HBM traffic of one k_solve launch on the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE
-# (profiles/k_solve_config2_hbm_traffic.md); None for other workloads
+# (profiles/k_solve_config2_hbm_traffic.md); None for other workloads.  The second figure is the same
+# kernel without the per-cell counting of converged lanes (--no-slots).
 SOLVE_TRAFFIC_BYTES = {2: 286.0e6}
+SOLVE_TRAFFIC_BYTES_NO_SLOTS = {2: 204.6e6}
 
 
 def resolution_sweep(torch, binding, wl, dev):
@@ -220,7 +222,7 @@ def main():
                         "ceiling_lane_random_gather_same_footprint": gl, "frac_of_lane_gather": loads / gl,
                         "ceiling_line_coalesced_gather_same_footprint": gline,
                         "ceiling_lds_lane_random_gather": glds, "footprint_bytes": grid_bytes},
-        "traffic": SOLVE_TRAFFIC_BYTES.get(args.config)})
+        "traffic": (SOLVE_TRAFFIC_BYTES_NO_SLOTS if args.no_slots else SOLVE_TRAFFIC_BYTES).get(args.config)})
 
     if args.probe_copy_mib > 0:
         a = torch.empty(args.probe_copy_mib << 18, dtype=f32, device=dev)
