@@ -203,6 +203,48 @@ def test_dedupe_parity(lib, case):
     assert run.ctx.dedupe(gu.dev(xc), gu.dev(cv), N, 65, md, keep, offs, None, None, 0, check=False) == binding.FS_E_SHAPE
 
 
+def test_step_replays_from_a_hip_graph(lib):
+    # fs_precompute + fs_solve + fs_grad enqueue kernels only (no synchronisation, no memset nodes once the
+    # library's buffers exist), so a caller can capture the step; every replay must reproduce the eager result
+    w = wl.make_config(2, n_points=3001, dims=(32, 32, 8))
+    N, K = w.N, w.K
+    f32 = torch.float32
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        ctx = binding.Context(w.dims, w.n_bones, w.lo, w.hi, tol=w.tol, div_thresh=w.div_thresh, max_iters=w.max_iters)
+        W, B, xq, gxc = gu.dev(w.W), gu.dev(w.B), gu.dev(w.xq), gu.dev(w.upstream_grads())
+        xc = torch.empty((K, 3, N), dtype=f32, device=gu.DEV)
+        Jo = torch.empty((K, 9, N), dtype=f32, device=gu.DEV)
+        cv = torch.empty((K, N), dtype=torch.uint8, device=gu.DEV)
+        slot = torch.empty((K, N), dtype=torch.int32, device=gu.DEV)
+        gW = torch.empty(w.W.shape, dtype=f32, device=gu.DEV)
+        gB = torch.empty(w.B.shape, dtype=f32, device=gu.DEV)
+        gxq = torch.empty((3, N), dtype=f32, device=gu.DEV)
+
+        def step():
+            ctx.precompute(W, B)
+            ctx.solve(xq, None, N, K, None, None, None, xc, cv, Jo, None, slot)
+            ctx.grad(W, xc, Jo, cv, gxc, None, N, K, gW, gB, gxq, slot)
+
+        step()                                   # eager: also sizes the library's buffers
+        side.synchronize()
+        ref = [t.clone() for t in (xc, cv, Jo, gW, gB, gxq)]
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        side.synchronize()
+        for rep in range(3):
+            for t in (xc, cv, Jo, gW, gB, gxq):
+                t.zero_()                        # eager work between the replays
+            side.synchronize()
+            graph.replay()
+            side.synchronize()
+            assert torch.equal(xc, ref[0]) and torch.equal(cv, ref[1]) and torch.equal(Jo, ref[2]), rep
+            for a, b in ((gW, ref[3]), (gB, ref[4]), (gxq, ref[5])):
+                assert ((a - b).norm() / b.norm()).item() < 2e-5, rep
+        ctx.close()
+
+
 def test_dedupe_offsets_over_a_very_long_list(lib):
     # one lane per point: the keep mask is the convergence mask and the offsets are its prefix sums.  2^24 + 5 points
     # need more than 4096 scan tiles, the case in which the tile sums are scanned by a pass of their own.
