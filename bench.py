@@ -132,6 +132,9 @@ def main():
     gB = torch.empty(w.B.shape, dtype=f32, device=dev)
     gxq = torch.empty((3, N), dtype=f32, device=dev)
     slot = None if args.no_slots else torch.empty((K, N), dtype=torch.int32, device=dev)
+    # with the cell positions handed on, J~ can stay in the library's result records (not when the solve itself
+    # draws voxel-based initial states: pairs without a candidate have no record there)
+    Jarg = None if (slot is not None and (args.unfused or w.init_mode == 0)) else Jo
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
     marks = []
@@ -145,12 +148,12 @@ def main():
             ctx.init(xq, pose, N, x0, J0, v0)
         if record: e[2].record()
         if args.unfused:
-            ctx.solve(xq, pose, N, K, x0, J0, v0, xc, cv, Jo, it, slot)
+            ctx.solve(xq, pose, N, K, x0, J0, v0, xc, cv, Jarg, it, slot)
         else:
-            ctx.solve(xq, pose, N, K, None, None, None, xc, cv, Jo, it, slot)
+            ctx.solve(xq, pose, N, K, None, None, None, xc, cv, Jarg, it, slot)
         if record: e[3].record()
         if not args.no_grad:
-            ctx.grad(W, xc, Jo, cv, gxc, pose, N, K, gW, gB, gxq, slot)
+            ctx.grad(W, xc, Jarg, cv, gxc, pose, N, K, gW, gB, gxq, slot)
         if record: e[4].record()
         if record: marks.append(e)
 
@@ -196,7 +199,9 @@ def main():
                                f"{w.n_bones} bones, {w.n_poses} pose(s), {N} points x {K} inits, "
                                f"max_iters {w.max_iters}, tol {w.tol}",
                    "step": "fs_precompute + " + ("fs_init + fs_solve" if args.unfused else "fs_solve (initial states fused)")
-                           + ("" if args.no_grad else " + fs_grad"),
+                           + ("" if args.no_grad else " + fs_grad")
+                           + ("" if slot is None else (", cell positions handed from the solve to the backward"
+                                                       + (", J~ kept in the library" if Jarg is None else ""))),
                    "pairs": N * K, "valid_pairs": valid, "converged_pairs": conv,
                    "lane_iterations": evals},
         "breakdown_ms": {"fs_precompute": float(pre_ms), "fs_init": float(init_ms), "fs_solve": float(solve_ms),

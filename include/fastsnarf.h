@@ -123,11 +123,14 @@ fs_status fs_init(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_t
  *   init_mode itself (same arithmetic as fs_init, bit-identical results) and fs_init is not needed.
  *   out: d_xc [K][3][N] last iterate; d_conv [K][N] 1 = converged; d_Jinv [K][9][N] last J~ (may be
  *   NULL); d_iters [K][N] steps taken (may be NULL).  Lanes with valid0 == 0 return x0, conv 0.
- *   d_slot [K][N] (may be NULL; needs d_Jinv): bookkeeping for fs_grad.  The kernel counts its
- *   converged lanes per grid cell of x* as they finish and writes each lane's arrival position in
- *   its cell (-1 where conv == 0); the counts stay in the context.  The positions depend on the
- *   order in which lanes finish, so they differ from run to run; any run's set is a valid input of
- *   fs_grad. */
+ *   d_slot [K][N] (may be NULL): bookkeeping for fs_grad.  The kernel counts its converged lanes per
+ *   grid cell of x* as they finish and writes each lane's arrival position in its cell (-1 where
+ *   conv == 0); the counts, and the solve's result records (roots, masks, J~), stay in the context
+ *   until the next fs_solve.  The positions depend on the order in which lanes finish, so they differ
+ *   from run to run; any run's set is a valid input of fs_grad.  With d_slot, d_Jinv may be NULL:
+ *   J~ is then not written out at all and fs_grad takes it from the context (FS_E_UNSUPPORTED when
+ *   the solve computes voxel-based initial states itself: there, pairs without a candidate have no
+ *   record, so d_Jinv is needed). */
 fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_t N, int32_t K,
                    const float *d_x0, const float *d_Jinv0, const uint8_t *d_valid0,
                    float *d_xc, uint8_t *d_conv, float *d_Jinv, uint8_t *d_iters, int32_t *d_slot);
@@ -135,12 +138,15 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
 /* Backward by implicit differentiation, Eq. (11)/(12); with FS_GRAD_BROYDEN_J the inverse
  * Jacobian is Broyden's last J~ (Sec. 3.2 "Approximated Gradient", Eq. (15)), with
  * FS_GRAD_EXACT_J it is recomputed analytically at x*.  Only lanes with conv == 1 contribute.
- *   in : d_xc, d_Jinv (may be NULL for FS_GRAD_EXACT_J), d_conv, d_gxc [K][3][N] = dL/dx*,
+ *   in : d_xc, d_Jinv (may be NULL for FS_GRAD_EXACT_J, or with d_slot), d_conv, d_gxc [K][3][N] = dL/dx*,
  *        d_W as given to fs_precompute
  *        d_slot: NULL, or the array the last fs_solve on this context wrote (same N, K, and d_xc,
- *        d_conv, d_pose as that call left them; FS_E_STATE otherwise where it can be told): the
+ *        d_conv, d_pose as that call left them; FS_E_STATE otherwise where it can be told).  The
  *        pass that sorts the lanes by grid cell then reuses the solve's counts instead of counting
- *        again.  The sums are the same up to the order of the fp32 additions.
+ *        again, and roots, masks and J~ are read from the result records that solve left in the
+ *        context (one contiguous record per pair) rather than from d_xc / d_conv / d_Jinv; d_Jinv may
+ *        then be NULL for FS_GRAD_BROYDEN_J too (unless that solve drew voxel-based initial states
+ *        itself, see fs_solve).  The sums are the same up to the order of the fp32 additions.
  *   out: d_gW [nx][ny][nz][n_bones] = dL/dW (summed over poses), d_gB [n_poses][n_bones][12],
  *        d_gxq [3][N] = dL/dx' (may be NULL).  Outputs are overwritten.  No floating-point atomics are
  *        used, but the order in which the lanes of a grid cell are added follows the order in which

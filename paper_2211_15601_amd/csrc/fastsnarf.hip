@@ -43,6 +43,7 @@ struct fs_ctx {
     int *gcount_solve; // [P*ncells + 1] per-cell counts of converged lanes written by the last fs_solve that gave slots
     long long slots_N; // N of that fs_solve (0: none)
     int slots_K;
+    bool slots_list;   // that solve drew its pairs from the candidate list: pairs without a candidate have no record
     int *gpos;         // [K*N] position of a lane inside its cell's list (grows on demand)
     float *grec;       // [K*N][8] cell-sorted {x*, lambda, cell} records (grows on demand)
     size_t gcap;       // lanes gpos / grec can hold
@@ -373,7 +374,6 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     FS_CHECK_PTR(ctx, d_Jinv, true);
     FS_CHECK_PTR(ctx, d_iters, true);
     FS_CHECK_PTR(ctx, d_slot, true);
-    if (d_slot && !d_Jinv) return fail(ctx, FS_E_ARG, "fs_solve: d_slot needs d_Jinv (both serve fs_grad)");
     SolveP S;
     S.N = N;
     S.total = (long long)N * K;
@@ -400,7 +400,10 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     I.C = ctx->C;
     I.bbox = ctx->bbox;
     I.cand = ctx->cand;
-    const bool with_J = d_Jinv != nullptr;
+    const bool with_J = d_Jinv != nullptr || d_slot != nullptr;     // with d_slot alone J~ stays in the result records
+    if (d_slot && !d_Jinv && fused && ctx->prm.init_mode == FS_INIT_VOXEL)
+        return fail(ctx, FS_E_UNSUPPORTED, "fs_solve: with voxel-based initial states computed by the solve itself, pairs without a "
+                                           "candidate have no result record: pass d_Jinv as well");
     const size_t need = (size_t)S.total * (with_J ? 4 : 1);
     if (need > ctx->srec_cap) {
         (void)hipStreamSynchronize(ctx->stream);
@@ -480,6 +483,7 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     if (lst == FS_OK && d_slot) {
         ctx->slots_N = N;
         ctx->slots_K = K;
+        ctx->slots_list = list != nullptr;
     }
     return lst;
 }
@@ -500,7 +504,7 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
     FS_CHECK_PTR(ctx, d_gxq, true);
     if (N > 0) {
         FS_CHECK_PTR(ctx, d_xc, false);
-        FS_CHECK_PTR(ctx, d_Jinv, mode == FS_GRAD_EXACT_J);
+        FS_CHECK_PTR(ctx, d_Jinv, mode == FS_GRAD_EXACT_J || (d_slot != nullptr && !ctx->slots_list));
         FS_CHECK_PTR(ctx, d_conv, false);
         FS_CHECK_PTR(ctx, d_gxc, false);
         FS_CHECK_PTR(ctx, d_pose, true);
@@ -508,6 +512,8 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
     FS_CHECK_PTR(ctx, d_slot, true);
     if (d_slot && (ctx->slots_N != N || ctx->slots_K != K || N == 0))
         return fail(ctx, FS_E_STATE, "fs_grad: d_slot must come from the last fs_solve on this context with the same N and K");
+    // every pair has a result record unless the solve drew its pairs from the candidate list
+    const bool from_rec = d_slot != nullptr && !ctx->slots_list;
     const GridP &G = ctx->G;
     const int ncell = (G.nx - 1) * (G.ny - 1) * (G.nz - 1);
     const long long ncp = (long long)G.P * ncell;
@@ -543,8 +549,14 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
     if (N > 0) {
         // small batches: several threads share a point's lanes so that the chip has enough threads in flight
         const int groups = N >= (1 << 19) ? 1 : (K >= 8 ? 8 : (K >= 4 ? 4 : (K >= 2 ? 2 : 1)));
-        k_grad_records<<<grid1d(N, 256 / groups), 256, 0, st>>>(G, mode, ctx->T, d_xc, d_Jinv, d_conv, d_gxc, d_pose, N, K, ncell,
-                                                                ctx->gcount, pos, reinterpret_cast<float4 *>(ctx->grec), d_gxq, groups);
+        const dim3 rg(grid1d(N, 256 / groups));
+        float4 *grec4 = reinterpret_cast<float4 *>(ctx->grec);
+        if (from_rec)   // the solve's own result records are still in the context: one 64-byte read per pair
+            k_grad_records<true><<<rg, 256, 0, st>>>(G, mode, ctx->T, d_xc, d_Jinv, d_conv, d_gxc, d_pose, N, K, ncell, ctx->gcount, pos,
+                                                    grec4, d_gxq, groups, ctx->srec);
+        else
+            k_grad_records<false><<<rg, 256, 0, st>>>(G, mode, ctx->T, d_xc, d_Jinv, d_conv, d_gxc, d_pose, N, K, ncell, ctx->gcount, pos,
+                                                     grec4, d_gxq, groups, nullptr);
     }
     if (N > 0) k_grad_pieces<<<grid1d((long long)lanes, PIECE_R), 64, 0, st>>>(G, ncp, ctx->gcount, ctx->grec);
     // crowded grids: one thread per (node, adjacent cell); sparse ones: one thread per node

@@ -506,9 +506,9 @@ __device__ __forceinline__ void write_record(float4 *__restrict__ rec, long long
     if (WITH_J) {
         float4 *o = rec + pq * 4;
         o[0] = make_float4(x[0], x[1], x[2], __int_as_float(flags));
-        o[1] = make_float4(J[0], J[1], J[2], J[3]);
-        o[2] = make_float4(J[4], J[5], J[6], J[7]);
-        o[3] = make_float4(J[8], __int_as_float(slot), 0.0f, 0.0f);
+        o[1] = make_float4(__int_as_float(slot), J[0], J[1], J[2]);
+        o[2] = make_float4(J[3], J[4], J[5], J[6]);
+        o[3] = make_float4(J[7], J[8], 0.0f, 0.0f);
     } else {
         rec[pq] = make_float4(x[0], x[1], x[2], __int_as_float(flags));
     }
@@ -568,16 +568,23 @@ __global__ __launch_bounds__(256) void k_solve_unpack(GridP G, InitP I, long lon
     o_conv[pq] = (uint8_t)(flags & 1);
     if (o_it) o_it[pq] = (uint8_t)(flags >> 8);
     if (WITH_J) {
-        float J[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
-        if (have) {
-            const float4 b = rec[pq * 4 + 1], c = rec[pq * 4 + 2], d = rec[pq * 4 + 3];
-            J[0] = b.x; J[1] = b.y; J[2] = b.z; J[3] = b.w; J[4] = c.x; J[5] = c.y; J[6] = c.z; J[7] = c.w; J[8] = d.x;
-            if (o_slot) o_slot[pq] = (flags & 1) ? __float_as_int(d.y) : -1;
-        } else if (o_slot) {
-            o_slot[pq] = -1;
-        }
+        if (o_J) {
+            float J[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+            int slot = -1;
+            if (have) {
+                const float4 b = rec[pq * 4 + 1], c = rec[pq * 4 + 2], d = rec[pq * 4 + 3];
+                J[0] = b.y; J[1] = b.z; J[2] = b.w; J[3] = c.x; J[4] = c.y; J[5] = c.z; J[6] = c.w; J[7] = d.x; J[8] = d.y;
+                slot = __float_as_int(b.x);
+            }
 #pragma unroll
-        for (int e = 0; e < 9; ++e) o_J[(k * 9 + e) * N + n] = J[e];
+            for (int e = 0; e < 9; ++e) o_J[(k * 9 + e) * N + n] = J[e];
+            if (o_slot) o_slot[pq] = (flags & 1) ? slot : -1;
+        } else if (o_slot) {
+            // J~ stays in the records: only their first sector is read
+            int slot = -1;
+            if (have && (flags & 1)) slot = __float_as_int(reinterpret_cast<const float *>(rec + pq * 4 + 1)[0]);
+            o_slot[pq] = slot;
+        }
     }
 }
 
@@ -594,7 +601,8 @@ __global__ void k_reset_cursor(unsigned *__restrict__ cursor, unsigned start)
 // Results leave the kernel as one contiguous record per pair (lanes finish at different times, so
 // writing the caller's structure-of-arrays layout from here would touch 14 cache lines per pair with
 // 4 bytes each); k_solve_unpack then moves the records into that layout with coalesced stores.
-// Record: WITH_J ? 16 floats {x*[3], flags, J~[9], slot, pad[2]} : 4 floats {x*[3], flags};
+// Record: WITH_J ? 16 floats {x*[3], flags, slot, J~[9], pad[2]} : 4 floats {x*[3], flags} (roots, flags and
+// slot share the record's first 32-byte sector: who needs no J~ reads only that);
 // flags = conv | iters << 8 (as an integer bit pattern).
 // LDSGRID: the whole transform grid (all poses) fits in LDS; every block copies it there first and all
 // corner records are then read from LDS, where per-lane addresses cost far less than in the vector
@@ -839,12 +847,16 @@ __global__ __launch_bounds__(256) void k_grad_count(GridP G, const float *__rest
 // cell, 0} goes to the lane's slot of the cell-sorted list (one aligned sector per record);
 // dL/dx' = sum_k M^T g_x without atomics.
 constexpr int GREC = 8;           // floats per record
+// FROM_REC: roots, masks, J~ and positions are taken from the result records the last solve left in the
+// context (one contiguous 64-byte record per pair, every pair has one) instead of the caller's arrays.
+template <bool FROM_REC>
 __global__ __launch_bounds__(256) void k_grad_records(GridP G, int mode, const float *__restrict__ T,
                                                       const float *__restrict__ xc, const float *__restrict__ Jinv,
                                                       const uint8_t *__restrict__ conv, const float *__restrict__ gxc,
                                                       const int32_t *__restrict__ pose, long long N, int K, int ncell,
                                                       const int *__restrict__ offset, const int *__restrict__ pos,
-                                                      float4 *__restrict__ rec, float *__restrict__ gxq, int groups)
+                                                      float4 *__restrict__ rec, float *__restrict__ gxq, int groups,
+                                                      const float4 *__restrict__ srec)
 {
     // `groups` (a power of two <= 8) threads share a point and take its lanes k = g, g + groups, ...;
     // consecutive threads of a group are consecutive points, so every load is coalesced
@@ -857,18 +869,32 @@ __global__ __launch_bounds__(256) void k_grad_records(GridP G, int mode, const f
         const int p = pose_of(pose, n, G.P);
         for (int k = g; k < K; k += groups) {
             const long long q = (long long)k * N + n;
-            if (!conv[q]) continue;
             float x[3], gx[3], M[9];
-#pragma unroll
-            for (int r = 0; r < 3; ++r) {
-                x[r] = xc[((long long)k * 3 + r) * N + n];
-                gx[r] = gxc[((long long)k * 3 + r) * N + n];
-            }
-            bool ok = true;
-            if (mode == 0) {
-#pragma unroll
-                for (int e = 0; e < 9; ++e) M[e] = Jinv[((long long)k * 9 + e) * N + n];
+            int pq;
+            if (FROM_REC) {
+                const float4 a = srec[q * 4];
+                if (!(__float_as_int(a.w) & 1)) continue;
+                x[0] = a.x; x[1] = a.y; x[2] = a.z;
+                const float4 b = srec[q * 4 + 1];
+                pq = __float_as_int(b.x);
+                if (mode == 0) {
+                    const float4 c = srec[q * 4 + 2], d = srec[q * 4 + 3];
+                    M[0] = b.y; M[1] = b.z; M[2] = b.w; M[3] = c.x; M[4] = c.y; M[5] = c.z; M[6] = c.w; M[7] = d.x; M[8] = d.y;
+                }
             } else {
+                if (!conv[q]) continue;
+#pragma unroll
+                for (int r = 0; r < 3; ++r) x[r] = xc[((long long)k * 3 + r) * N + n];
+                pq = pos[q];
+                if (mode == 0) {
+#pragma unroll
+                    for (int e = 0; e < 9; ++e) M[e] = Jinv[((long long)k * 9 + e) * N + n];
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < 3; ++r) gx[r] = gxc[((long long)k * 3 + r) * N + n];
+            bool ok = true;
+            if (mode != 0) {
                 float d[3], J[9];
                 field_dJ(T + (long long)p * G.V * 12, G, x, d, J);
                 ok = inv3(J, M);
@@ -883,7 +909,6 @@ __global__ __launch_bounds__(256) void k_grad_records(GridP G, int mode, const f
             }
             const Cell c = locate(G, x);
             const int cl = p * ncell + cell_linear(G, c);
-            const int pq = pos[q];
             const long long slot = (long long)offset[cl] + pq;
             // positions that do not belong to these roots (a caller mixing arrays of different solves)
             // must not send the store outside the cell's part of the list
