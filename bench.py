@@ -132,9 +132,8 @@ def main():
     gB = torch.empty(w.B.shape, dtype=f32, device=dev)
     gxq = torch.empty((3, N), dtype=f32, device=dev)
     slot = None if args.no_slots else torch.empty((K, N), dtype=torch.int32, device=dev)
-    # with the cell positions handed on, J~ can stay in the library's result records (not when the solve itself
-    # draws voxel-based initial states: pairs without a candidate have no record there)
-    Jarg = None if (slot is not None and (args.unfused or w.init_mode == 0)) else Jo
+    # with the cell positions handed on, J~ can stay in the library's result records
+    Jarg = None if slot is not None else Jo
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
     marks = []

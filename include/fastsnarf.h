@@ -128,9 +128,7 @@ fs_status fs_init(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_t
  *   conv == 0); the counts, and the solve's result records (roots, masks, J~), stay in the context
  *   until the next fs_solve.  The positions depend on the order in which lanes finish, so they differ
  *   from run to run; any run's set is a valid input of fs_grad.  With d_slot, d_Jinv may be NULL:
- *   J~ is then not written out at all and fs_grad takes it from the context (FS_E_UNSUPPORTED when
- *   the solve computes voxel-based initial states itself: there, pairs without a candidate have no
- *   record, so d_Jinv is needed). */
+ *   J~ is then not written out at all and fs_grad takes it from the context. */
 fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_t N, int32_t K,
                    const float *d_x0, const float *d_Jinv0, const uint8_t *d_valid0,
                    float *d_xc, uint8_t *d_conv, float *d_Jinv, uint8_t *d_iters, int32_t *d_slot);
@@ -145,8 +143,8 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
  *        pass that sorts the lanes by grid cell then reuses the solve's counts instead of counting
  *        again, and roots, masks and J~ are read from the result records that solve left in the
  *        context (one contiguous record per pair) rather than from d_xc / d_conv / d_Jinv; d_Jinv may
- *        then be NULL for FS_GRAD_BROYDEN_J too (unless that solve drew voxel-based initial states
- *        itself, see fs_solve).  The sums are the same up to the order of the fp32 additions.
+ *        then be NULL for FS_GRAD_BROYDEN_J too.  The sums are the same up to the order of the fp32
+ *        additions.
  *   out: d_gW [nx][ny][nz][n_bones] = dL/dW (summed over poses), d_gB [n_poses][n_bones][12],
  *        d_gxq [3][N] = dL/dx' (may be NULL).  Outputs are overwritten.  No floating-point atomics are
  *        used, but the order in which the lanes of a grid cell are added follows the order in which

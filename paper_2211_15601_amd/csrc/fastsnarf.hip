@@ -401,9 +401,6 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     I.bbox = ctx->bbox;
     I.cand = ctx->cand;
     const bool with_J = d_Jinv != nullptr || d_slot != nullptr;     // with d_slot alone J~ stays in the result records
-    if (d_slot && !d_Jinv && fused && ctx->prm.init_mode == FS_INIT_VOXEL)
-        return fail(ctx, FS_E_UNSUPPORTED, "fs_solve: with voxel-based initial states computed by the solve itself, pairs without a "
-                                           "candidate have no result record: pass d_Jinv as well");
     const size_t need = (size_t)S.total * (with_J ? 4 : 1);
     if (need > ctx->srec_cap) {
         (void)hipStreamSynchronize(ctx->stream);
@@ -472,13 +469,13 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     const bool nocand = fused && ctx->prm.init_mode == FS_INIT_VOXEL;
     const int ub = grid1d(S.total, 256);
     if (with_J && nocand)
-        k_solve_unpack<true, true><<<ub, 256, 0, st>>>(ctx->G, I, N, S.total, d_xq, d_pose, ctx->srec, d_xc, d_conv, d_Jinv, d_iters, d_slot);
+        k_solve_unpack<true, true><<<ub, 256, 0, st>>>(N, S.total, ctx->voffs, ctx->srec, d_xc, d_conv, d_Jinv, d_iters, d_slot);
     else if (with_J)
-        k_solve_unpack<true, false><<<ub, 256, 0, st>>>(ctx->G, I, N, S.total, d_xq, d_pose, ctx->srec, d_xc, d_conv, d_Jinv, d_iters, d_slot);
+        k_solve_unpack<true, false><<<ub, 256, 0, st>>>(N, S.total, ctx->voffs, ctx->srec, d_xc, d_conv, d_Jinv, d_iters, d_slot);
     else if (nocand)
-        k_solve_unpack<false, true><<<ub, 256, 0, st>>>(ctx->G, I, N, S.total, d_xq, d_pose, ctx->srec, d_xc, d_conv, d_Jinv, d_iters, d_slot);
+        k_solve_unpack<false, true><<<ub, 256, 0, st>>>(N, S.total, ctx->voffs, ctx->srec, d_xc, d_conv, d_Jinv, d_iters, d_slot);
     else
-        k_solve_unpack<false, false><<<ub, 256, 0, st>>>(ctx->G, I, N, S.total, d_xq, d_pose, ctx->srec, d_xc, d_conv, d_Jinv, d_iters, d_slot);
+        k_solve_unpack<false, false><<<ub, 256, 0, st>>>(N, S.total, ctx->voffs, ctx->srec, d_xc, d_conv, d_Jinv, d_iters, d_slot);
     fs_status lst = launch_status(ctx, "fs_solve");
     if (lst == FS_OK && d_slot) {
         ctx->slots_N = N;
@@ -504,7 +501,7 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
     FS_CHECK_PTR(ctx, d_gxq, true);
     if (N > 0) {
         FS_CHECK_PTR(ctx, d_xc, false);
-        FS_CHECK_PTR(ctx, d_Jinv, mode == FS_GRAD_EXACT_J || (d_slot != nullptr && !ctx->slots_list));
+        FS_CHECK_PTR(ctx, d_Jinv, mode == FS_GRAD_EXACT_J || d_slot != nullptr);
         FS_CHECK_PTR(ctx, d_conv, false);
         FS_CHECK_PTR(ctx, d_gxc, false);
         FS_CHECK_PTR(ctx, d_pose, true);
@@ -512,8 +509,7 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
     FS_CHECK_PTR(ctx, d_slot, true);
     if (d_slot && (ctx->slots_N != N || ctx->slots_K != K || N == 0))
         return fail(ctx, FS_E_STATE, "fs_grad: d_slot must come from the last fs_solve on this context with the same N and K");
-    // every pair has a result record unless the solve drew its pairs from the candidate list
-    const bool from_rec = d_slot != nullptr && !ctx->slots_list;
+    const bool from_rec = d_slot != nullptr;
     const GridP &G = ctx->G;
     const int ncell = (G.nx - 1) * (G.ny - 1) * (G.nz - 1);
     const long long ncp = (long long)G.P * ncell;
@@ -553,10 +549,10 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
         float4 *grec4 = reinterpret_cast<float4 *>(ctx->grec);
         if (from_rec)   // the solve's own result records are still in the context: one 64-byte read per pair
             k_grad_records<true><<<rg, 256, 0, st>>>(G, mode, ctx->T, d_xc, d_Jinv, d_conv, d_gxc, d_pose, N, K, ncell, ctx->gcount, pos,
-                                                    grec4, d_gxq, groups, ctx->srec);
+                                                    grec4, d_gxq, groups, ctx->srec, ctx->slots_list ? ctx->voffs : nullptr);
         else
             k_grad_records<false><<<rg, 256, 0, st>>>(G, mode, ctx->T, d_xc, d_Jinv, d_conv, d_gxc, d_pose, N, K, ncell, ctx->gcount, pos,
-                                                     grec4, d_gxq, groups, nullptr);
+                                                     grec4, d_gxq, groups, nullptr, nullptr);
     }
     if (N > 0) k_grad_pieces<<<grid1d((long long)lanes, PIECE_R), 64, 0, st>>>(G, ncp, ctx->gcount, ctx->grec);
     // crowded grids: one thread per (node, adjacent cell); sparse ones: one thread per node

@@ -541,10 +541,10 @@ __global__ __launch_bounds__(256) void k_voxel_expand(long long N, int K, const 
 
 // records -> caller's layout: one thread per pair q = k*N + n, consecutive threads consecutive n.
 // NOCAND: the solve ran with fused voxel-based initial states and wrote no record for lanes whose
-// cell holds no k-th candidate; those get the answer of an invalid lane (x0 = 0, J~ = 0, not converged).
+// cell holds no k-th candidate (cand_offs[n+1] - cand_offs[n] = candidates of point n, packed at the front);
+// those get the answer of an invalid lane (x0 = 0, J~ = 0, not converged).
 template <bool WITH_J, bool NOCAND>
-__global__ __launch_bounds__(256) void k_solve_unpack(GridP G, InitP I, long long N, long long total,
-                                                      const float *__restrict__ xq, const int32_t *__restrict__ pose,
+__global__ __launch_bounds__(256) void k_solve_unpack(long long N, long long total, const int *__restrict__ cand_offs,
                                                       const float4 *__restrict__ rec, float *__restrict__ o_x,
                                                       uint8_t *__restrict__ o_conv, float *__restrict__ o_J,
                                                       uint8_t *__restrict__ o_it, int32_t *__restrict__ o_slot)
@@ -553,12 +553,7 @@ __global__ __launch_bounds__(256) void k_solve_unpack(GridP G, InitP I, long lon
     if (pq >= total) return;
     const long long k = pq / N, n = pq - k * N;
     bool have = true;
-    if (NOCAND) {
-        const int p = pose_of(pose, n, G.P);
-        const float xp[3] = {xq[n], xq[N + n], xq[2 * N + n]};
-        const int cidx = cell_index(I.C, I.bbox + p * 6, xp);
-        have = I.cand[((long long)p * I.C.ncell + cidx) * I.C.ck + k] >= 0;
-    }
+    if (NOCAND) have = k < cand_offs[n + 1] - cand_offs[n];
     float4 a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
     if (have) a = WITH_J ? rec[pq * 4] : rec[pq];
     o_x[(k * 3 + 0) * N + n] = a.x;
@@ -848,7 +843,8 @@ __global__ __launch_bounds__(256) void k_grad_count(GridP G, const float *__rest
 // dL/dx' = sum_k M^T g_x without atomics.
 constexpr int GREC = 8;           // floats per record
 // FROM_REC: roots, masks, J~ and positions are taken from the result records the last solve left in the
-// context (one contiguous 64-byte record per pair, every pair has one) instead of the caller's arrays.
+// context (one contiguous 64-byte record per pair) instead of the caller's arrays; when that solve drew its
+// pairs from the candidate list, only the first cand_offs[n+1] - cand_offs[n] lanes of point n have a record.
 template <bool FROM_REC>
 __global__ __launch_bounds__(256) void k_grad_records(GridP G, int mode, const float *__restrict__ T,
                                                       const float *__restrict__ xc, const float *__restrict__ Jinv,
@@ -856,7 +852,7 @@ __global__ __launch_bounds__(256) void k_grad_records(GridP G, int mode, const f
                                                       const int32_t *__restrict__ pose, long long N, int K, int ncell,
                                                       const int *__restrict__ offset, const int *__restrict__ pos,
                                                       float4 *__restrict__ rec, float *__restrict__ gxq, int groups,
-                                                      const float4 *__restrict__ srec)
+                                                      const float4 *__restrict__ srec, const int *__restrict__ cand_offs)
 {
     // `groups` (a power of two <= 8) threads share a point and take its lanes k = g, g + groups, ...;
     // consecutive threads of a group are consecutive points, so every load is coalesced
@@ -867,7 +863,8 @@ __global__ __launch_bounds__(256) void k_grad_records(GridP G, int mode, const f
     float gq[3] = {0.0f, 0.0f, 0.0f};
     if (n < N) {
         const int p = pose_of(pose, n, G.P);
-        for (int k = g; k < K; k += groups) {
+        const int nk = (FROM_REC && cand_offs) ? min(K, cand_offs[n + 1] - cand_offs[n]) : K;
+        for (int k = g; k < nk; k += groups) {
             const long long q = (long long)k * N + n;
             float x[3], gx[3], M[9];
             int pq;

@@ -139,23 +139,15 @@ def test_grad_with_slots_from_solve(lib, case):
             rel = np.linalg.norm(a.astype(np.float64) - b) / max(np.linalg.norm(b), 1e-30)
             print(f"{w.name} slots rep {rep} {name}: relative L2 vs f64 oracle {rel:.2e}")
             assert rel < 2e-5, (name, rel)
-    # J~ may stay inside the library: solve with slots but without d_Jinv, backward without d_Jinv.  Not with
-    # voxel-based initial states computed by the solve itself (pairs without a candidate have no record there).
-    if w.init_mode == wl.INIT_BONE:
-        xc2, cv2, _, _ = run.solve(fused=True, slots=True, want_J=False)
-        np.testing.assert_array_equal(xc2.view(np.uint32), xc.view(np.uint32))
-        np.testing.assert_array_equal(cv2, cv)
-        gW, gB, gxq = run.grad(xc2, None, cv2, gxc, slot=run.slot)
-        for name, a, b in (("gW", gW, rW), ("gB", gB, rB), ("gxq", gxq, rq)):
-            rel = np.linalg.norm(a.astype(np.float64) - b) / max(np.linalg.norm(b), 1e-30)
-            print(f"{w.name} J~ kept inside {name}: relative L2 vs f64 oracle {rel:.2e}")
-            assert np.isfinite(a).all() and rel < 2e-5, (name, rel)
-    else:
-        xcn = torch.empty((w.K, 3, w.N), dtype=torch.float32, device=gu.DEV)
-        cvn = torch.empty((w.K, w.N), dtype=torch.uint8, device=gu.DEV)
-        st = run.ctx.solve(run.xq, run.pose, w.N, w.K, None, None, None, xcn, cvn, None, None, run.slot, check=False)
-        assert st == binding.FS_E_UNSUPPORTED
-        xc, cv, Jo, it = run.solve(fused=True, slots=True)          # restore the state the rest of the test uses
+    # J~ may stay inside the library: solve with slots but without d_Jinv, backward without d_Jinv
+    xc2, cv2, _, _ = run.solve(fused=True, slots=True, want_J=False)
+    np.testing.assert_array_equal(xc2.view(np.uint32), xc.view(np.uint32))
+    np.testing.assert_array_equal(cv2, cv)
+    gW, gB, gxq = run.grad(xc2, None, cv2, gxc, slot=run.slot)
+    for name, a, b in (("gW", gW, rW), ("gB", gB, rB), ("gxq", gxq, rq)):
+        rel = np.linalg.norm(a.astype(np.float64) - b) / max(np.linalg.norm(b), 1e-30)
+        print(f"{w.name} J~ kept inside {name}: relative L2 vs f64 oracle {rel:.2e}")
+        assert np.isfinite(a).all() and rel < 2e-5, (name, rel)
     # and the counting path gives the same result on the same inputs
     cW, cB, cq = run.grad(xc, Jo, cv, gxc)
     assert np.linalg.norm(cW.astype(np.float64) - rW) / np.linalg.norm(rW) < 2e-5
