@@ -449,7 +449,7 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     const size_t shm = lds ? grid_bytes : 0;
 #define FS_LAUNCH_SOLVE(F, J, L)                                                                                      \
     k_solve<F, J, L><<<grd, blk, shm, st>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, d_x0, d_Jinv0, d_valid0, ctx->srec, \
-                                            ctx->cursor, list, list_len, cell_count, ncell)
+                                            ctx->cursor, list, list_len, cell_count, ncell, d_slot)
     if (lds) {
         if (fused && with_J) FS_LAUNCH_SOLVE(true, true, true);
         else if (fused) FS_LAUNCH_SOLVE(true, false, true);

@@ -501,14 +501,14 @@ struct InitP {
 
 template <bool WITH_J>
 __device__ __forceinline__ void write_record(float4 *__restrict__ rec, long long pq, const float x[3], const float J[9],
-                                             int flags, int slot = -1)
+                                             int flags)
 {
     if (WITH_J) {
         float4 *o = rec + pq * 4;
         o[0] = make_float4(x[0], x[1], x[2], __int_as_float(flags));
-        o[1] = make_float4(__int_as_float(slot), J[0], J[1], J[2]);
-        o[2] = make_float4(J[3], J[4], J[5], J[6]);
-        o[3] = make_float4(J[7], J[8], 0.0f, 0.0f);
+        o[1] = make_float4(J[0], J[1], J[2], J[3]);
+        o[2] = make_float4(J[4], J[5], J[6], J[7]);
+        o[3] = make_float4(J[8], 0.0f, 0.0f, 0.0f);
     } else {
         rec[pq] = make_float4(x[0], x[1], x[2], __int_as_float(flags));
     }
@@ -562,30 +562,54 @@ __global__ __launch_bounds__(256) void k_solve_unpack(long long N, long long tot
     const int flags = __float_as_int(a.w);
     o_conv[pq] = (uint8_t)(flags & 1);
     if (o_it) o_it[pq] = (uint8_t)(flags >> 8);
-    if (WITH_J) {
-        if (o_J) {
-            float J[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
-            int slot = -1;
-            if (have) {
-                const float4 b = rec[pq * 4 + 1], c = rec[pq * 4 + 2], d = rec[pq * 4 + 3];
-                J[0] = b.y; J[1] = b.z; J[2] = b.w; J[3] = c.x; J[4] = c.y; J[5] = c.z; J[6] = c.w; J[7] = d.x; J[8] = d.y;
-                slot = __float_as_int(b.x);
-            }
-#pragma unroll
-            for (int e = 0; e < 9; ++e) o_J[(k * 9 + e) * N + n] = J[e];
-            if (o_slot) o_slot[pq] = (flags & 1) ? slot : -1;
-        } else if (o_slot) {
-            // J~ stays in the records: only their first sector is read
-            int slot = -1;
-            if (have && (flags & 1)) slot = __float_as_int(reinterpret_cast<const float *>(rec + pq * 4 + 1)[0]);
-            o_slot[pq] = slot;
+    // the solve wrote the positions of its converged lanes into o_slot itself; the others are marked here
+    if (o_slot && !(flags & 1)) o_slot[pq] = -1;
+    if (WITH_J && o_J) {
+        float J[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+        if (have) {
+            const float4 b = rec[pq * 4 + 1], c = rec[pq * 4 + 2], d = rec[pq * 4 + 3];
+            J[0] = b.x; J[1] = b.y; J[2] = b.z; J[3] = b.w; J[4] = c.x; J[5] = c.y; J[6] = c.z; J[7] = c.w; J[8] = d.x;
         }
+#pragma unroll
+        for (int e = 0; e < 9; ++e) o_J[(k * 9 + e) * N + n] = J[e];
     }
 }
 
 __global__ void k_reset_cursor(unsigned *__restrict__ cursor, unsigned start)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) *cursor = start;
+}
+
+// The parked requests of one wave: entry i = {cell, pair}, one per SIMD lane.  Lanes of one point that reach
+// the same root are neighbours in the wave and finish within a few passes of each other, so many entries name
+// the same cell: those are counted together and one lane adds the group to the cell's counter.
+__device__ __forceinline__ void flush_slots(int (&pend)[2][64], int npend, int lane, int *__restrict__ cell_count,
+                                            int32_t *__restrict__ slot_out)
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");      // the LDS writes of the wave's other lanes
+    __builtin_amdgcn_wave_barrier();
+    const bool valid = lane < npend;
+    const int c = valid ? pend[0][lane] : -1;
+    const int pq = valid ? pend[1][lane] : 0;
+    int leader = lane, rank = 0, members = 1;
+    unsigned long long todo = __ballot(valid);
+    while (todo) {
+        const int first = __ffsll((long long)todo) - 1;
+        const int key = __shfl(c, first);
+        const unsigned long long same = __ballot(valid && c == key);
+        if (valid && c == key) {
+            leader = first;
+            rank = __popcll(same & ((1ull << lane) - 1ull));
+            members = __popcll(same);
+        }
+        todo &= ~same;
+    }
+    int base = 0;
+    if (valid && leader == lane) base = atomicAdd(cell_count + c, members);
+    base = __shfl(base, leader);
+    if (valid) slot_out[pq] = base + rank;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");      // before the entries are overwritten
+    __builtin_amdgcn_wave_barrier();
 }
 
 // FUSED = false: initial states are read from x0 / J0 / valid0.  FUSED = true: a lane computes its
@@ -596,8 +620,8 @@ __global__ void k_reset_cursor(unsigned *__restrict__ cursor, unsigned start)
 // Results leave the kernel as one contiguous record per pair (lanes finish at different times, so
 // writing the caller's structure-of-arrays layout from here would touch 14 cache lines per pair with
 // 4 bytes each); k_solve_unpack then moves the records into that layout with coalesced stores.
-// Record: WITH_J ? 16 floats {x*[3], flags, slot, J~[9], pad[2]} : 4 floats {x*[3], flags} (roots, flags and
-// slot share the record's first 32-byte sector: who needs no J~ reads only that);
+// Record: WITH_J ? 16 floats {x*[3], flags, J~[9], pad[3]} : 4 floats {x*[3], flags} (who needs no J~ reads only
+// the first 16 bytes);
 // flags = conv | iters << 8 (as an integer bit pattern).
 // LDSGRID: the whole transform grid (all poses) fits in LDS; every block copies it there first and all
 // corner records are then read from LDS, where per-lane addresses cost far less than in the vector
@@ -609,9 +633,11 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const
                                                const uint8_t *__restrict__ valid0, float4 *__restrict__ rec,
                                                unsigned *__restrict__ cursor, const int *__restrict__ list,
                                                const int *__restrict__ list_len, int *__restrict__ cell_count,
-                                               int ncell)
+                                               int ncell, int32_t *__restrict__ slot_out)
 {
     extern __shared__ float4 s_grid[];
+    // converged lanes waiting for their position in their grid cell's list: {cell, pair} per wave
+    __shared__ int s_pend[4][2][64];
     const float *T = Tglobal;
     if (LDSGRID) {
         const int n4 = (int)((long long)G.P * G.V * 3);      // float4 per record: 3
@@ -638,6 +664,8 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const
     float J[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
     float q[8][12];                  // corner records of the lane's current cell, kept across iterations
     long long held = -1;             // grid offset of the cell whose corners q holds (-1: none)
+    int npend = 0;                   // wave-uniform: entries of s_pend in use
+    const int wib = threadIdx.x >> 6;
 
     while (true) {
         unsigned long long idle = __ballot(!active);
@@ -736,6 +764,8 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const
             if (exhausted) break;
             continue;
         }
+        bool want_slot = false;
+        int slot_cell = 0;
         if (active) {
             float d[3], gn[3];
             // steps shrink as a lane converges, so it often stays in the cell it was in: reload the
@@ -778,10 +808,11 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const
             const bool conv = r2 < S.tol2;
             const bool done = conv || !(r2 < S.div2) || it >= S.max_iters;
             if (done) {
-                // for the backward: the arrival position of a converged lane in the list of its grid cell
-                int slot = -1;
-                if (WITH_J && cell_count && conv) slot = atomicAdd(cell_count + pz * ncell + cell_linear(G, cell), 1);
-                write_record<WITH_J>(rec, (long long)k * N + n, x, J, (conv ? 1 : 0) | (it << 8), slot);
+                write_record<WITH_J>(rec, (long long)k * N + n, x, J, (conv ? 1 : 0) | (it << 8));
+                if (WITH_J && cell_count && conv) {
+                    want_slot = true;
+                    slot_cell = pz * ncell + cell_linear(G, cell);
+                }
                 active = false;
             } else {
 #pragma unroll
@@ -791,7 +822,30 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const
                 }
             }
         }
+        // For the backward every converged lane needs its arrival position in the list of its grid cell: one
+        // returning atomic on the cell's counter.  A wave would wait for that answer in every pass (a few of
+        // its lanes finish in each), so the requests are parked in LDS and sent 48 or more at a time, one per cell.
+        if (WITH_J && cell_count) {
+            const unsigned long long m = __ballot(want_slot);
+            if (m) {
+                if (npend + __popcll(m) > 64) {
+                    flush_slots(s_pend[wib], npend, lane, cell_count, slot_out);
+                    npend = 0;
+                }
+                if (want_slot) {
+                    const int at = npend + __popcll(m & ((1ull << lane) - 1ull));
+                    s_pend[wib][0][at] = slot_cell;
+                    s_pend[wib][1][at] = (int)((long long)k * N + n);
+                }
+                npend += __popcll(m);
+            }
+            if (npend >= 48) {
+                flush_slots(s_pend[wib], npend, lane, cell_count, slot_out);
+                npend = 0;
+            }
+        }
     }
+    if (WITH_J && cell_count && npend > 0) flush_slots(s_pend[wib], npend, lane, cell_count, slot_out);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -872,11 +926,10 @@ __global__ __launch_bounds__(256) void k_grad_records(GridP G, int mode, const f
                 const float4 a = srec[q * 4];
                 if (!(__float_as_int(a.w) & 1)) continue;
                 x[0] = a.x; x[1] = a.y; x[2] = a.z;
-                const float4 b = srec[q * 4 + 1];
-                pq = __float_as_int(b.x);
+                pq = pos[q];
                 if (mode == 0) {
-                    const float4 c = srec[q * 4 + 2], d = srec[q * 4 + 3];
-                    M[0] = b.y; M[1] = b.z; M[2] = b.w; M[3] = c.x; M[4] = c.y; M[5] = c.z; M[6] = c.w; M[7] = d.x; M[8] = d.y;
+                    const float4 b = srec[q * 4 + 1], c = srec[q * 4 + 2], d = srec[q * 4 + 3];
+                    M[0] = b.x; M[1] = b.y; M[2] = b.z; M[3] = b.w; M[4] = c.x; M[5] = c.y; M[6] = c.z; M[7] = c.w; M[8] = d.x;
                 }
             } else {
                 if (!conv[q]) continue;
