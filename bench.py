@@ -35,7 +35,7 @@ PEAK_FP32_UNPACKED_TFLOPS = 78.6    # 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.
 # HBM traffic of one k_solve launch on the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE
 # (profiles/k_solve_config2_hbm_traffic.md); None for other workloads.  The second figure is the same
 # kernel without the per-cell counting of converged lanes (--no-slots).
-SOLVE_TRAFFIC_BYTES = {2: 286.0e6}
+SOLVE_TRAFFIC_BYTES = {2: 290.6e6}
 SOLVE_TRAFFIC_BYTES_NO_SLOTS = {2: 204.6e6}
 
 
