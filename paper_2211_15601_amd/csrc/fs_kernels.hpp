@@ -851,13 +851,6 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const
 // ------------------------------------------------------------------------------------------------
 // Backward (Eq. (11)/(12), (15)).
 // ------------------------------------------------------------------------------------------------
-__global__ void k_fill_zero(long long n, float *__restrict__ a)
-{
-    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    const long long stride = (long long)gridDim.x * blockDim.x;
-    for (; i < n; i += stride) a[i] = 0.0f;
-}
-
 // The gradient w.r.t. the transform grid, G_T[p][v] = sum over converged lanes of
 // omega_corner * lambda (x) [x*; 1], is accumulated without floating-point atomics (device-scope
 // atomics leave the L2 on this chip and are slow): converged lanes are counting-sorted by the grid
