@@ -973,18 +973,30 @@ __global__ __launch_bounds__(256) void k_grad_records(GridP G, int mode, const f
     }
 }
 
-// contribution of sorted record s to the node that is corner (da, db, dc) of the record's cell
-__device__ __forceinline__ void grad_accumulate(const GridP &G, const float *__restrict__ rec, int s, int da, int db,
-                                                int dc, float (&acc)[12])
+// fraction of x along one axis inside the cell that starts at node i0: what locate() returns for a point of
+// that cell (same clamping, same subtraction), without looking the cell up again
+__device__ __forceinline__ float frac_in_cell(float x, float lo, float inv_h, float m, int i0)
+{
+    float u = (x - lo) * inv_h;
+    u = !(u >= 0.0f) ? 0.0f : (u > m ? m : u);
+    return u - (float)i0;
+}
+
+// contribution of sorted record s, which lies in the cell with origin (cx, cy, cz), to the node that is that
+// cell's corner (da, db, dc)
+__device__ __forceinline__ void grad_accumulate(const GridP &G, const float *__restrict__ rec, int s, int cx, int cy, int cz,
+                                                int da, int db, int dc, float (&acc)[12])
 {
     const float4 *r = reinterpret_cast<const float4 *>(rec + (long long)s * GREC);
     const float4 r0 = r[0], r1 = r[1];
     const float x[3] = {r0.x, r0.y, r0.z};
     const float lam[3] = {r0.w, r1.x, r1.y};
-    const Cell c = locate(G, x);
-    const float wx = da ? c.f[0] : 1.0f - c.f[0];
-    const float wy = db ? c.f[1] : 1.0f - c.f[1];
-    const float wz = dc ? c.f[2] : 1.0f - c.f[2];
+    const float fx = frac_in_cell(x[0], G.lo[0], G.inv_h[0], G.m[0], cx);
+    const float fy = frac_in_cell(x[1], G.lo[1], G.inv_h[1], G.m[1], cy);
+    const float fz = frac_in_cell(x[2], G.lo[2], G.inv_h[2], G.m[2], cz);
+    const float wx = da ? fx : 1.0f - fx;
+    const float wy = db ? fy : 1.0f - fy;
+    const float wz = dc ? fz : 1.0f - fz;
     const float om = (wx * wy) * wz;
 #pragma unroll
     for (int rr = 0; rr < 3; ++rr) {
@@ -1169,7 +1181,9 @@ __global__ __launch_bounds__(256) void k_grad_nodes_p(GridP G, int ncell, const 
                     acc[4 * h + 3] += u.w;
                 }
             } else {
-                for (int s = ps; s < pe; ++s) grad_accumulate(G, rec, s, cn & 1, (cn >> 1) & 1, (cn >> 2) & 1, acc);
+                for (int s = ps; s < pe; ++s)
+                    grad_accumulate(G, rec, s, ix - (cn & 1), iy - ((cn >> 1) & 1), iz - ((cn >> 2) & 1), cn & 1, (cn >> 1) & 1,
+                                    (cn >> 2) & 1, acc);
             }
         }
     }
