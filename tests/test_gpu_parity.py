@@ -171,6 +171,21 @@ def test_grad_with_slots_from_solve(lib, case):
     assert st == binding.FS_E_STATE
 
 
+def test_exact_jacobian_gradient_with_slots(lib):
+    # FS_GRAD_EXACT_J with the solve's cell positions: roots and masks come from the library's result records,
+    # the inverse Jacobian is recomputed at x*; held to the strict-fp32 oracle like the array-fed path
+    w = wl.make_config(2, n_points=4001, dims=(32, 32, 8))
+    run = gu.GpuRun(w, grad_mode=binding.FS_GRAD_EXACT_J)
+    T = run.precompute()
+    xc, cv, _, _ = run.solve(fused=True, slots=True, want_J=False)
+    gxc = w.upstream_grads()
+    rW, rB, rq = oracle.grad(w.dims, w.lo, w.hi, T, w.W, w.B, xc, None, cv, gxc, mode=1, prec="f32")
+    gW, gB, gxq = run.grad(xc, None, cv, gxc, slot=run.slot)
+    for name, a, b in (("gW", gW, rW), ("gB", gB, rB), ("gxq", gxq, rq)):
+        rel = np.linalg.norm(a.astype(np.float64) - b) / max(np.linalg.norm(b.astype(np.float64)), 1e-30)
+        assert np.isfinite(a).all() and rel < 2e-5, (name, rel)
+
+
 @pytest.mark.parametrize("case", [(2, 5003, (32, 32, 8), None), (3, 16 * 250, (32, 32, 8), None), (1, 4096, None, None)], ids=_ids)
 def test_dedupe_parity(lib, case):
     # Sec. 3.1 "Remove Duplicate Correspondences": keep mask, offsets, packed roots and lane ids, bit for bit
