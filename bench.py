@@ -93,8 +93,8 @@ def main():
                     help="materialise the initial states with fs_init instead of computing them inside fs_solve")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (lanes are independent; see DESIGN.md for how the "
-              "path would shard); rerun with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on exactly one GPU (lanes are independent: several GPUs would each take a share "
+              "of the points and a copy of the transform grid); rerun with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
