@@ -554,7 +554,7 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
             k_grad_records<false><<<rg, 256, 0, st>>>(G, mode, ctx->T, d_xc, d_Jinv, d_conv, d_gxc, d_pose, N, K, ncell, ctx->gcount, pos,
                                                      grec4, d_gxq, groups, nullptr, nullptr);
     }
-    if (N > 0) k_grad_pieces<<<grid1d((long long)lanes, PIECE_R), 64, 0, st>>>(G, ncp, ctx->gcount, ctx->grec);
+    if (N > 0) k_grad_pieces<<<grid1d((long long)lanes, PIECE_R), 64 * PIECE_WAVES, 0, st>>>(G, ncp, ctx->gcount, ctx->grec);
     // crowded grids: one thread per (node, adjacent cell); sparse ones: one thread per node
     const long long nodes = (long long)G.P * G.V;
     if ((long long)lanes >= 8 * nodes)

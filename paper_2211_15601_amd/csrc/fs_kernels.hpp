@@ -1022,8 +1022,12 @@ __device__ __forceinline__ int adjacent_cell(const GridP &G, int ncell, int p, i
 constexpr int PIECE_R = 256;
 constexpr int PIECE_MIN = 96 / GREC;
 constexpr int PIECE_RPL = PIECE_R / 64;   // records per SIMD lane when a wave scans its range
+constexpr int PIECE_WAVES = 2;            // waves per range
+constexpr int PIECE_OWN = PIECE_R / PIECE_WAVES;   // records a wave loads and expands
+constexpr int PIECE_LOAD = PIECE_OWN / 64;         // ... per SIMD lane
 
-// One wave per range.  Every record of the range is expanded once (SIMD lane = record) into its 8 corner
+// One block of PIECE_WAVES waves per range: the waves share the loading and expanding of the records and
+// take the long pieces in turn.  Every record of the range is expanded once (SIMD lane = record) into its 8 corner
 // weights omega_c and its 12 products lambda_r [x*; 1]_j, staged in LDS; the sums of a piece are then the
 // matrix product  S[c][rj] = sum_t omega_c(t) * (lambda_r [x;1]_j)(t),  an 8 x len by len x 12 contraction,
 // taken four records at a time by the 16x16x4 fp32 MFMA (rows 8..15 and columns 12..15 are zero padding).
@@ -1032,31 +1036,38 @@ constexpr int PIECE_RPL = PIECE_R / 64;   // records per SIMD lane when a wave s
 constexpr int PIECE_ROW = 20;     // floats per staged record: 8 weights + 12 products
 typedef float v4f __attribute__((ext_vector_type(4)));
 
-__global__ __launch_bounds__(64) void k_grad_pieces(GridP G, long long ncp, const int *__restrict__ offset, float *rec)
+__global__ __launch_bounds__(64 * PIECE_WAVES) void k_grad_pieces(GridP G, long long ncp, const int *__restrict__ offset, float *rec)
 {
     __shared__ float4 sm4[PIECE_R * PIECE_ROW / 4];
+    __shared__ int s_cell[PIECE_R];
     float *sm = reinterpret_cast<float *>(sm4);
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const long long s = (long long)blockIdx.x * PIECE_R;
     const long long total = offset[ncp];
     if (s >= total) return;
     const int e = (int)min((long long)PIECE_R, total - s);
-    // SIMD lane l holds records l, 64 + l, 128 + l, ... of the range
-    float4 r0[PIECE_RPL], r1[PIECE_RPL];
+    // each wave loads and expands its share of the range: SIMD lane l of wave w holds records
+    // PIECE_OWN * w + l, PIECE_OWN * w + 64 + l, ...
+    float4 r0[PIECE_LOAD], r1[PIECE_LOAD];
 #pragma unroll
-    for (int b = 0; b < PIECE_RPL; ++b) {
+    for (int b = 0; b < PIECE_LOAD; ++b) {
+        const int t = PIECE_OWN * w + 64 * b + lane;
         r0[b] = r1[b] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        if (64 * b + lane < e) {
-            const float4 *r = reinterpret_cast<const float4 *>(rec + (s + 64 * b + lane) * GREC);
+        if (t < e) {
+            const float4 *r = reinterpret_cast<const float4 *>(rec + (s + t) * GREC);
             r0[b] = r[0];
             r1[b] = r[1];
         }
+        s_cell[t] = t < e ? __float_as_int(r1[b].z) : -1;
     }
-    // a record starts a piece if its cell differs from the one before it (the first of the range always does)
+    __syncthreads();
+    // every wave finds the pieces of the whole range (same data, same result): lane l looks at records
+    // l, 64 + l, 128 + l, ...; a record starts a piece if its cell differs from the one before it (the
+    // first of the range always does)
     int c[PIECE_RPL];
     bool f[PIECE_RPL];
 #pragma unroll
-    for (int b = 0; b < PIECE_RPL; ++b) c[b] = 64 * b + lane < e ? __float_as_int(r1[b].z) : -1;
+    for (int b = 0; b < PIECE_RPL; ++b) c[b] = s_cell[64 * b + lane];
 #pragma unroll
     for (int b = 0; b < PIECE_RPL; ++b) {
         int prev = __shfl_up(c[b], 1);
@@ -1086,11 +1097,11 @@ __global__ __launch_bounds__(64) void k_grad_pieces(GridP G, long long ncp, cons
         any_long = any_long || len[b] >= PIECE_MIN;
         later = min(later, __shfl(suf, 0));
     }
-    if (!__any(any_long)) return;       // nothing to summarise here (sparse lists end here)
+    if (!__any(any_long)) return;       // nothing to summarise here (sparse lists end here); same in every wave
     // expand the records
 #pragma unroll
-    for (int b = 0; b < PIECE_RPL; ++b) {
-        const int t = 64 * b + lane;
+    for (int b = 0; b < PIECE_LOAD; ++b) {
+        const int t = PIECE_OWN * w + 64 * b + lane;
         float4 o[5];
 #pragma unroll
         for (int h = 0; h < 5; ++h) o[h] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
@@ -1110,12 +1121,16 @@ __global__ __launch_bounds__(64) void k_grad_pieces(GridP G, long long ncp, cons
     }
     __syncthreads();
     const int col = lane & 15, kq = lane >> 4;
+    int turn = 0;                        // the waves take the long pieces in turn
 #pragma unroll
     for (int i = 0; i < PIECE_RPL; ++i) {
         unsigned long long m = __ballot(len[i] >= PIECE_MIN);
         while (m) {
             const int src = __ffsll((long long)m) - 1;
             m &= m - 1ull;
+            const bool mine = turn == w;
+            turn = turn + 1 == PIECE_WAVES ? 0 : turn + 1;
+            if (!mine) continue;
             const int ps = 64 * i + src, pe = ps + __shfl(len[i], src);
             // four groups per pass into four accumulators: their LDS reads are in flight together and no
             // MFMA waits for the one before it; records outside the piece enter as zeros
