@@ -86,8 +86,10 @@ fs_status fs_set_params(fs_ctx *ctx, const fs_params *params);
 /* Launch-shape knobs of the solve kernel; results never depend on them.  chunk = lanes a wave draws
  * from the work cursor at a time (8..4096; every draw is one atomic on a single counter, which serves about
  * 1e8 of them per second, so small chunks make the counter the bottleneck), refill_min = idle SIMD lanes that trigger a refill
- * (1..64), blocks_per_cu = resident 256-thread blocks per compute unit (capped by what the occupancy
- * query reports); for these a value of 0 keeps the current setting.  point_major = 1: consecutive SIMD
+ * (1..64; until it is set: 24, or 32 for voxel-based candidates and for a grid held in LDS),
+ * blocks_per_cu = resident 256-thread blocks per compute unit (capped by what the occupancy
+ * query reports; until it is set the library takes 2, or 3 where it solves the shorter list of
+ * voxel-based candidates); for these a value of 0 keeps the current setting.  point_major = 1: consecutive SIMD
  * lanes take the K initial states of one point, 0: consecutive points with the same initial state,
  * -1: keep.  lds_grid = 1: transform grids of at most 64 KiB (all poses) are copied into LDS by every
  * block of the solve and read from there, 0: always read through the caches, -1: keep. */

@@ -230,7 +230,7 @@ fs_status fs_create(const fs_grid_desc *desc, const fs_params *params, void *hip
     {
         int per_cu = 0, cus = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_solve<true, true, false>, 256, 0) != hipSuccess || per_cu < 1) per_cu = 2;
-        c->blocks_per_cu = 2;
+        c->blocks_per_cu = 0;      /* 0: chosen per call */
         c->point_major = 1;
         c->lds_grid = 1;   /* the kernel is bound by the vector-memory path: more waves only thrash the L1 */
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
@@ -238,7 +238,7 @@ fs_status fs_create(const fs_grid_desc *desc, const fs_params *params, void *hip
         c->n_cus = cus;
         c->occ_blocks_per_cu = per_cu;
         c->chunk = 128;
-        c->refill_min = 32;
+        c->refill_min = 0;         /* 0: chosen per call */
     }
     if (ok && params->init_mode == FS_INIT_VOXEL) {
         CorrP &C = c->C;
@@ -383,15 +383,20 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     S.K = K;
     S.point_major = ctx->point_major;
     S.chunk = ctx->chunk;
-    S.refill_min = ctx->refill_min;
     const long long chunks = (S.total + S.chunk - 1) / S.chunk;
     const int wpb = 4;
     const size_t grid_bytes = (size_t)ctx->G.P * ctx->G.V * 48;
     const bool lds = ctx->lds_grid && grid_bytes <= FS_LDS_GRID_MAX;
     // reading through the caches the kernel is bound by the vector-memory path and more waves only thrash
     // the L1; with the grid in LDS it is latency / ALU bound and wants every wave the registers allow
-    const int want_blocks = lds ? std::max(ctx->blocks_per_cu, 3) : ctx->blocks_per_cu;
+    // (measured: with one initial state per bone, many long trajectories, 2 blocks per CU are fastest; with
+    // the shorter list of voxel-based candidates, which start near their roots, 3)
+    const int auto_blocks = (fused && ctx->prm.init_mode == FS_INIT_VOXEL) ? 3 : 2;
+    const int set_blocks = ctx->blocks_per_cu ? ctx->blocks_per_cu : auto_blocks;
+    const int want_blocks = lds ? std::max(set_blocks, 3) : set_blocks;
     const int per_cu = std::max(1, std::min(want_blocks, ctx->occ_blocks_per_cu));
+    // refilling earlier pays where trajectories are long and the grid is read through the caches
+    S.refill_min = ctx->refill_min ? ctx->refill_min : ((auto_blocks == 2 && !lds) ? 24 : 32);
     const int blocks = (int)std::min<long long>(grid1d(chunks, wpb), (long long)per_cu * ctx->n_cus);
     InitP I;
     I.mode = ctx->prm.init_mode;

@@ -627,7 +627,7 @@ __device__ __forceinline__ void flush_slots(int (&pend)[2][64], int npend, int l
 // corner records are then read from LDS, where per-lane addresses cost far less than in the vector
 // memory path.
 template <bool FUSED, bool WITH_J, bool LDSGRID>
-__global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const float *__restrict__ Tglobal,
+__global__ __launch_bounds__(256, 3) void k_solve(GridP G, SolveP S, InitP I, const float *__restrict__ Tglobal,
                                                const float *__restrict__ xq, const int32_t *__restrict__ pose,
                                                const float *__restrict__ x0, const float *__restrict__ J0,
                                                const uint8_t *__restrict__ valid0, float4 *__restrict__ rec,
@@ -651,7 +651,7 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const
     const int lane = threadIdx.x & 63;
     // wave-uniform: the wave's current chunk is [next, c1).  The first chunk of wave w is chunk w (the cursor
     // starts behind these): 2048 waves asking one counter at once would wait 9 ns each, one after the other.
-    long long next = (long long)((blockIdx.x * blockDim.x + threadIdx.x) >> 6) * S.chunk;
+    long long next = (long long)__builtin_amdgcn_readfirstlane((int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6)) * S.chunk;
     long long c1 = min(total, next + S.chunk);
     bool exhausted = false;          // wave-uniform: the global cursor has run past the end
     const long long N = S.N;
@@ -665,7 +665,7 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const
     float q[8][12];                  // corner records of the lane's current cell, kept across iterations
     long long held = -1;             // grid offset of the cell whose corners q holds (-1: none)
     int npend = 0;                   // wave-uniform: entries of s_pend in use
-    const int wib = threadIdx.x >> 6;
+    const int wib = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
 
     while (true) {
         unsigned long long idle = __ballot(!active);
@@ -676,7 +676,7 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const
             if (next >= c1) {
                 unsigned b = 0;
                 if (lane == 0) b = atomicAdd(cursor, (unsigned)S.chunk);
-                b = (unsigned)__shfl((int)b, 0);
+                b = (unsigned)__builtin_amdgcn_readfirstlane((int)b);
                 if ((long long)b >= total) {
                     exhausted = true;
                 } else {
@@ -688,16 +688,17 @@ __global__ __launch_bounds__(256) void k_solve(GridP G, SolveP S, InitP I, const
                 const int rank = __popcll(idle & ((1ull << lane) - 1ull));
                 const long long pq = next + rank;
                 if (!active && pq < c1) {
+                    // K * N < 2^31: 32-bit division
                     if (list) {
-                        const long long e = list[pq];
-                        n = e / S.K;
-                        k = (int)(e - n * S.K);
+                        const unsigned e = (unsigned)list[pq];
+                        n = e / (unsigned)S.K;
+                        k = (int)(e - (unsigned)n * (unsigned)S.K);
                     } else if (S.point_major) {   // consecutive SIMD lanes: the K initial states of one point
-                        n = pq / S.K;
-                        k = (int)(pq - n * S.K);
+                        n = (unsigned)pq / (unsigned)S.K;
+                        k = (int)((unsigned)pq - (unsigned)n * (unsigned)S.K);
                     } else {                      // consecutive SIMD lanes: consecutive points, same initial state
-                        k = (int)(pq / N);
-                        n = pq - (long long)k * N;
+                        k = (int)((unsigned)pq / (unsigned)N);
+                        n = (unsigned)pq - (unsigned)k * (unsigned)N;
                     }
                     const int p = pose_of(pose, n, G.P);
                     pz = p;
