@@ -86,15 +86,25 @@ fs_status fs_set_params(fs_ctx *ctx, const fs_params *params);
 /* Launch-shape knobs of the solve kernel; results never depend on them.  chunk = lanes a wave draws
  * from the work cursor at a time (8..4096; every draw is one atomic on a single counter, which serves about
  * 1e8 of them per second, so small chunks make the counter the bottleneck), refill_min = idle SIMD lanes that trigger a refill
- * (1..64; until it is set: 24, or 32 for voxel-based candidates and for a grid held in LDS),
+ * (1..64; until it is set: 8, or 32 for a grid held in LDS),
  * blocks_per_cu = resident 256-thread blocks per compute unit (capped by what the occupancy
  * query reports; until it is set the library takes 2, or 3 where it solves the shorter list of
- * voxel-based candidates); for these a value of 0 keeps the current setting.  point_major = 1: consecutive SIMD
+ * voxel-based candidates on a grid of at most 32 MiB, or holds the grid in LDS); for these a value of 0
+ * keeps the current setting.  point_major = 1: consecutive SIMD
  * lanes take the K initial states of one point, 0: consecutive points with the same initial state,
  * -1: keep.  lds_grid = 1: transform grids of at most 64 KiB (all poses) are copied into LDS by every
  * block of the solve and read from there, 0: always read through the caches, -1: keep. */
 fs_status fs_set_tuning(fs_ctx *ctx, int32_t chunk, int32_t refill_min, int32_t blocks_per_cu, int32_t point_major,
                         int32_t lds_grid);
+
+/* The waves of a block of the solve kernel hand work to each other through queues in LDS (one wave prepares
+ * initial states, the others iterate), and every wait on such a queue is bounded: a wave that has polled
+ * `polls` times in vain (about 0.2 us each; default 2^22) gives up and leaves, so the kernel always ends.
+ * The call during which that happened returns FS_OK (nothing is synchronised), its results are incomplete,
+ * and every later call on the context that uses the device returns FS_E_DEVICE: destroy the context.  No healthy run
+ * comes near the default; the limit exists for tests of this path (polls = 0: the consumers give up at
+ * their first empty queue).  polls >= 0. */
+fs_status fs_set_spin_limit(fs_ctx *ctx, int32_t polls);
 
 /* Pre-compute linear blend skinning on the grid nodes, Eq. (13) / Sec. 3.1 "Pre-computing
  * LBS": T[p][v] = sum_b W[v][b] * B[p][b], bones accumulated in index order with fused

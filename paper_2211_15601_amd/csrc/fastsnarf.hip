@@ -56,7 +56,10 @@ struct fs_ctx {
     int *vlist;        // [K*N] pairs that have a candidate
     size_t vcap;       // points voffs / vlist can hold
     int scan_cap;      // tiles scan_sums can hold
-    int n_cus, occ_blocks_per_cu, chunk, refill_min, blocks_per_cu, point_major, lds_grid;
+    int n_cus, occ_blocks_per_cu, occ_ws_blocks_per_cu, chunk, refill_min, blocks_per_cu, point_major, lds_grid;
+    int spin_limit;    // polls of a work queue before a wave of the producer / consumer solve kernel gives up
+    int *gave_up;      // pinned host word, mapped into the device: a wave that gave up sets it
+    int *gave_up_dev;  // the device's address of it
     // optional timing of the Broyden kernel alone (events on the context's stream)
     bool timing;
     std::vector<std::pair<hipEvent_t, hipEvent_t>> *timed;
@@ -100,6 +103,16 @@ fs_status launch_status(fs_ctx *c, const char *what)
 {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(c, FS_E_DEVICE, "%s: %s", what, hipGetErrorString(e));
+    return FS_OK;
+}
+
+// A wave of the solve kernel that waited too long for its block's work queue has left early: the results
+// of that call are incomplete.  Seen by the first call that comes after the kernel has run; the context
+// stays in error from then on.
+fs_status check_gave_up(fs_ctx *c, const char *what)
+{
+    if (c->gave_up && *static_cast<volatile int *>(c->gave_up))
+        return fail(c, FS_E_DEVICE, "%s: an earlier fs_solve did not finish (a wave of its kernel gave up waiting for its block's work queue); create a new context", what);
     return FS_OK;
 }
 
@@ -229,7 +242,11 @@ fs_status fs_create(const fs_grid_desc *desc, const fs_params *params, void *hip
               dev_alloc(&c->Bok, P * nb) && dev_alloc(&c->cursor, 4);
     {
         int per_cu = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_solve<true, true, false>, 256, 0) != hipSuccess || per_cu < 1) per_cu = 2;
+        int per_cu_ws = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_solve<true, true>, 256, 0) != hipSuccess || per_cu < 1) per_cu = 2;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_ws, k_solve_ws<true, true, FS_WS_CONSUMERS>, 64 * (FS_WS_CONSUMERS + 1), 0) != hipSuccess || per_cu_ws < 1) per_cu_ws = 2;
+        c->occ_ws_blocks_per_cu = per_cu_ws;
+        c->spin_limit = 1 << 22;   /* x about 0.2 us per poll */
         c->blocks_per_cu = 0;      /* 0: chosen per call */
         c->point_major = 1;
         c->lds_grid = 1;   /* the kernel is bound by the vector-memory path: more waves only thrash the L1 */
@@ -248,8 +265,17 @@ fs_status fs_create(const fs_grid_desc *desc, const fs_params *params, void *hip
              dev_alloc(&c->cell_of, P * V) && dev_alloc(&c->count, P * C.ncell + 1) && dev_alloc(&c->fill, P * V) &&
              dev_alloc(&c->order, P * V) && dev_alloc(&c->cand, P * (size_t)C.ncell * C.ck);
     }
+    if (ok) {
+        ok = hipHostMalloc(reinterpret_cast<void **>(&c->gave_up), sizeof(int), hipHostMallocMapped) == hipSuccess;
+        if (ok) {
+            *c->gave_up = 0;
+            ok = hipHostGetDevicePointer(reinterpret_cast<void **>(&c->gave_up_dev), c->gave_up, 0) == hipSuccess;
+        }
+        if (!ok) (void)hipGetLastError();
+    }
     if (!ok) {
         free_all(c);
+        if (c->gave_up) (void)hipHostFree(c->gave_up);
         delete c;
         return FS_E_ALLOC;
     }
@@ -269,6 +295,7 @@ fs_status fs_destroy(fs_ctx *ctx)
         delete ctx->timed;
     }
     free_all(ctx);
+    if (ctx->gave_up) (void)hipHostFree(ctx->gave_up);
     delete ctx;
     return FS_OK;
 }
@@ -300,9 +327,18 @@ fs_status fs_set_tuning(fs_ctx *ctx, int32_t chunk, int32_t refill_min, int32_t 
     return FS_OK;
 }
 
+fs_status fs_set_spin_limit(fs_ctx *ctx, int32_t polls)
+{
+    if (!ctx) return FS_E_ARG;
+    if (polls < 0) return fail(ctx, FS_E_ARG, "fs_set_spin_limit: polls must be >= 0");
+    ctx->spin_limit = polls;
+    return FS_OK;
+}
+
 fs_status fs_precompute(fs_ctx *ctx, const float *d_W, const float *d_B)
 {
     if (!ctx) return FS_E_ARG;
+    { fs_status gs = check_gave_up(ctx, "fs_precompute"); if (gs != FS_OK) return gs; }
     FS_CHECK_PTR(ctx, d_W, false);
     FS_CHECK_PTR(ctx, d_B, false);
     const GridP &G = ctx->G;
@@ -329,6 +365,7 @@ fs_status fs_init(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_t
                   uint8_t *d_valid0)
 {
     if (!ctx) return FS_E_ARG;
+    { fs_status gs = check_gave_up(ctx, "fs_init"); if (gs != FS_OK) return gs; }
     if (!ctx->have_T) return fail(ctx, FS_E_STATE, "fs_init: call fs_precompute first");
     const int K = lanes_K(ctx);
     if (N < 0 || (long long)N * K >= (1ll << 31)) return fail(ctx, FS_E_SHAPE, "fs_init: need 0 <= N and K*N < 2^31");
@@ -354,6 +391,7 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
                    uint8_t *d_iters, int32_t *d_slot)
 {
     if (!ctx) return FS_E_ARG;
+    { fs_status gs = check_gave_up(ctx, "fs_solve"); if (gs != FS_OK) return gs; }
     if (!ctx->have_T) return fail(ctx, FS_E_STATE, "fs_solve: call fs_precompute first");
     if (K != lanes_K(ctx)) return fail(ctx, FS_E_SHAPE, "fs_solve: K = %d but the init mode produces %d lanes per point", K, lanes_K(ctx));
     if (N < 0 || (long long)N * K >= (1ll << 31)) return fail(ctx, FS_E_SHAPE, "fs_solve: need 0 <= N and K*N < 2^31");
@@ -383,20 +421,21 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     S.K = K;
     S.point_major = ctx->point_major;
     S.chunk = ctx->chunk;
+    S.spin_limit = ctx->spin_limit;
     const long long chunks = (S.total + S.chunk - 1) / S.chunk;
-    const int wpb = 4;
     const size_t grid_bytes = (size_t)ctx->G.P * ctx->G.V * 48;
     const bool lds = ctx->lds_grid && grid_bytes <= FS_LDS_GRID_MAX;
-    // reading through the caches the kernel is bound by the vector-memory path and more waves only thrash
-    // the L1; with the grid in LDS it is latency / ALU bound and wants every wave the registers allow
-    // (measured: with one initial state per bone, many long trajectories, 2 blocks per CU are fastest; with
-    // the shorter list of voxel-based candidates, which start near their roots, 3)
-    const int auto_blocks = (fused && ctx->prm.init_mode == FS_INIT_VOXEL) ? 3 : 2;
-    const int set_blocks = ctx->blocks_per_cu ? ctx->blocks_per_cu : auto_blocks;
-    const int want_blocks = lds ? std::max(set_blocks, 3) : set_blocks;
-    const int per_cu = std::max(1, std::min(want_blocks, ctx->occ_blocks_per_cu));
-    // refilling earlier pays where trajectories are long and the grid is read through the caches
-    S.refill_min = ctx->refill_min ? ctx->refill_min : ((auto_blocks == 2 && !lds) ? 24 : 32);
+    // Launch shape.  Grid in LDS (k_solve): latency / ALU bound, every wave the registers allow, refill at 32 idle
+    // lanes.  Grid read through the caches (k_solve_ws, bound by the vector-memory path, where more waves thrash
+    // the L1): blocks of one producer and FS_WS_CONSUMERS consumers; measured fastest with 2 blocks per CU for one
+    // initial state per bone (many long trajectories) and for grids far beyond the L2, and with 3 for the shorter
+    // list of voxel-based candidates, which start near their roots, on a grid the L2 holds; consumers refill from
+    // their queue at 8 idle lanes (4 ... 16: no difference).
+    const int wpb = lds ? 4 : 1;       // waves of a block that draw chunks from the cursor
+    const int auto_blocks = lds ? 3 : ((fused && ctx->prm.init_mode == FS_INIT_VOXEL && grid_bytes <= (32u << 20)) ? 3 : 2);
+    const int want_blocks = ctx->blocks_per_cu ? (lds ? std::max(ctx->blocks_per_cu, 3) : ctx->blocks_per_cu) : auto_blocks;
+    const int per_cu = std::max(1, std::min(want_blocks, lds ? ctx->occ_blocks_per_cu : ctx->occ_ws_blocks_per_cu));
+    S.refill_min = ctx->refill_min ? ctx->refill_min : (lds ? 32 : 8);
     const int blocks = (int)std::min<long long>(grid1d(chunks, wpb), (long long)per_cu * ctx->n_cus);
     InitP I;
     I.mode = ctx->prm.init_mode;
@@ -437,7 +476,8 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     const int ncell = (ctx->G.nx - 1) * (ctx->G.ny - 1) * (ctx->G.nz - 1);
     int *cell_count = nullptr;
     ctx->slots_N = 0;
-    // every wave owns the chunk of its own number to begin with; the shared cursor starts behind those
+    // every wave that draws chunks (all four of a k_solve block, the producer of a k_solve_ws block) owns the
+    // chunk of its own number to begin with; the shared cursor starts behind those
     const unsigned cursor0 = (unsigned)((long long)blocks * wpb * S.chunk);
     if (d_slot) {
         const long long ncp = (long long)ctx->G.P * ncell;
@@ -448,25 +488,29 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     } else {
         k_reset_cursor<<<1, 64, 0, st>>>(ctx->cursor, cursor0);
     }
-    const dim3 grd(blocks), blk(wpb * WAVE);
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     if (ctx->timing && hipEventCreate(&ev0) == hipSuccess && hipEventCreate(&ev1) == hipSuccess) (void)hipEventRecord(ev0, st);
-    const size_t shm = lds ? grid_bytes : 0;
-#define FS_LAUNCH_SOLVE(F, J, L)                                                                                      \
-    k_solve<F, J, L><<<grd, blk, shm, st>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, d_x0, d_Jinv0, d_valid0, ctx->srec, \
-                                            ctx->cursor, list, list_len, cell_count, ncell, d_slot)
     if (lds) {
-        if (fused && with_J) FS_LAUNCH_SOLVE(true, true, true);
-        else if (fused) FS_LAUNCH_SOLVE(true, false, true);
-        else if (with_J) FS_LAUNCH_SOLVE(false, true, true);
-        else FS_LAUNCH_SOLVE(false, false, true);
-    } else {
-        if (fused && with_J) FS_LAUNCH_SOLVE(true, true, false);
-        else if (fused) FS_LAUNCH_SOLVE(true, false, false);
-        else if (with_J) FS_LAUNCH_SOLVE(false, true, false);
-        else FS_LAUNCH_SOLVE(false, false, false);
-    }
+#define FS_LAUNCH_SOLVE(F, J)                                                                                          \
+    k_solve<F, J><<<dim3(blocks), dim3(4 * WAVE), grid_bytes, st>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, d_x0, d_Jinv0, \
+                                                                    d_valid0, ctx->srec, ctx->cursor, list, list_len,  \
+                                                                    cell_count, ncell, d_slot)
+        if (fused && with_J) FS_LAUNCH_SOLVE(true, true);
+        else if (fused) FS_LAUNCH_SOLVE(true, false);
+        else if (with_J) FS_LAUNCH_SOLVE(false, true);
+        else FS_LAUNCH_SOLVE(false, false);
 #undef FS_LAUNCH_SOLVE
+    } else {
+#define FS_LAUNCH_SOLVE(F, J)                                                                                          \
+    k_solve_ws<F, J, FS_WS_CONSUMERS><<<dim3(blocks), dim3((FS_WS_CONSUMERS + 1) * WAVE), 0, st>>>(                    \
+        ctx->G, S, I, ctx->T, d_xq, d_pose, d_x0, d_Jinv0, d_valid0, ctx->srec, ctx->cursor, list, list_len, cell_count,  \
+        ncell, d_slot, ctx->gave_up_dev)
+        if (fused && with_J) FS_LAUNCH_SOLVE(true, true);
+        else if (fused) FS_LAUNCH_SOLVE(true, false);
+        else if (with_J) FS_LAUNCH_SOLVE(false, true);
+        else FS_LAUNCH_SOLVE(false, false);
+#undef FS_LAUNCH_SOLVE
+    }
     if (ev0 && ev1) {
         (void)hipEventRecord(ev1, st);
         ctx->timed->emplace_back(ev0, ev1);
@@ -495,6 +539,7 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
                   float *d_gB, float *d_gxq)
 {
     if (!ctx) return FS_E_ARG;
+    { fs_status gs = check_gave_up(ctx, "fs_grad"); if (gs != FS_OK) return gs; }
     if (!ctx->have_T) return fail(ctx, FS_E_STATE, "fs_grad: call fs_precompute first");
     if (K < 1 || K > FS_MAX_BONES) return fail(ctx, FS_E_SHAPE, "fs_grad: K out of range");
     if (N < 0 || (long long)N * K >= (1ll << 31)) return fail(ctx, FS_E_SHAPE, "fs_grad: need 0 <= N and K*N < 2^31");
@@ -583,6 +628,7 @@ fs_status fs_dedupe(fs_ctx *ctx, const float *d_xc, const uint8_t *d_conv, int64
                     uint8_t *d_keep, int32_t *d_offsets, float *d_roots, int32_t *d_lane, int64_t cap)
 {
     if (!ctx) return FS_E_ARG;
+    { fs_status gs = check_gave_up(ctx, "fs_dedupe"); if (gs != FS_OK) return gs; }
     if (K < 1 || K > FS_MAX_BONES) return fail(ctx, FS_E_SHAPE, "fs_dedupe: K must be in 1..%d", (int)FS_MAX_BONES);
     if (N < 0 || (long long)N * K >= (1ll << 31)) return fail(ctx, FS_E_SHAPE, "fs_dedupe: need 0 <= N and K*N < 2^31");
     if (!(min_dist >= 0.0f) || !std::isfinite(min_dist)) return fail(ctx, FS_E_ARG, "fs_dedupe: min_dist must be finite and >= 0");
@@ -617,6 +663,7 @@ fs_status fs_set_timing(fs_ctx *ctx, int32_t enable)
 fs_status fs_get_timing(fs_ctx *ctx, double *solve_kernel_ms, int32_t *launches)
 {
     if (!ctx || !solve_kernel_ms || !launches) return FS_E_ARG;
+    { fs_status gs = check_gave_up(ctx, "fs_get_timing"); if (gs != FS_OK) return gs; }
     *solve_kernel_ms = 0.0;
     *launches = 0;
     if (!ctx->timed) return FS_OK;

@@ -479,6 +479,7 @@ struct SolveP {
     float tol2, div2;
     int K;
     int point_major;     // order in which pairs are handed out
+    int spin_limit;      // producer / consumer kernel: polls of a work queue before a wave gives up
 };
 
 __device__ __forceinline__ int cell_linear(const GridP &G, const Cell &c)
@@ -612,6 +613,9 @@ __device__ __forceinline__ void flush_slots(int (&pend)[2][64], int npend, int l
     __builtin_amdgcn_wave_barrier();
 }
 
+// Broyden solve for a transform grid (all poses) small enough to be held in LDS: every block copies it there
+// first and all corner records are then read from LDS, where per-lane addresses cost far less than in the
+// vector memory path.  Every wave does everything:
 // FUSED = false: initial states are read from x0 / J0 / valid0.  FUSED = true: a lane computes its
 // initial state when it picks up a pair (Sec. 3.1 "Custom CUDA Kernel": the kernel first computes the
 // initialisation states); the corner records fetched for the Jacobian then also serve the first
@@ -623,10 +627,7 @@ __device__ __forceinline__ void flush_slots(int (&pend)[2][64], int npend, int l
 // Record: WITH_J ? 16 floats {x*[3], flags, J~[9], pad[3]} : 4 floats {x*[3], flags} (who needs no J~ reads only
 // the first 16 bytes);
 // flags = conv | iters << 8 (as an integer bit pattern).
-// LDSGRID: the whole transform grid (all poses) fits in LDS; every block copies it there first and all
-// corner records are then read from LDS, where per-lane addresses cost far less than in the vector
-// memory path.
-template <bool FUSED, bool WITH_J, bool LDSGRID>
+template <bool FUSED, bool WITH_J>
 __global__ __launch_bounds__(256, 3) void k_solve(GridP G, SolveP S, InitP I, const float *__restrict__ Tglobal,
                                                const float *__restrict__ xq, const int32_t *__restrict__ pose,
                                                const float *__restrict__ x0, const float *__restrict__ J0,
@@ -638,14 +639,13 @@ __global__ __launch_bounds__(256, 3) void k_solve(GridP G, SolveP S, InitP I, co
     extern __shared__ float4 s_grid[];
     // converged lanes waiting for their position in their grid cell's list: {cell, pair} per wave
     __shared__ int s_pend[4][2][64];
-    const float *T = Tglobal;
-    if (LDSGRID) {
+    {
         const int n4 = (int)((long long)G.P * G.V * 3);      // float4 per record: 3
         const float4 *src = reinterpret_cast<const float4 *>(Tglobal);
         for (int i = threadIdx.x; i < n4; i += blockDim.x) s_grid[i] = src[i];
         __syncthreads();
-        T = reinterpret_cast<const float *>(s_grid);
     }
+    const float *T = reinterpret_cast<const float *>(s_grid);
     // with a list only the pairs list[0 .. *list_len) (encoded n*K + k) are solved
     const long long total = list ? (long long)*list_len : S.total;
     const int lane = threadIdx.x & 63;
@@ -845,6 +845,355 @@ __global__ __launch_bounds__(256, 3) void k_solve(GridP G, SolveP S, InitP I, co
                 npend = 0;
             }
         }
+    }
+    if (WITH_J && cell_count && npend > 0) flush_slots(s_pend[wib], npend, lane, cell_count, slot_out);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Broyden solve with the work divided between the waves of a block.  One wave (the producer) prepares
+// pairs 64 at a time, every SIMD lane busy: initial state, first evaluation of the field, first step; pairs
+// that end there (invalid state, converged or diverged at x0) it answers itself.  The other waves (the
+// consumers) only iterate: each owns a queue of prepared states {x', x, g, dx, J~, pair} in LDS, its idle
+// lanes pick states up with a few LDS reads, and its loop holds nothing but the Broyden step.  The producer
+// gives every batch to the consumer whose queue is emptiest.  Neither role ever holds the other's registers.
+// Queues: single producer, single consumer; tail is written by the producer only, head by the consumer only.
+// Every wait is bounded: a wave that has polled its queue S.spin_limit times in vain raises *give_up (host-visible)
+// and leaves; the producer raises s_done on its way out in any case, so its consumers leave too.
+// ------------------------------------------------------------------------------------------------
+constexpr int WS_RING = 128;                 // entries per queue (two batches)
+constexpr int FS_WS_CONSUMERS = 3;           // measured: one producer keeps up with three consumers, not with four
+constexpr int ST_XP = 0, ST_X = 3, ST_G = 6, ST_DX = 9, ST_J = 12, ST_N = 21, ST_K = 22, ST_P = 23, ST_FIELDS = 24;
+
+__device__ __forceinline__ int lds_load_acquire(const int *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+__device__ __forceinline__ void lds_store_release(int *p, int v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
+__device__ __forceinline__ void park_slots(bool want_slot, int slot_cell, int pair, int (&pend)[2][64], int &npend, int lane,
+                                           int *__restrict__ cell_count, int32_t *__restrict__ slot_out)
+{
+    const unsigned long long m = __ballot(want_slot);
+    if (m) {
+        if (npend + __popcll(m) > 64) {
+            flush_slots(pend, npend, lane, cell_count, slot_out);
+            npend = 0;
+        }
+        if (want_slot) {
+            const int at = npend + __popcll(m & ((1ull << lane) - 1ull));
+            pend[0][at] = slot_cell;
+            pend[1][at] = pair;
+        }
+        npend += __popcll(m);
+    }
+    if (npend >= 48) {
+        flush_slots(pend, npend, lane, cell_count, slot_out);
+        npend = 0;
+    }
+}
+
+template <bool FUSED, bool WITH_J, int NCONS>
+__global__ __launch_bounds__(64 * (NCONS + 1), 3) void k_solve_ws(GridP G, SolveP S, InitP I, const float *__restrict__ T,
+                                               const float *__restrict__ xq, const int32_t *__restrict__ pose,
+                                               const float *__restrict__ x0, const float *__restrict__ J0,
+                                               const uint8_t *__restrict__ valid0, float4 *__restrict__ rec,
+                                               unsigned *__restrict__ cursor, const int *__restrict__ list,
+                                               const int *__restrict__ list_len, int *__restrict__ cell_count,
+                                               int ncell, int32_t *__restrict__ slot_out, int *__restrict__ give_up)
+{
+    __shared__ float s_ring[NCONS][ST_FIELDS][WS_RING];
+    __shared__ int s_tail[NCONS], s_head[NCONS], s_done;
+    __shared__ int s_pend[NCONS + 1][2][64];
+    if (threadIdx.x < NCONS) {
+        s_tail[threadIdx.x] = 0;
+        s_head[threadIdx.x] = 0;
+    }
+    if (threadIdx.x == 0) s_done = 0;
+    __syncthreads();
+    const long long total = list ? (long long)*list_len : S.total;
+    const int lane = threadIdx.x & 63;
+    const int wib = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const long long N = S.N;
+    int npend = 0;                   // wave-uniform: entries of s_pend in use
+
+    if (wib == NCONS) {
+        // ------------------------------------------------ producer ------------------------------------------------
+        // the first chunk of block b is chunk b; the shared cursor starts behind those
+        long long next = (long long)blockIdx.x * S.chunk;
+        long long c1 = min(total, next + S.chunk);
+        int tails[NCONS];
+#pragma unroll
+        for (int c = 0; c < NCONS; ++c) tails[c] = 0;
+        bool lost = false;
+        while (!lost) {
+            if (next >= c1) {
+                unsigned b = 0;
+                if (lane == 0) b = atomicAdd(cursor, (unsigned)S.chunk);
+                b = (unsigned)__builtin_amdgcn_readfirstlane((int)b);
+                if ((long long)b >= total) break;
+                next = b;
+                c1 = min(total, (long long)b + S.chunk);
+            }
+            const long long pq = next + lane;
+            next += min(64ll, c1 - next);
+            bool keep = false, want_slot = false;
+            int slot_cell = 0, pair = 0;
+            int nn = 0, nk = 0, np = 0;
+            float nxp[3] = {0, 0, 0}, nx[3] = {0, 0, 0}, ng[3] = {0, 0, 0}, ndx[3] = {0, 0, 0};
+            float nJ[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+            if (pq < c1) {
+                const unsigned upq = (unsigned)pq;        // K * N < 2^31
+                if (list) {
+                    const unsigned e = (unsigned)list[pq];
+                    nn = (int)(e / (unsigned)S.K);
+                    nk = (int)(e - (unsigned)nn * (unsigned)S.K);
+                } else if (S.point_major) {   // consecutive SIMD lanes: the K initial states of one point
+                    nn = (int)(upq / (unsigned)S.K);
+                    nk = (int)(upq - (unsigned)nn * (unsigned)S.K);
+                } else {                      // consecutive SIMD lanes: consecutive points, same initial state
+                    nk = (int)(upq / (unsigned)N);
+                    nn = (int)(upq - (unsigned)nk * (unsigned)N);
+                }
+                np = pose_of(pose, nn, G.P);
+                pair = (int)((long long)nk * N + nn);
+                const float *Tn = T + (long long)np * G.V * 12;
+                bool ok, norec = false;     // norec: no record needed, k_solve_unpack knows the answer
+#pragma unroll
+                for (int r = 0; r < 3; ++r) nxp[r] = xq[r * N + nn];
+                if (FUSED) {
+                    if (I.mode == 0) {
+                        const float *bi = I.Binv + ((long long)np * G.nb + nk) * 12;
+                        ok = I.Bok[np * G.nb + nk] != 0;
+                        if (ok) {
+                            const float y[3] = {nxp[0] - bi[9], nxp[1] - bi[10], nxp[2] - bi[11]};
+#pragma unroll
+                            for (int r = 0; r < 3; ++r)
+                                nx[r] = FS_FMA(bi[r * 3 + 0], y[0], FS_FMA(bi[r * 3 + 1], y[1], bi[r * 3 + 2] * y[2]));
+                        }
+                    } else {
+                        const int cidx = cell_index(I.C, I.bbox + np * 6, nxp);
+                        const int v = I.cand[((long long)np * I.C.ncell + cidx) * I.C.ck + nk];
+                        ok = v >= 0;
+                        norec = !ok;
+                        if (ok) node_pos(G, v, nx);
+                    }
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 3; ++r) nx[r] = x0[((long long)nk * 3 + r) * N + nn];
+#pragma unroll
+                    for (int e = 0; e < 9; ++e) nJ[e] = J0[((long long)nk * 9 + e) * N + nn];
+                    ok = valid0[(long long)nk * N + nn] != 0;
+                }
+                if (ok) {
+                    const Cell c0 = locate(G, nx);
+                    float qn[8][12];
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) load12(Tn + c0.base + corner_off(G, c), qn[c]);
+                    float d[3];
+                    if (FUSED) {
+                        float Jac[9];
+                        jacobian_from_corners(G, c0, qn, nx, d, Jac);      // d: the same arithmetic as blend_apply
+                        ok = inv3(Jac, nJ);
+                        if (!ok) {
+#pragma unroll
+                            for (int e = 0; e < 9; ++e) nJ[e] = 0.0f;
+                        }
+                    } else {
+                        blend_apply(c0, qn, nx, d);
+                    }
+                    if (ok) {
+#pragma unroll
+                        for (int r = 0; r < 3; ++r) ng[r] = d[r] - nxp[r];
+                        const float r2 = FS_FMA(ng[2], ng[2], FS_FMA(ng[1], ng[1], ng[0] * ng[0]));
+                        const bool conv = r2 < S.tol2;
+                        if (conv || !(r2 < S.div2) || 0 >= S.max_iters) {
+                            write_record<WITH_J>(rec, pair, nx, nJ, conv ? 1 : 0);
+                            if (WITH_J && cell_count && conv) {
+                                want_slot = true;
+                                slot_cell = np * ncell + cell_linear(G, c0);
+                            }
+                        } else {
+                            keep = true;
+#pragma unroll
+                            for (int r = 0; r < 3; ++r)
+                                ndx[r] = -FS_FMA(nJ[r * 3 + 2], ng[2], FS_FMA(nJ[r * 3 + 1], ng[1], nJ[r * 3] * ng[0]));
+                        }
+                    }
+                }
+                if (!ok && !norec) write_record<WITH_J>(rec, pair, nx, nJ, 0);
+            }
+            const unsigned long long km = __ballot(keep);
+            const int nkeep = __popcll(km);
+            if (nkeep > 0) {
+                // the consumer with the emptiest queue takes the batch; wait while none has room
+                int best = 0, room = -1, spins = 0;
+                while (true) {
+#pragma unroll
+                    for (int c = 0; c < NCONS; ++c) {
+                        const int r = WS_RING - (tails[c] - __builtin_amdgcn_readfirstlane(lds_load_acquire(&s_head[c])));
+                        if (r > room) { room = r; best = c; }
+                    }
+                    if (room >= nkeep) break;
+                    room = -1;
+                    if (++spins > S.spin_limit) { lost = true; break; }
+                    __builtin_amdgcn_s_sleep(8);
+                }
+                if (lost) break;
+                int tl = 0;
+#pragma unroll
+                for (int c = 0; c < NCONS; ++c) if (c == best) tl = tails[c];
+                if (keep) {
+                    const int at = (tl + __popcll(km & ((1ull << lane) - 1ull))) & (WS_RING - 1);
+                    float (&ring)[ST_FIELDS][WS_RING] = s_ring[best];
+#pragma unroll
+                    for (int r = 0; r < 3; ++r) {
+                        ring[ST_XP + r][at] = nxp[r];
+                        ring[ST_X + r][at] = nx[r];
+                        ring[ST_G + r][at] = ng[r];
+                        ring[ST_DX + r][at] = ndx[r];
+                    }
+#pragma unroll
+                    for (int e = 0; e < 9; ++e) ring[ST_J + e][at] = nJ[e];
+                    ring[ST_N][at] = __int_as_float(nn);
+                    ring[ST_K][at] = __int_as_float(nk);
+                    ring[ST_P][at] = __int_as_float(np);
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                __builtin_amdgcn_wave_barrier();
+                tl += nkeep;
+#pragma unroll
+                for (int c = 0; c < NCONS; ++c) if (c == best) tails[c] = tl;
+                if (lane == 0) lds_store_release(&s_tail[best], tl);
+            }
+            if (WITH_J && cell_count) park_slots(want_slot, slot_cell, pair, s_pend[wib], npend, lane, cell_count, slot_out);
+        }
+        if (lost && lane == 0) *give_up = 1;
+        if (WITH_J && cell_count && npend > 0) flush_slots(s_pend[wib], npend, lane, cell_count, slot_out);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        if (lane == 0) lds_store_release(&s_done, 1);
+        return;
+    }
+
+    // ---------------------------------------------------- consumer ----------------------------------------------------
+    float (&ring)[ST_FIELDS][WS_RING] = s_ring[wib];
+    bool active = false;
+    int n = 0, k = 0, it = 0, pz = 0, head = 0, spins = 0;
+    const float *Tp = T;
+    float xp[3] = {0, 0, 0}, x[3] = {0, 0, 0}, xt[3] = {0, 0, 0}, g[3] = {0, 0, 0}, dx[3] = {0, 0, 0};
+    float J[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+    float q[8][12];                  // corner records of the lane's current cell, kept across iterations
+    long long held = -1;             // grid offset of the cell whose corners q holds (-1: none)
+    bool run = true;                 // wave-uniform
+    while (run) {
+        const unsigned long long idle = __ballot(!active);
+        const int nidle = __popcll(idle);
+        if (nidle >= S.refill_min) {
+            const int tail = __builtin_amdgcn_readfirstlane(lds_load_acquire(&s_tail[wib]));
+            const int avail = tail - head;
+            if (avail > 0) {
+                const int rank = __popcll(idle & ((1ull << lane) - 1ull));
+                if (!active && rank < avail) {
+                    const int e = (head + rank) & (WS_RING - 1);
+#pragma unroll
+                    for (int r = 0; r < 3; ++r) {
+                        xp[r] = ring[ST_XP + r][e];
+                        x[r] = ring[ST_X + r][e];
+                        g[r] = ring[ST_G + r][e];
+                        dx[r] = ring[ST_DX + r][e];
+                    }
+#pragma unroll
+                    for (int c = 0; c < 9; ++c) J[c] = ring[ST_J + c][e];
+                    n = __float_as_int(ring[ST_N][e]);
+                    k = __float_as_int(ring[ST_K][e]);
+                    pz = __float_as_int(ring[ST_P][e]);
+#pragma unroll
+                    for (int r = 0; r < 3; ++r) xt[r] = x[r] + dx[r];
+                    Tp = T + (long long)pz * G.V * 12;
+                    it = 0;
+                    held = -1;
+                    active = true;
+                }
+                head += min(nidle, avail);
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");      // the reads above are done
+                __builtin_amdgcn_wave_barrier();
+                if (lane == 0) lds_store_release(&s_head[wib], head);
+            }
+        }
+        if (!__any(active)) {
+            // nothing in flight: more to come?  (s_done is read before the tail: the producer raises it last)
+            const int d = __builtin_amdgcn_readfirstlane(lds_load_acquire(&s_done));
+            const int tail = __builtin_amdgcn_readfirstlane(lds_load_acquire(&s_tail[wib]));
+            if (tail == head) {
+                if (d) {
+                    run = false;
+                } else if (++spins > S.spin_limit) {
+                    if (lane == 0) *give_up = 1;
+                    run = false;
+                } else {
+                    __builtin_amdgcn_s_sleep(8);
+                }
+            }
+        } else {
+            spins = 0;
+        }
+        bool want_slot = false;
+        int slot_cell = 0;
+        if (active) {
+            float d[3], gn[3];
+            const Cell cell = locate(G, xt);
+            const long long want = (long long)(Tp - T) + cell.base;
+            if (want != held) {
+#pragma unroll
+                for (int c = 0; c < 8; ++c) load12(Tp + cell.base + corner_off(G, c), q[c]);
+                held = want;
+            }
+            blend_apply(cell, q, xt, d);
+#pragma unroll
+            for (int r = 0; r < 3; ++r) gn[r] = d[r] - xp[r];
+            float dg[3], v[3], u[3];
+#pragma unroll
+            for (int r = 0; r < 3; ++r) dg[r] = gn[r] - g[r];
+#pragma unroll
+            for (int c = 0; c < 3; ++c) v[c] = FS_FMA(dx[2], J[6 + c], FS_FMA(dx[1], J[3 + c], dx[0] * J[c]));
+#pragma unroll
+            for (int r = 0; r < 3; ++r)
+                u[r] = dx[r] - FS_FMA(J[r * 3 + 2], dg[2], FS_FMA(J[r * 3 + 1], dg[1], J[r * 3] * dg[0]));
+            const float den = FS_FMA(v[2], dg[2], FS_FMA(v[1], dg[1], v[0] * dg[0]));
+            if (den != 0.0f && __builtin_fabsf(den) < __builtin_inff()) {
+                const float rinv = 1.0f / den;
+#pragma unroll
+                for (int r = 0; r < 3; ++r) {
+                    const float sc = u[r] * rinv;
+#pragma unroll
+                    for (int c = 0; c < 3; ++c) J[r * 3 + c] = FS_FMA(sc, v[c], J[r * 3 + c]);
+                }
+            }
+            ++it;
+#pragma unroll
+            for (int r = 0; r < 3; ++r) { x[r] = xt[r]; g[r] = gn[r]; }
+            const float r2 = FS_FMA(g[2], g[2], FS_FMA(g[1], g[1], g[0] * g[0]));
+            const bool conv = r2 < S.tol2;
+            const bool done = conv || !(r2 < S.div2) || it >= S.max_iters;
+            if (done) {
+                write_record<WITH_J>(rec, (long long)k * N + n, x, J, (conv ? 1 : 0) | (it << 8));
+                if (WITH_J && cell_count && conv) {
+                    want_slot = true;
+                    slot_cell = pz * ncell + cell_linear(G, cell);
+                }
+                active = false;
+            } else {
+#pragma unroll
+                for (int r = 0; r < 3; ++r) {
+                    dx[r] = -FS_FMA(J[r * 3 + 2], g[2], FS_FMA(J[r * 3 + 1], g[1], J[r * 3] * g[0]));
+                    xt[r] = x[r] + dx[r];
+                }
+            }
+        }
+        if (WITH_J && cell_count)
+            park_slots(want_slot, slot_cell, (int)((long long)k * N + n), s_pend[wib], npend, lane, cell_count, slot_out);
     }
     if (WITH_J && cell_count && npend > 0) flush_slots(s_pend[wib], npend, lane, cell_count, slot_out);
 }

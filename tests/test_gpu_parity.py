@@ -315,15 +315,19 @@ def test_autograd_hook_matches_oracle_gradient(lib):
 @pytest.mark.parametrize("shape", [((2, 2, 2), 1, 1, 40), ((5, 4, 3), 5, 3, 1000), ((7, 3, 9), 17, 2, 777),
                                    ((4, 6, 5), 33, 1, 513), ((3, 3, 3), 64, 2, 300), ((9, 8, 7), 3, 4, 20011)],
                          ids=lambda t: f"g{t[0]}-b{t[1]}-p{t[2]}-n{t[3]}")
-def test_odd_shapes_full_path(lib, shape):
+@pytest.mark.parametrize("lds_grid", [1, 0], ids=["grid_in_lds", "grid_cached"])
+def test_odd_shapes_full_path(lib, shape, lds_grid):
     # bone counts on both sides of the 16-bone MFMA tiles and of the 4-wide weight reads, grids down to one cell,
-    # several poses, ragged N: transform grid, solve and both gradient paths against the oracle
+    # several poses, ragged N: transform grid, solve (both solve kernels: the one that holds these small grids
+    # in LDS, and the producer / consumer one that reads them through the caches) and both gradient paths
+    # against the oracle
     dims, nb, P, n = shape
     s = wl.random_affine_scene(100 + nb, dims=dims, n_bones=nb, n_poses=P, n_points=n)
     w = wl.Workload("odd", s["dims"], nb, P, s["lo"], s["hi"], s["W"], s["B"], s["x"], s["pose"], s["x"],
                     1e-5, 10.0, 50, wl.INIT_BONE, nb, (4, 4, 4, 3))
     pose = w.pose if P > 1 else None
     run = gu.GpuRun(w)
+    run.ctx.set_tuning(lds_grid=lds_grid)
     T = run.precompute()
     T_ref = oracle.precompute(w.dims, w.W, w.B, prec="f32")
     np.testing.assert_array_equal(T.view(np.uint32), T_ref.view(np.uint32))
@@ -362,10 +366,12 @@ def test_one_hot_weights_closed_form_on_gpu(lib):
         np.testing.assert_allclose(xc[kk], ref, atol=2e-6)
 
 
-def test_edge_cases(lib):
+@pytest.mark.parametrize("lds_grid", [1, 0], ids=["grid_in_lds", "grid_cached"])
+def test_edge_cases(lib, lds_grid):
     w = wl.make_config(1, n_points=77, dims=(8, 8, 4))
     run = gu.GpuRun(w)
     ctx = run.ctx
+    ctx.set_tuning(lds_grid=lds_grid)
     N, K = w.N, w.K
     z = lambda *s, dt=torch.float32: torch.zeros(s, dtype=dt, device=gu.DEV)
     x0, J0, v0 = z(K, 3, N), z(K, 9, N), z(K, N, dt=torch.uint8)
@@ -397,6 +403,7 @@ def test_edge_cases(lib):
     x0r, J0r, v0r = gu.oracle_inits(w2, T_ref)
     v0r[3, 10] = 0
     run2 = gu.GpuRun(w2)
+    run2.ctx.set_tuning(lds_grid=lds_grid)
     run2.precompute()
     out = run2.solve(x0r, J0r, v0r)
     ref = gu.oracle_solve(w2, T_ref, x0r, J0r, v0r)
@@ -406,6 +413,7 @@ def test_edge_cases(lib):
     np.testing.assert_array_equal(out[0][3, :, 10], x0r[3, :, 10])
     # max_iters = 0: only lanes that start on a root converge
     run3 = gu.GpuRun(w, max_iters=0)
+    run3.ctx.set_tuning(lds_grid=lds_grid)
     run3.precompute()
     x0r, J0r, v0r = gu.oracle_inits(w, T_ref)
     out = run3.solve(x0r, J0r, v0r)
@@ -415,9 +423,11 @@ def test_edge_cases(lib):
     np.testing.assert_array_equal(out[0].view(np.uint32), x0r.view(np.uint32))
 
 
-def test_single_point_and_tiny_grid(lib):
+@pytest.mark.parametrize("lds_grid", [1, 0], ids=["grid_in_lds", "grid_cached"])
+def test_single_point_and_tiny_grid(lib, lds_grid):
     w = wl.make_config(1, n_points=1, dims=(2, 2, 2))
     run = gu.GpuRun(w)
+    run.ctx.set_tuning(lds_grid=lds_grid)
     T = run.precompute()
     T_ref = oracle.precompute(w.dims, w.W, w.B, prec="f32")
     np.testing.assert_array_equal(T, T_ref)
@@ -425,6 +435,35 @@ def test_single_point_and_tiny_grid(lib):
     x0r, J0r, v0r = gu.oracle_inits(w, T_ref)
     np.testing.assert_array_equal(x0, x0r)
     out = run.solve()
+    ref = gu.oracle_solve(w, T_ref, x0r, J0r, v0r)
+    np.testing.assert_array_equal(out[1], ref[1])
+    np.testing.assert_array_equal(out[3], ref[3])
+
+
+def test_wave_that_gives_up_is_reported(lib):
+    # every wait inside the producer / consumer solve kernel is bounded; with the bound at zero the consumers leave
+    # at their first empty queue: the kernel still ends, that call returns FS_OK (nothing is synchronised), and
+    # every later call that uses the device reports it
+    w = wl.make_config(2, n_points=4096, dims=(32, 32, 8))
+    run = gu.GpuRun(w)
+    ctx = run.ctx
+    run.precompute()
+    N, K = w.N, w.K
+    xc = torch.empty((K, 3, N), dtype=torch.float32, device=gu.DEV)
+    cv = torch.empty((K, N), dtype=torch.uint8, device=gu.DEV)
+    assert ctx.set_spin_limit(-1, check=False) == binding.FS_E_ARG
+    ctx.set_spin_limit(0)
+    assert ctx.solve(run.xq, None, N, K, None, None, None, xc, cv, check=False) == binding.FS_OK
+    torch.cuda.synchronize()
+    assert ctx.solve(run.xq, None, N, K, None, None, None, xc, cv, check=False) == binding.FS_E_DEVICE
+    assert "gave up" in ctx.last_error()
+    assert ctx.precompute(run.W, run.B, check=False) == binding.FS_E_DEVICE
+    # a fresh context with the default bound solves the same input completely
+    run2 = gu.GpuRun(w)
+    T_ref = oracle.precompute(w.dims, w.W, w.B, prec="f32")
+    run2.precompute()
+    out = run2.solve(fused=True)
+    x0r, J0r, v0r = gu.oracle_inits(w, T_ref)
     ref = gu.oracle_solve(w, T_ref, x0r, J0r, v0r)
     np.testing.assert_array_equal(out[1], ref[1])
     np.testing.assert_array_equal(out[3], ref[3])
