@@ -8,7 +8,8 @@ Workload: the SMPL-scale single-pose configuration (24 bones, 64x64x16 weight gr
 65,536 query points x 24 per-bone initial states, max 50 iterations, tol 1e-5).
 
 Prints ONE JSON line.  `value` = converged (point, init) root solves per second over the whole
-step.  `roofline` describes the Broyden kernel k_solve (the dominant one), timed by the library with
+step.  `roofline` describes the Broyden kernel (k_solve_ws, or k_solve when the grid fits in LDS: the dominant
+one), timed by the library with
 HIP events around that kernel on the stream it runs on.  `cpu_baseline` is the CPU oracle timed on
 this machine's host cores.
 """
@@ -32,11 +33,11 @@ FLOP_STEP = 18       # dx = -J~ g 15, x + dx 3
 LOADS_EVAL = 24      # 8 corner records x 3 rows of 16 bytes
 PEAK_FP32_TFLOPS = 157.3            # published fp32 vector peak (needs packed fp32 instructions)
 PEAK_FP32_UNPACKED_TFLOPS = 78.6    # 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz: one FMA per lane per clock
-# HBM traffic of one k_solve launch on the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE
+# HBM traffic of one launch of the Broyden kernel on the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE
 # (profiles/k_solve_config2_hbm_traffic.md); None for other workloads.  The second figure is the same
 # kernel without the per-cell counting of converged lanes (--no-slots).
-SOLVE_TRAFFIC_BYTES = {2: 290.6e6}
-SOLVE_TRAFFIC_BYTES_NO_SLOTS = {2: 204.6e6}
+SOLVE_TRAFFIC_BYTES = {2: 290.1e6}
+SOLVE_TRAFFIC_BYTES_NO_SLOTS = {2: 199.1e6}
 
 
 def resolution_sweep(torch, binding, wl, dev):
@@ -187,6 +188,8 @@ def main():
     flops = evals * FLOP_EVAL + steps_total * (FLOP_UPDATE + FLOP_STEP)
     achieved = flops / (solve_kernel_ms * 1e-3) / 1e12
 
+    # transform grids (all poses) of at most 64 KiB are held in LDS by k_solve; larger ones go to k_solve_ws
+    grid_in_lds = w.n_poses * w.dims[0] * w.dims[1] * w.dims[2] * 48 <= 64 * 1024
     out = {
         "metric": "converged (point, init) root solves/sec",
         "value": conv / (ms_per_step * 1e-3),
@@ -207,7 +210,7 @@ def main():
                          "fs_grad": float(grad_ms)},
         "solve_only": {"converged_solves_per_s": conv / (solve_ms * 1e-3),
                        "lane_iterations_per_s": evals / (solve_ms * 1e-3)},
-        "roofline": {"kernel": "k_solve", "bound": "alu", "achieved": achieved, "peak": PEAK_FP32_TFLOPS,
+        "roofline": {"kernel": "k_solve" if grid_in_lds else "k_solve_ws", "bound": "alu", "achieved": achieved, "peak": PEAK_FP32_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_TFLOPS, "traffic": None,
                      "flop_per_launch": flops, "avg_launch_ms": float(solve_kernel_ms), "launches_timed": kernel_launches},
     }
