@@ -58,6 +58,7 @@ struct fs_ctx {
     int scan_cap;      // tiles scan_sums can hold
     int n_cus, occ_blocks_per_cu, occ_ws_blocks_per_cu, chunk, refill_min, blocks_per_cu, point_major, lds_grid;
     int spin_limit;    // polls of a work queue before a wave of the producer / consumer solve kernel gives up
+    int pre_serial;    // number of the last fs_precompute; cursor[2] == pre_serial: that grid has an entry that is not finite
     int *gave_up;      // pinned host word, mapped into the device: a wave that gave up sets it
     int *gave_up_dev;  // the device's address of it
     // optional timing of the Broyden kernel alone (events on the context's stream)
@@ -240,11 +241,12 @@ fs_status fs_create(const fs_grid_desc *desc, const fs_params *params, void *hip
     const size_t P = desc->n_poses, nb = desc->n_bones;
     bool ok = dev_alloc(&c->T, P * V * 12) && dev_alloc(&c->Bdev, P * nb * 12) && dev_alloc(&c->Binv, P * nb * 12) &&
               dev_alloc(&c->Bok, P * nb) && dev_alloc(&c->cursor, 4);
+    if (ok) ok = hipMemset(c->cursor, 0, 4 * sizeof(unsigned)) == hipSuccess;
     {
         int per_cu = 0, cus = 0;
         int per_cu_ws = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_solve<true, true>, 256, 0) != hipSuccess || per_cu < 1) per_cu = 2;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_ws, k_solve_ws<true, true, FS_WS_CONSUMERS>, 64 * (FS_WS_CONSUMERS + 1), 0) != hipSuccess || per_cu_ws < 1) per_cu_ws = 2;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_ws, k_solve_ws<true, true, FS_WS_CONSUMERS, false>, 64 * (FS_WS_CONSUMERS + 1), 0) != hipSuccess || per_cu_ws < 1) per_cu_ws = 2;
         c->occ_ws_blocks_per_cu = per_cu_ws;
         c->spin_limit = 1 << 22;   /* x about 0.2 us per poll */
         c->blocks_per_cu = 0;      /* 0: chosen per call */
@@ -343,7 +345,9 @@ fs_status fs_precompute(fs_ctx *ctx, const float *d_W, const float *d_B)
     FS_CHECK_PTR(ctx, d_B, false);
     const GridP &G = ctx->G;
     hipStream_t st = ctx->stream;
-    k_precompute<<<grid1d(G.V, 256), 256, 0, st>>>(G, d_W, d_B, ctx->T, ctx->Bdev, ctx->Binv, ctx->Bok);
+    ++ctx->pre_serial;
+    k_precompute<<<grid1d(G.V, 256), 256, 0, st>>>(G, d_W, d_B, ctx->T, ctx->Bdev, ctx->Binv, ctx->Bok,
+                                                   reinterpret_cast<int *>(ctx->cursor + 2), ctx->pre_serial);
     if (ctx->prm.init_mode == FS_INIT_VOXEL) {
         const CorrP &C = ctx->C;
         const int ncp = G.P * C.ncell;
@@ -501,14 +505,25 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
         else FS_LAUNCH_SOLVE(false, false);
 #undef FS_LAUNCH_SOLVE
     } else {
-#define FS_LAUNCH_SOLVE(F, J)                                                                                          \
-    k_solve_ws<F, J, FS_WS_CONSUMERS><<<dim3(blocks), dim3((FS_WS_CONSUMERS + 1) * WAVE), 0, st>>>(                    \
+#define FS_LAUNCH_SOLVE(F, J, Z)                                                                                       \
+    k_solve_ws<F, J, FS_WS_CONSUMERS, Z><<<dim3(blocks), dim3((FS_WS_CONSUMERS + 1) * WAVE), 0, st>>>(                 \
         ctx->G, S, I, ctx->T, d_xq, d_pose, d_x0, d_Jinv0, d_valid0, ctx->srec, ctx->cursor, list, list_len, cell_count,  \
-        ncell, d_slot, ctx->gave_up_dev)
-        if (fused && with_J) FS_LAUNCH_SOLVE(true, true);
-        else if (fused) FS_LAUNCH_SOLVE(true, false);
-        else if (with_J) FS_LAUNCH_SOLVE(false, true);
-        else FS_LAUNCH_SOLVE(false, false);
+        ncell, d_slot, ctx->gave_up_dev, reinterpret_cast<const int *>(ctx->cursor + 2), ctx->pre_serial)
+        // one state per bone starts many lanes outside the box (51 % of the evaluations on the SMPL-scale scene
+        // have a clamped coordinate): there the consumers skip the corner records of weight zero (kernel -8 %);
+        // voxel-based candidates start inside it, and the bookkeeping costs more than it saves (+15 %)
+        const bool skip = ctx->prm.init_mode == FS_INIT_BONE;
+        if (skip) {
+            if (fused && with_J) FS_LAUNCH_SOLVE(true, true, true);
+            else if (fused) FS_LAUNCH_SOLVE(true, false, true);
+            else if (with_J) FS_LAUNCH_SOLVE(false, true, true);
+            else FS_LAUNCH_SOLVE(false, false, true);
+        } else {
+            if (fused && with_J) FS_LAUNCH_SOLVE(true, true, false);
+            else if (fused) FS_LAUNCH_SOLVE(true, false, false);
+            else if (with_J) FS_LAUNCH_SOLVE(false, true, false);
+            else FS_LAUNCH_SOLVE(false, false, false);
+        }
 #undef FS_LAUNCH_SOLVE
     }
     if (ev0 && ev1) {

@@ -29,8 +29,11 @@ __device__ __forceinline__ void bone_inverse(int i, const float *__restrict__ B,
 __global__ __launch_bounds__(256) void k_precompute(GridP G, const float *__restrict__ W,
                                                     const float *__restrict__ B, float *__restrict__ T,
                                                     float *__restrict__ Bcopy, float *__restrict__ Binv,
-                                                    uint8_t *__restrict__ Bok)
+                                                    uint8_t *__restrict__ Bok, int *__restrict__ nonfinite,
+                                                    int serial)
 {
+    // *nonfinite = serial (the number of this call) tells the solve that this grid holds an entry that is not
+    // finite: a record with weight zero may then not be skipped (0 * inf is not 0)
     const long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     for (long long i = v; i < (long long)G.P * G.nb; i += (long long)gridDim.x * blockDim.x)
         bone_inverse((int)i, B, Bcopy, Binv, Bok);
@@ -74,6 +77,10 @@ __global__ __launch_bounds__(256) void k_precompute(GridP G, const float *__rest
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             if (q < np) {
+                float big = 0.0f;
+#pragma unroll
+                for (int e = 0; e < 12; ++e) big = __builtin_fmaxf(big, __builtin_fabsf(acc[q][e]) < __builtin_inff() ? 0.0f : 1.0f);
+                if (big != 0.0f) *nonfinite = serial;
                 float4 *o = reinterpret_cast<float4 *>(T + ((long long)(p0 + q) * G.V + v) * 12);
                 o[0] = make_float4(acc[q][0], acc[q][1], acc[q][2], acc[q][3]);
                 o[1] = make_float4(acc[q][4], acc[q][5], acc[q][6], acc[q][7]);
@@ -895,14 +902,58 @@ __device__ __forceinline__ void park_slots(bool want_slot, int slot_cell, int pa
     }
 }
 
-template <bool FUSED, bool WITH_J, int NCONS>
-__global__ __launch_bounds__(64 * (NCONS + 1), 3) void k_solve_ws(GridP G, SolveP S, InitP I, const float *__restrict__ T,
+// ---- corner records with zero weight need not be fetched ------------------------------------------------
+// A coordinate outside the box is clamped, so its fraction is exactly 0 or 1 and the four corners on the far
+// side of that axis get the weight 0: their records contribute 0 * T_c, i.e. nothing but possibly the sign of
+// an exact zero.  A consumer of k_solve_ws may fetch only the other corners (bit c of the mask below); the
+// registers of the skipped ones keep whatever finite record (or the initial zeros) they held before.  If a
+// blended entry then comes out as an exact zero, the skipped records are fetched and the evaluation is
+// repeated, so that even the sign of that zero is the one the full sum has.
+// Corners that can have a non-zero weight: along a clamped axis only the side the point was clamped to
+// (fraction 0: offset 0, fraction 1: offset 1).  An axis that merely happens to have fraction 0 keeps both sides.
+__device__ __forceinline__ int corners_needed(const Cell &c)
+{
+    const int mx = c.cl[0] ? (c.f[0] == 0.0f ? 0x55 : 0xAA) : 0xFF;
+    const int my = c.cl[1] ? (c.f[1] == 0.0f ? 0x33 : 0xCC) : 0xFF;
+    const int mz = c.cl[2] ? (c.f[2] == 0.0f ? 0x0F : 0xF0) : 0xFF;
+    return mx & my & mz;
+}
+
+__device__ __forceinline__ void load_corners(const float *__restrict__ Tcell, const GridP &G, int mask, float (&q)[8][12])
+{
+#pragma unroll
+    for (int c = 0; c < 8; ++c)
+        if ((mask >> c) & 1) load12(Tcell + corner_off(G, c), q[c]);
+}
+
+// blend_apply that also tells whether one of the 12 blended entries is an exact zero
+__device__ __forceinline__ bool blend_apply_z(const Cell &c, const float (&q)[8][12], const float x[3], float d[3])
+{
+    float om[8];
+    corner_weights(c, om);
+    float T[12];
+#pragma unroll
+    for (int e = 0; e < 12; ++e) T[e] = om[0] * q[0][e];
+#pragma unroll
+    for (int k = 1; k < 8; ++k)
+#pragma unroll
+        for (int e = 0; e < 12; ++e) T[e] = FS_FMA(om[k], q[k][e], T[e]);
+    apply12(T, x, d);
+    float m = __builtin_fabsf(T[0]);
+#pragma unroll
+    for (int e = 1; e < 12; ++e) m = __builtin_fminf(m, __builtin_fabsf(T[e]));
+    return m == 0.0f;
+}
+
+template <bool FUSED, bool WITH_J, int NCONS, bool SKIP>
+__global__ __launch_bounds__(64 * (NCONS + 1), SKIP ? 2 : 3) void k_solve_ws(GridP G, SolveP S, InitP I, const float *__restrict__ T,
                                                const float *__restrict__ xq, const int32_t *__restrict__ pose,
                                                const float *__restrict__ x0, const float *__restrict__ J0,
                                                const uint8_t *__restrict__ valid0, float4 *__restrict__ rec,
                                                unsigned *__restrict__ cursor, const int *__restrict__ list,
                                                const int *__restrict__ list_len, int *__restrict__ cell_count,
-                                               int ncell, int32_t *__restrict__ slot_out, int *__restrict__ give_up)
+                                               int ncell, int32_t *__restrict__ slot_out, int *__restrict__ give_up,
+                                               const int *__restrict__ nonfinite, int serial)
 {
     __shared__ float s_ring[NCONS][ST_FIELDS][WS_RING];
     __shared__ int s_tail[NCONS], s_head[NCONS], s_done;
@@ -1086,6 +1137,15 @@ __global__ __launch_bounds__(64 * (NCONS + 1), 3) void k_solve_ws(GridP G, Solve
     float J[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
     float q[8][12];                  // corner records of the lane's current cell, kept across iterations
     long long held = -1;             // grid offset of the cell whose corners q holds (-1: none)
+    int held_mask = 0;               // SKIP: which of them
+    // SKIP needs a grid of finite entries (k_precompute says if this one is not)
+    const bool may_skip = SKIP && __builtin_amdgcn_readfirstlane(*nonfinite) != serial;
+    if (SKIP) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+#pragma unroll
+            for (int e = 0; e < 12; ++e) q[c][e] = 0.0f;
+    }
     bool run = true;                 // wave-uniform
     while (run) {
         const unsigned long long idle = __ballot(!active);
@@ -1145,12 +1205,29 @@ __global__ __launch_bounds__(64 * (NCONS + 1), 3) void k_solve_ws(GridP G, Solve
             float d[3], gn[3];
             const Cell cell = locate(G, xt);
             const long long want = (long long)(Tp - T) + cell.base;
-            if (want != held) {
+            if (SKIP) {
+                const int need = may_skip ? corners_needed(cell) : 0xFF;
+                if (want != held) {
+                    held = want;
+                    held_mask = 0;
+                }
+                if (need & ~held_mask) {
+                    load_corners(Tp + cell.base, G, need & ~held_mask, q);
+                    held_mask |= need;
+                }
+                if (blend_apply_z(cell, q, xt, d) && held_mask != 0xFF) {
+                    load_corners(Tp + cell.base, G, 0xFF & ~held_mask, q);
+                    held_mask = 0xFF;
+                    blend_apply(cell, q, xt, d);
+                }
+            } else {
+                if (want != held) {
 #pragma unroll
-                for (int c = 0; c < 8; ++c) load12(Tp + cell.base + corner_off(G, c), q[c]);
-                held = want;
+                    for (int c = 0; c < 8; ++c) load12(Tp + cell.base + corner_off(G, c), q[c]);
+                    held = want;
+                }
+                blend_apply(cell, q, xt, d);
             }
-            blend_apply(cell, q, xt, d);
 #pragma unroll
             for (int r = 0; r < 3; ++r) gn[r] = d[r] - xp[r];
             float dg[3], v[3], u[3];
