@@ -36,8 +36,8 @@ PEAK_FP32_UNPACKED_TFLOPS = 78.6    # 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.
 # HBM traffic of one launch of the Broyden kernel on the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE
 # (profiles/k_solve_config2_hbm_traffic.md); None for other workloads.  The second figure is the same
 # kernel without the per-cell counting of converged lanes (--no-slots).
-SOLVE_TRAFFIC_BYTES = {2: 290.1e6}
-SOLVE_TRAFFIC_BYTES_NO_SLOTS = {2: 199.1e6}
+SOLVE_TRAFFIC_BYTES = {2: 292.0e6}
+SOLVE_TRAFFIC_BYTES_NO_SLOTS = {2: 198.7e6}
 
 
 def resolution_sweep(torch, binding, wl, dev):
