@@ -18,7 +18,8 @@
  *    context's stream during the call and keeps no reference afterwards.
  *  - All calls enqueue on the context's HIP stream and return without synchronising; results are
  *    ready when the stream reaches that point.  Argument and state errors are reported at once
- *    through the return code; a failed launch is reported by the call that made it.
+ *    through the return code; a failed launch is reported by the call that made it; a solve whose
+ *    kernel gave up one of its bounded waits (fs_set_spin_limit) is reported by the calls after it.
  *    No exceptions or aborts cross this boundary.  fs_last_error() gives a readable message.
  *  - All arithmetic is IEEE fp32.  Point sets are structure-of-arrays: xq is [3][N]; per-lane
  *    arrays are [K][c][N] (lane = (initial state k, point n)), c = 3 for positions, 9 for a
@@ -46,7 +47,7 @@ typedef enum {
     FS_E_SHAPE = 2,       /* size out of range or inconsistent with the context              */
     FS_E_STATE = 3,       /* call order: e.g. fs_solve before fs_precompute                  */
     FS_E_ALLOC = 4,       /* device allocation failed                                        */
-    FS_E_DEVICE = 5,      /* HIP runtime error (no device, failed launch)                    */
+    FS_E_DEVICE = 5,      /* HIP runtime error (no device, failed launch); unfinished solve  */
     FS_E_UNSUPPORTED = 6
 } fs_status;
 
@@ -72,8 +73,8 @@ typedef struct {
 } fs_params;
 
 /* Create a context on the current HIP device.  `hip_stream` is a hipStream_t (NULL = the
- * default stream).  Allocates the library-owned grids (n_poses * V * 48 bytes and smaller).
- * On failure *out is NULL. */
+ * default stream).  Allocates the library-owned grids (n_poses * V * 48 bytes and smaller) and
+ * one word of pinned host memory.  On failure *out is NULL. */
 fs_status fs_create(const fs_grid_desc *desc, const fs_params *params, void *hip_stream, fs_ctx **out);
 
 /* Free everything the context owns.  Synchronises the stream first.  NULL is allowed. */
