@@ -501,3 +501,57 @@ def test_grid_entries_that_are_not_finite(lib):
     ref = gu.oracle_solve(w, T_fin, a, b, c)
     np.testing.assert_array_equal(out[1], ref[1])
     np.testing.assert_array_equal(out[3], ref[3])
+
+
+def test_large_batch_sampled_parity(lib):
+    # 2^28 pairs and more: result records and outputs lie beyond 4 GiB from their bases, pair indices need 29
+    # bits.  The SMPL-scale scene's points tiled and jittered; the oracle solves a sample of the points (every
+    # point is independent of the others) and the GPU's results for those must be the same bits; dL/dx' of the
+    # sampled points too (it depends on a point's own lanes only).
+    w = wl.make_config(2)
+    reps = 171
+    rng = np.random.default_rng(77)
+    N = w.N * reps - 37                                    # ragged
+    xq = np.tile(w.xq, (1, reps))[:, :N] + rng.normal(0.0, 1e-3, (3, N)).astype(np.float32)
+    K = w.K
+    assert K * N > 2 ** 28
+    ctx = binding.Context(w.dims, w.n_bones, w.lo, w.hi, tol=w.tol, div_thresh=w.div_thresh, max_iters=w.max_iters)
+    W, B, xq_d = gu.dev(w.W), gu.dev(w.B), gu.dev(xq)
+    ctx.precompute(W, B)
+    f32 = torch.float32
+    xc = torch.empty((K, 3, N), dtype=f32, device=gu.DEV)
+    cv = torch.empty((K, N), dtype=torch.uint8, device=gu.DEV)
+    it = torch.empty((K, N), dtype=torch.uint8, device=gu.DEV)
+    slot = torch.empty((K, N), dtype=torch.int32, device=gu.DEV)
+    ctx.solve(xq_d, None, N, K, None, None, None, xc, cv, None, it, slot)
+    torch.cuda.synchronize()
+    sample = np.sort(np.concatenate([rng.choice(N, 1500, replace=False), [0, 1, N - 2, N - 1]])).astype(np.int64)
+    idx = torch.from_numpy(sample).to(gu.DEV)
+    g_xc = xc.index_select(2, idx).cpu().numpy()
+    g_cv = cv.index_select(1, idx).cpu().numpy()
+    g_it = it.index_select(1, idx).cpu().numpy()
+    ws = wl.Workload(**{**w.__dict__, "xq": np.ascontiguousarray(xq[:, sample])})
+    T_ref = oracle.precompute(w.dims, w.W, w.B, prec="f32")
+    x0r, J0r, v0r = gu.oracle_inits(ws, T_ref)
+    oxc, ocv, oJ, oit = gu.oracle_solve(ws, T_ref, x0r, J0r, v0r)
+    np.testing.assert_array_equal(g_cv, ocv)
+    np.testing.assert_array_equal(g_it, oit)
+    np.testing.assert_array_equal(g_xc.view(np.uint32), oxc.view(np.uint32))
+    # every lane was written, masks are 0/1, every converged lane has a position in its cell and no other lane has
+    assert int((cv > 1).sum().item()) == 0
+    nconv = int(cv.sum(dtype=torch.int64).item())
+    assert nconv > 0.9 * K * N
+    assert int(((slot >= 0) != (cv == 1)).sum().item()) == 0
+    # backward on the whole batch, checked on the sample
+    gxc = torch.empty((K, 3, N), dtype=f32, device=gu.DEV).normal_(generator=torch.Generator(device=gu.DEV).manual_seed(5))
+    gW = torch.empty(w.W.shape, dtype=f32, device=gu.DEV)
+    gB = torch.empty(w.B.shape, dtype=f32, device=gu.DEV)
+    gxq = torch.empty((3, N), dtype=f32, device=gu.DEV)
+    ctx.grad(W, xc, None, cv, gxc, None, N, K, gW, gB, gxq, slot)
+    torch.cuda.synchronize()
+    g_gxc = gxc.index_select(2, idx).cpu().numpy()
+    rW, rB, rq = oracle.grad(w.dims, w.lo, w.hi, T_ref, w.W, w.B, oxc, oJ, ocv, g_gxc, pose=None, mode=0, prec="f64")
+    got = gxq.index_select(1, idx).cpu().numpy()
+    assert np.linalg.norm(got - rq) / np.linalg.norm(rq) < 2e-5
+    assert bool(torch.isfinite(gW).all().item()) and bool(torch.isfinite(gB).all().item())
+    ctx.close()
