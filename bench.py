@@ -38,6 +38,12 @@ PEAK_FP32_UNPACKED_TFLOPS = 78.6    # 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.
 # kernel without the per-cell counting of converged lanes (--no-slots).
 SOLVE_TRAFFIC_BYTES = {2: 292.0e6}
 SOLVE_TRAFFIC_BYTES_NO_SLOTS = {2: 198.7e6}
+# L1 (vector cache) accesses and L1 -> L2 read requests of one launch of the Broyden kernel on the default
+# workload, from rocprofv3 TCP_TOTAL_CACHE_ACCESSES_sum / TCP_TCC_READ_REQ_sum
+# (profiles/k_solve_config2_gather_path.md): the per-lane 16-byte gathers the texture path actually served,
+# after the same-cell reuse and the skipping of weight-zero corners.
+SOLVE_L1_ACCESSES = {2: 143.3e6}
+SOLVE_L1_TO_L2_REQUESTS = {2: 29.15e6}
 
 
 def resolution_sweep(torch, binding, wl, dev):
@@ -230,6 +236,19 @@ def main():
                         "ceiling_line_coalesced_gather_same_footprint": gline,
                         "ceiling_lds_lane_random_gather": glds, "footprint_bytes": grid_bytes},
         "traffic": (SOLVE_TRAFFIC_BYTES_NO_SLOTS if args.no_slots else SOLVE_TRAFFIC_BYTES).get(args.config)})
+    if args.config in SOLVE_L1_ACCESSES and not args.no_slots and not args.unfused:
+        # the texture path's own roofline: served gathers per second against the ceiling measured on this device for
+        # the kernel's mix of L1 hits (lane-random gathers from an L1-resident array) and L2 hits (from an array of
+        # the grid's size)
+        acc, req = SOLVE_L1_ACCESSES[args.config], SOLVE_L1_TO_L2_REQUESTS[args.config]
+        hit = 1.0 - req / acc
+        g1 = binding.microbench(binding.MB_GATHER_LANE, 8192)
+        blended = 1.0 / (hit / g1 + (1.0 - hit) / gl)
+        served = acc / (solve_kernel_ms * 1e-3)
+        out["roofline"]["gather_path"].update({
+            "l1_accesses_per_launch": acc, "l1_hit_rate": hit, "served_16B_gathers_per_s": served,
+            "ceiling_lane_random_gather_l1_resident": g1, "ceiling_for_this_hit_rate": blended,
+            "frac_of_ceiling_for_this_hit_rate": served / blended})
 
     if args.probe_copy_mib > 0:
         a = torch.empty(args.probe_copy_mib << 18, dtype=f32, device=dev)
