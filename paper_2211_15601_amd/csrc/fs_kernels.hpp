@@ -857,7 +857,8 @@ __global__ __launch_bounds__(256, 3) void k_solve(GridP G, SolveP S, InitP I, co
 }
 
 // ------------------------------------------------------------------------------------------------
-// Broyden solve with the work divided between the waves of a block.  One wave (the producer) prepares
+// Broyden solve (Eq. (7) with the rank-one update of J~, Algorithm 1 variant 2, per-iteration filter of
+// Sec. 3.1 "Custom CUDA Kernel") with the work divided between the waves of a block.  One wave (the producer) prepares
 // pairs 64 at a time, every SIMD lane busy: initial state, first evaluation of the field, first step; pairs
 // that end there (invalid state, converged or diverged at x0) it answers itself.  The other waves (the
 // consumers) only iterate: each owns a queue of prepared states {x', x, g, dx, J~, pair} in LDS, its idle
