@@ -980,6 +980,7 @@ __global__ __launch_bounds__(64 * (NCONS + 1), SKIP ? 2 : 3) void k_solve_ws(Gri
 #pragma unroll
         for (int c = 0; c < NCONS; ++c) tails[c] = 0;
         bool lost = false;
+        const bool prod_skip = SKIP && __builtin_amdgcn_readfirstlane(*nonfinite) != serial;
         while (!lost) {
             if (next >= c1) {
                 unsigned b = 0;
@@ -1042,10 +1043,41 @@ __global__ __launch_bounds__(64 * (NCONS + 1), SKIP ? 2 : 3) void k_solve_ws(Gri
                 if (ok) {
                     const Cell c0 = locate(G, nx);
                     float qn[8][12];
-#pragma unroll
-                    for (int c = 0; c < 8; ++c) load12(Tn + c0.base + corner_off(G, c), qn[c]);
                     float d[3];
-                    if (FUSED) {
+                    if (FUSED && SKIP) {
+                        // corner records of weight zero contribute nothing to the Jacobian either (the derivative of
+                        // their weight vanishes along the clamped axis by definition and carries the zero factor
+                        // along the others): fetch the rest, zeros in their place, and if an entry of the blend
+                        // or of the Jacobian comes out as an exact zero, do it again with all eight
+                        const int need = prod_skip ? corners_needed(c0) : 0xFF;
+#pragma unroll
+                        for (int c = 0; c < 8; ++c) {
+#pragma unroll
+                            for (int e = 0; e < 12; ++e) qn[c][e] = 0.0f;
+                        }
+                        load_corners(Tn + c0.base, G, need, qn);
+                        float Jac[9];
+                        jacobian_from_corners(G, c0, qn, nx, d, Jac);
+                        if (need != 0xFF) {
+                            float d2[3];
+                            bool z = blend_apply_z(c0, qn, nx, d2);      // the same blend as inside the Jacobian
+                            float m = __builtin_fabsf(Jac[0]);
+#pragma unroll
+                            for (int e = 1; e < 9; ++e) m = __builtin_fminf(m, __builtin_fabsf(Jac[e]));
+                            z = z || m == 0.0f;
+                            if (z) {
+                                load_corners(Tn + c0.base, G, 0xFF & ~need, qn);
+                                jacobian_from_corners(G, c0, qn, nx, d, Jac);
+                            }
+                        }
+                        ok = inv3(Jac, nJ);
+                        if (!ok) {
+#pragma unroll
+                            for (int e = 0; e < 9; ++e) nJ[e] = 0.0f;
+                        }
+                    } else if (FUSED) {
+#pragma unroll
+                        for (int c = 0; c < 8; ++c) load12(Tn + c0.base + corner_off(G, c), qn[c]);
                         float Jac[9];
                         jacobian_from_corners(G, c0, qn, nx, d, Jac);      // d: the same arithmetic as blend_apply
                         ok = inv3(Jac, nJ);
@@ -1054,6 +1086,8 @@ __global__ __launch_bounds__(64 * (NCONS + 1), SKIP ? 2 : 3) void k_solve_ws(Gri
                             for (int e = 0; e < 9; ++e) nJ[e] = 0.0f;
                         }
                     } else {
+#pragma unroll
+                        for (int c = 0; c < 8; ++c) load12(Tn + c0.base + corner_off(G, c), qn[c]);
                         blend_apply(c0, qn, nx, d);
                     }
                     if (ok) {
