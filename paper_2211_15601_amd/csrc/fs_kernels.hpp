@@ -591,31 +591,45 @@ __global__ void k_reset_cursor(unsigned *__restrict__ cursor, unsigned start)
 // The parked requests of one wave: entry i = {cell, pair}, one per SIMD lane.  Lanes of one point that reach
 // the same root are neighbours in the wave and finish within a few passes of each other, so many entries name
 // the same cell: those are counted together and one lane adds the group to the cell's counter.
-__device__ __forceinline__ void flush_slots(int (&pend)[2][64], int npend, int lane, int *__restrict__ cell_count,
+constexpr int PEND = 128;       // requests a wave parks before it sends them
+constexpr int PEND_SEND = 112;  // ... at least this many
+
+__device__ __forceinline__ void flush_slots(int (&pend)[2][PEND], int npend, int lane, int *__restrict__ cell_count,
                                             int32_t *__restrict__ slot_out)
 {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");      // the LDS writes of the wave's other lanes
     __builtin_amdgcn_wave_barrier();
-    const bool valid = lane < npend;
-    const int c = valid ? pend[0][lane] : -1;
-    const int pq = valid ? pend[1][lane] : 0;
-    int leader = lane, rank = 0, members = 1;
-    unsigned long long todo = __ballot(valid);
-    while (todo) {
-        const int first = __ffsll((long long)todo) - 1;
-        const int key = __shfl(c, first);
-        const unsigned long long same = __ballot(valid && c == key);
-        if (valid && c == key) {
-            leader = first;
-            rank = __popcll(same & ((1ull << lane) - 1ull));
-            members = __popcll(same);
+    // two rounds of 64 entries; the atomics of both are on their way before either answer is used
+    bool valid[2];
+    int pq[2], leader[2], rank[2], base[2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+        valid[b] = 64 * b + lane < npend;
+        const int c = valid[b] ? pend[0][64 * b + lane] : -1;
+        pq[b] = valid[b] ? pend[1][64 * b + lane] : 0;
+        int members = 1;
+        leader[b] = lane;
+        rank[b] = 0;
+        unsigned long long todo = __ballot(valid[b]);
+        while (todo) {
+            const int first = __ffsll((long long)todo) - 1;
+            const int key = __builtin_amdgcn_readlane(c, first);
+            const unsigned long long same = __ballot(valid[b] && c == key);
+            if (valid[b] && c == key) {
+                leader[b] = first;
+                rank[b] = __popcll(same & ((1ull << lane) - 1ull));
+                members = __popcll(same);
+            }
+            todo &= ~same;
         }
-        todo &= ~same;
+        base[b] = 0;
+        if (valid[b] && leader[b] == lane) base[b] = atomicAdd(cell_count + c, members);
     }
-    int base = 0;
-    if (valid && leader == lane) base = atomicAdd(cell_count + c, members);
-    base = __shfl(base, leader);
-    if (valid) slot_out[pq] = base + rank;
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+        const int bs = __shfl(base[b], leader[b]);
+        if (valid[b]) slot_out[pq[b]] = bs + rank[b];
+    }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");      // before the entries are overwritten
     __builtin_amdgcn_wave_barrier();
 }
@@ -645,7 +659,7 @@ __global__ __launch_bounds__(256, 3) void k_solve(GridP G, SolveP S, InitP I, co
 {
     extern __shared__ float4 s_grid[];
     // converged lanes waiting for their position in their grid cell's list: {cell, pair} per wave
-    __shared__ int s_pend[4][2][64];
+    __shared__ int s_pend[4][2][PEND];
     {
         const int n4 = (int)((long long)G.P * G.V * 3);      // float4 per record: 3
         const float4 *src = reinterpret_cast<const float4 *>(Tglobal);
@@ -832,11 +846,11 @@ __global__ __launch_bounds__(256, 3) void k_solve(GridP G, SolveP S, InitP I, co
         }
         // For the backward every converged lane needs its arrival position in the list of its grid cell: one
         // returning atomic on the cell's counter.  A wave would wait for that answer in every pass (a few of
-        // its lanes finish in each), so the requests are parked in LDS and sent 48 or more at a time, one per cell.
+        // its lanes finish in each), so the requests are parked in LDS and sent 112 or more at a time, one per cell and round of 64.
         if (WITH_J && cell_count) {
             const unsigned long long m = __ballot(want_slot);
             if (m) {
-                if (npend + __popcll(m) > 64) {
+                if (npend + __popcll(m) > PEND) {
                     flush_slots(s_pend[wib], npend, lane, cell_count, slot_out);
                     npend = 0;
                 }
@@ -847,7 +861,7 @@ __global__ __launch_bounds__(256, 3) void k_solve(GridP G, SolveP S, InitP I, co
                 }
                 npend += __popcll(m);
             }
-            if (npend >= 48) {
+            if (npend >= PEND_SEND) {
                 flush_slots(s_pend[wib], npend, lane, cell_count, slot_out);
                 npend = 0;
             }
@@ -881,12 +895,12 @@ __device__ __forceinline__ void lds_store_release(int *p, int v)
     __hip_atomic_store(p, v, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
-__device__ __forceinline__ void park_slots(bool want_slot, int slot_cell, int pair, int (&pend)[2][64], int &npend, int lane,
+__device__ __forceinline__ void park_slots(bool want_slot, int slot_cell, int pair, int (&pend)[2][PEND], int &npend, int lane,
                                            int *__restrict__ cell_count, int32_t *__restrict__ slot_out)
 {
     const unsigned long long m = __ballot(want_slot);
     if (m) {
-        if (npend + __popcll(m) > 64) {
+        if (npend + __popcll(m) > PEND) {
             flush_slots(pend, npend, lane, cell_count, slot_out);
             npend = 0;
         }
@@ -897,7 +911,7 @@ __device__ __forceinline__ void park_slots(bool want_slot, int slot_cell, int pa
         }
         npend += __popcll(m);
     }
-    if (npend >= 48) {
+    if (npend >= PEND_SEND) {
         flush_slots(pend, npend, lane, cell_count, slot_out);
         npend = 0;
     }
@@ -958,7 +972,7 @@ __global__ __launch_bounds__(64 * (NCONS + 1), SKIP ? 2 : 3) void k_solve_ws(Gri
 {
     __shared__ float s_ring[NCONS][ST_FIELDS][WS_RING];
     __shared__ int s_tail[NCONS], s_head[NCONS], s_done;
-    __shared__ int s_pend[NCONS + 1][2][64];
+    __shared__ int s_pend[NCONS + 1][2][PEND];
     if (threadIdx.x < NCONS) {
         s_tail[threadIdx.x] = 0;
         s_head[threadIdx.x] = 0;
