@@ -36,14 +36,14 @@ PEAK_FP32_UNPACKED_TFLOPS = 78.6    # 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.
 # HBM traffic of one launch of the Broyden kernel on the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE
 # (profiles/k_solve_config2_hbm_traffic.md); None for other workloads.  The second figure is the same
 # kernel without the per-cell counting of converged lanes (--no-slots).
-SOLVE_TRAFFIC_BYTES = {2: 291.7e6}
-SOLVE_TRAFFIC_BYTES_NO_SLOTS = {2: 199.0e6}
+SOLVE_TRAFFIC_BYTES = {2: 274.3e6}
+SOLVE_TRAFFIC_BYTES_NO_SLOTS = {2: 199.1e6}
 # L1 (vector cache) accesses and L1 -> L2 read requests of one launch of the Broyden kernel on the default
 # workload, from rocprofv3 TCP_TOTAL_CACHE_ACCESSES_sum / TCP_TCC_READ_REQ_sum
 # (profiles/k_solve_config2_gather_path.md): the per-lane 16-byte gathers the texture path actually served,
 # after the same-cell reuse and the skipping of weight-zero corners.
 SOLVE_L1_ACCESSES = {2: 131.3e6}
-SOLVE_L1_TO_L2_REQUESTS = {2: 26.3e6}
+SOLVE_L1_TO_L2_REQUESTS = {2: 26.6e6}
 
 
 def resolution_sweep(torch, binding, wl, dev):
