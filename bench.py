@@ -2,20 +2,24 @@
 """Benchmark of the Fast-SNARF articulation hot path on one MI355X.
 
 One "step" = one pass of the whole path over one synthetic batch that is already resident in
-HBM: fs_precompute -> fs_solve (initial states computed inside the kernel; J~ and iteration counts
-kept) -> fs_grad.  `--unfused` materialises the initial states with fs_init first.
-Workload: the SMPL-scale single-pose configuration (24 bones, 64x64x16 weight grid,
-65,536 query points x 24 per-bone initial states, max 50 iterations, tol 1e-5).
+HBM: fs_precompute -> fs_solve (initial states computed inside the kernel; iteration counts kept,
+J~ left in the library's result records) -> fs_grad.  `--unfused` materialises the initial states
+with fs_init first.
+
+Headline workload (default `--config 5`): the largest single-GPU configuration, the multi-pose batch
+(8 poses, 24 bones each, 128x128x32 weight grid = 192 MiB of transform grids, 524,288 points per pose,
+voxel-based initial states with up to 3 candidates, max 50 iterations, tol 1e-5).  The other four
+configurations are timed too and reported, shorter, under `per_config`.
 
 Prints ONE JSON line.  `value` = converged (point, init) root solves per second over the whole
-step.  `roofline` describes the Broyden kernel (k_solve_ws, or k_solve when the grid fits in LDS: the dominant
-one), timed by the library with
-HIP events around that kernel on the stream it runs on.  `cpu_baseline` is the CPU oracle timed on
-this machine's host cores.
+step.  `roofline` describes the Broyden kernel (k_solve_ws, or k_solve when the grid fits in LDS: the
+dominant one), timed by the library with HIP events around that kernel on the stream it runs on.
+`cpu_baseline` is the CPU oracle timed on this machine's host cores.
 """
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -31,19 +35,138 @@ FLOP_EVAL = 237      # locate 12, corner weights 19, 8x12 tri-linear blend 180, 
 FLOP_UPDATE = 63     # dg 3, v = J~^T dx 15, u = dx - J~ dg 18, v.dg 5, divide 1, u/den 3, rank-one 18
 FLOP_STEP = 18       # dx = -J~ g 15, x + dx 3
 LOADS_EVAL = 24      # 8 corner records x 3 rows of 16 bytes
+BYTES_EVAL = 384     # ... = 8 x 48 bytes gathered per field evaluation
 PEAK_FP32_TFLOPS = 157.3            # published fp32 vector peak (needs packed fp32 instructions)
 PEAK_FP32_UNPACKED_TFLOPS = 78.6    # 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz: one FMA per lane per clock
-# HBM traffic of one launch of the Broyden kernel on the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE
-# (profiles/k_solve_config2_hbm_traffic.md); None for other workloads.  The second figure is the same
-# kernel without the per-cell counting of converged lanes (--no-slots).
-SOLVE_TRAFFIC_BYTES = {2: 274.3e6}
-SOLVE_TRAFFIC_BYTES_NO_SLOTS = {2: 199.1e6}
-# L1 (vector cache) accesses and L1 -> L2 read requests of one launch of the Broyden kernel on the default
-# workload, from rocprofv3 TCP_TOTAL_CACHE_ACCESSES_sum / TCP_TCC_READ_REQ_sum
-# (profiles/k_solve_config2_gather_path.md): the per-lane 16-byte gathers the texture path actually served,
-# after the same-cell reuse and the skipping of weight-zero corners.
-SOLVE_L1_ACCESSES = {2: 131.3e6}
-SOLVE_L1_TO_L2_REQUESTS = {2: 26.6e6}
+PEAK_HBM_BPS = 8.0e12
+LDS_GRID_MAX = 64 * 1024            # transform grids (all poses) up to this size are held in LDS by k_solve
+
+
+def profile_value(cfg, key):
+    """A figure measured with rocprofv3 and committed under profiles/ (a line `key: number` in the summary of the
+    Broyden kernel on this configuration); None where no such run was made."""
+    path = os.path.join(ROOT, "profiles", f"k_solve_config{cfg}_counters.md")
+    try:
+        with open(path) as f:
+            m = re.search(rf"^{re.escape(key)}\s*:\s*([0-9.eE+-]+)\s*$", f.read(), re.M)
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
+def pct(a):
+    a = np.asarray(a, dtype=np.float64)
+    return {"median": float(np.median(a)), "p10": float(np.percentile(a, 10)), "p90": float(np.percentile(a, 90))}
+
+
+class Case:
+    """One configuration resident on the device: context, inputs, outputs."""
+
+    def __init__(self, cfg, args, torch, binding, wl, dev):
+        self.cfg, self.args, self.torch, self.binding = cfg, args, torch, binding
+        w = self.w = wl.make_config(cfg)
+        N, K = self.N, self.K = w.N, w.K
+        self.ctx = binding.Context(w.dims, w.n_bones, w.lo, w.hi, n_poses=w.n_poses, tol=w.tol, div_thresh=w.div_thresh,
+                                   max_iters=w.max_iters, init_mode=w.init_mode, grad_mode=binding.FS_GRAD_BROYDEN_J,
+                                   corr_dims=w.corr_dims)
+        up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+        self.W, self.B, self.xq = up(w.W), up(w.B), up(w.xq)
+        self.pose = up(w.pose) if w.n_poses > 1 else None
+        self.gxc = up(w.upstream_grads())
+        f32, u8 = torch.float32, torch.uint8
+        e = lambda shape, dt: torch.empty(shape, dtype=dt, device=dev)
+        self.x0, self.J0, self.v0 = e((K, 3, N), f32), e((K, 9, N), f32), e((K, N), u8)
+        self.xc, self.cv, self.it = e((K, 3, N), f32), e((K, N), u8), e((K, N), u8)
+        self.gW, self.gB, self.gxq = e(w.W.shape, f32), e(w.B.shape, f32), e((3, N), f32)
+        self.slot = None if args.no_slots else e((K, N), torch.int32)
+        # with the cell positions handed on, J~ can stay in the library's result records
+        self.Jarg = None if self.slot is not None else e((K, 9, N), f32)
+        self.grid_bytes = int(w.n_poses * w.dims[0] * w.dims[1] * w.dims[2] * 48)
+        self.kernel = "k_solve" if self.grid_bytes <= LDS_GRID_MAX else "k_solve_ws"
+
+    def step(self, marks=None):
+        a, c, t = self.args, self.ctx, self.torch
+        ev = [t.cuda.Event(enable_timing=True) for _ in range(5)] if marks is not None else None
+        if ev: ev[0].record()
+        c.precompute(self.W, self.B)
+        if ev: ev[1].record()
+        if a.unfused:
+            c.init(self.xq, self.pose, self.N, self.x0, self.J0, self.v0)
+        if ev: ev[2].record()
+        if a.unfused:
+            c.solve(self.xq, self.pose, self.N, self.K, self.x0, self.J0, self.v0, self.xc, self.cv, self.Jarg, self.it, self.slot)
+        else:
+            c.solve(self.xq, self.pose, self.N, self.K, None, None, None, self.xc, self.cv, self.Jarg, self.it, self.slot)
+        if ev: ev[3].record()
+        if not a.no_grad:
+            c.grad(self.W, self.xc, self.Jarg, self.cv, self.gxc, self.pose, self.N, self.K, self.gW, self.gB, self.gxq, self.slot)
+        if ev:
+            ev[4].record()
+            marks.append(ev)
+
+    def measure(self, steps, warmup, launches):
+        """Wall-clock of `steps` whole steps, the Broyden kernel's own time (HIP events inside the library, on the
+        stream it is launched on) over the same steps, then `launches` more steps with events between the calls
+        for the per-call statistics."""
+        t, c = self.torch, self.ctx
+        for _ in range(warmup):
+            self.step()
+        t.cuda.synchronize()
+        c.set_timing(True)
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.step()
+        t.cuda.synchronize()
+        t1 = time.perf_counter()
+        kms, kn = c.get_timing()
+        c.set_timing(False)
+        self.ms_per_step = (t1 - t0) * 1e3 / steps
+        self.kernel_ms, self.kernel_launches = kms / max(kn, 1), kn
+        marks = []
+        for _ in range(launches):
+            self.step(marks)
+        t.cuda.synchronize()
+        ph = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(4)] for e in marks])   # ms
+        self.calls = {"fs_precompute": pct(ph[:, 0]), "fs_solve": pct(ph[:, 2]), "fs_grad": pct(ph[:, 3]),
+                      "step": pct(ph.sum(1)), "launches": launches}
+        if self.args.unfused:
+            self.calls["fs_init"] = pct(ph[:, 1])
+        # (untimed) validity flags for the count of field evaluations
+        c.init(self.xq, self.pose, self.N, self.x0, self.J0, self.v0)
+        t.cuda.synchronize()
+        valid = self.v0 == 1
+        self.conv = int(self.cv.sum(dtype=t.int64).item())
+        self.valid = int(valid.sum().item())
+        its = self.it[valid].to(t.int64)
+        self.steps_total = int(its.sum().item())
+        self.evals = self.steps_total + self.valid            # field evaluations = active lane-iterations
+        self.iter_hist = t.bincount(its, minlength=self.w.max_iters + 1).cpu().tolist()
+        self.flops = self.evals * FLOP_EVAL + self.steps_total * (FLOP_UPDATE + FLOP_STEP)
+
+    def workload(self):
+        w = self.w
+        return (f"config {self.cfg} ({w.name}): grid {w.dims[0]}x{w.dims[1]}x{w.dims[2]}, {w.n_bones} bones, "
+                f"{w.n_poses} pose(s), {self.N} points x {self.K} inits "
+                f"({'one per bone' if w.init_mode == 0 else 'voxel-based candidates'}), max_iters {w.max_iters}, tol {w.tol}")
+
+    def roofline(self):
+        ks = self.kernel_ms * 1e-3
+        achieved = self.flops / ks / 1e12
+        traffic = profile_value(self.cfg, "hbm_bytes_per_launch") if not (self.args.no_slots or self.args.unfused) else None
+        r = {"kernel": self.kernel, "bound": "alu", "achieved": achieved, "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s",
+             "frac": achieved / PEAK_FP32_TFLOPS, "traffic": traffic,
+             "peak_unpacked": PEAK_FP32_UNPACKED_TFLOPS, "frac_unpacked": achieved / PEAK_FP32_UNPACKED_TFLOPS,
+             "flop_per_launch": self.flops, "evaluations_per_launch": self.evals,
+             "avg_launch_ms": float(self.kernel_ms), "launches_timed": self.kernel_launches,
+             "evaluations_per_s": self.evals / ks,
+             "algorithmic_gather_bytes_per_s": self.evals * BYTES_EVAL / ks}
+        if traffic is not None:
+            r["hbm"] = {"counter_bytes_per_launch": traffic, "achieved_bytes_per_s": traffic / ks,
+                        "frac_of_peak": traffic / ks / PEAK_HBM_BPS}
+        return r
+
+    def close(self):
+        self.ctx.close()
 
 
 def resolution_sweep(torch, binding, wl, dev):
@@ -79,13 +202,52 @@ def resolution_sweep(torch, binding, wl, dev):
         ctx.close()
 
 
+def cpu_baseline(case, args):
+    """The CPU oracle (strict fp32: the arithmetic the parity tests hold the GPU to; then float64 once) running the
+    same step on the same inputs on this machine's host cores."""
+    import oracle
+    w = case.w
+    ncores = int(os.environ.get("OMP_NUM_THREADS", len(os.sched_getaffinity(0))))
+    pz = w.pose if w.n_poses > 1 else None
+    gx = w.upstream_grads()
+
+    def one(prec):
+        c0 = time.perf_counter()
+        T = oracle.precompute(w.dims, w.W, w.B, prec=prec)
+        if w.init_mode == 0:
+            a0, b0, c0v = oracle.init_bone(w.dims, w.lo, w.hi, T, w.B, w.xq, pose=pz, prec=prec)
+        else:
+            bb, cd = oracle.corr_build(w.dims, w.lo, w.hi, T, w.corr_dims, prec=prec)
+            a0, b0, c0v = oracle.init_voxel(w.dims, w.lo, w.hi, T, w.corr_dims, bb, cd, w.xq, pose=pz, prec=prec)
+        oxc, ocv, oJ, oit = oracle.solve(w.dims, w.lo, w.hi, T, w.xq, a0, b0, c0v, pose=pz, tol=w.tol,
+                                         div_thresh=w.div_thresh, max_iters=w.max_iters, prec=prec)
+        if not args.no_grad:
+            oracle.grad(w.dims, w.lo, w.hi, T, w.W, w.B, oxc, oJ, ocv, gx, pose=pz, mode=0, prec=prec)
+        return time.perf_counter() - c0, ocv
+    best, ocv = None, None
+    for _ in range(2):
+        dt, ocv = one("f32")
+        best = dt if best is None else min(best, dt)
+    dt64, ocv64 = one("f64")
+    base = {"value": int(ocv.sum()) / best, "unit": "solves/s", "cores": ncores, "kind": "oracle",
+            "sample": "the whole workload of this run, same step (strict-fp32 oracle, best of 2 passes)",
+            "seconds": best,
+            "float64_oracle": {"value": int(ocv64.sum()) / dt64, "seconds": dt64, "converged_pairs": int(ocv64.sum())}}
+    return base, {"conv_equal": bool((ocv == case.cv.cpu().numpy()).all())}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2, help="workload configuration 1..5 (default 2: SMPL-scale)")
+    ap.add_argument("--config", type=int, default=5,
+                    help="headline workload configuration 1..5 (default 5: multi-pose, the largest that one GPU takes)")
+    ap.add_argument("--launches", type=int, default=100,
+                    help="extra steps, after the timed region, with HIP events between the fs_* calls (median / p10 / p90 per call)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-per-config", action="store_true", help="time the headline configuration only")
+    ap.add_argument("--no-microbench", action="store_true", help="skip the library's micro-benchmarks of the gather ceilings")
     ap.add_argument("--no-grad", action="store_true", help="leave fs_grad out of the step")
     ap.add_argument("--no-slots", action="store_true",
                     help="fs_grad counts lanes per cell itself instead of reusing fs_solve's counts")
@@ -118,168 +280,82 @@ def main():
         resolution_sweep(torch, binding, wl, dev)
         return
 
-    w = wl.make_config(args.config)
-    N, K = w.N, w.K
-    ctx = binding.Context(w.dims, w.n_bones, w.lo, w.hi, n_poses=w.n_poses, tol=w.tol, div_thresh=w.div_thresh,
-                          max_iters=w.max_iters, init_mode=w.init_mode, grad_mode=binding.FS_GRAD_BROYDEN_J,
-                          corr_dims=w.corr_dims)
-    up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
-    W, B, xq = up(w.W), up(w.B), up(w.xq)
-    pose = up(w.pose) if w.n_poses > 1 else None
-    gxc = up(w.upstream_grads())
-    f32, u8 = torch.float32, torch.uint8
-    x0 = torch.empty((K, 3, N), dtype=f32, device=dev)
-    J0 = torch.empty((K, 9, N), dtype=f32, device=dev)
-    v0 = torch.empty((K, N), dtype=u8, device=dev)
-    xc = torch.empty((K, 3, N), dtype=f32, device=dev)
-    Jo = torch.empty((K, 9, N), dtype=f32, device=dev)
-    cv = torch.empty((K, N), dtype=u8, device=dev)
-    it = torch.empty((K, N), dtype=u8, device=dev)
-    gW = torch.empty(w.W.shape, dtype=f32, device=dev)
-    gB = torch.empty(w.B.shape, dtype=f32, device=dev)
-    gxq = torch.empty((3, N), dtype=f32, device=dev)
-    slot = None if args.no_slots else torch.empty((K, N), dtype=torch.int32, device=dev)
-    # with the cell positions handed on, J~ can stay in the library's result records
-    Jarg = None if slot is not None else Jo
-
-    ev = lambda: torch.cuda.Event(enable_timing=True)
-    marks = []
-
-    def step(record):
-        e = [ev() for _ in range(5)] if record else None
-        if record: e[0].record()
-        ctx.precompute(W, B)
-        if record: e[1].record()
-        if args.unfused:
-            ctx.init(xq, pose, N, x0, J0, v0)
-        if record: e[2].record()
-        if args.unfused:
-            ctx.solve(xq, pose, N, K, x0, J0, v0, xc, cv, Jarg, it, slot)
-        else:
-            ctx.solve(xq, pose, N, K, None, None, None, xc, cv, Jarg, it, slot)
-        if record: e[3].record()
-        if not args.no_grad:
-            ctx.grad(W, xc, Jarg, cv, gxc, pose, N, K, gW, gB, gxq, slot)
-        if record: e[4].record()
-        if record: marks.append(e)
-
-    for _ in range(args.warmup):
-        step(False)
-    torch.cuda.synchronize()
-    ctx.set_timing(True)          # HIP events around the Broyden kernel itself, on its stream
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step(False)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-
-    kernel_ms_total, kernel_launches = ctx.get_timing()
-    ctx.set_timing(False)
-    solve_kernel_ms = kernel_ms_total / max(kernel_launches, 1)
-    # per-call breakdown from a second, untimed pass (the event records between the calls cost a few
-    # microseconds each and stay out of the timed region)
-    for _ in range(min(args.steps, 20)):
-        step(True)
-    torch.cuda.synchronize()
-    phases = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(4)] for e in marks])   # ms
-    pre_ms, init_ms, solve_ms, grad_ms = phases.mean(0)
-
-    ctx.init(xq, pose, N, x0, J0, v0)                 # (untimed) validity flags for the lane-iteration count
-    torch.cuda.synchronize()
-    conv = int(cv.sum().item())
-    valid = int(v0.sum().item())
-    steps_total = int(it.to(torch.int64)[v0 == 1].sum().item())
-    evals = steps_total + valid                       # field evaluations = active lane-iterations
-    flops = evals * FLOP_EVAL + steps_total * (FLOP_UPDATE + FLOP_STEP)
-    achieved = flops / (solve_kernel_ms * 1e-3) / 1e12
-
-    # transform grids (all poses) of at most 64 KiB are held in LDS by k_solve; larger ones go to k_solve_ws
-    grid_in_lds = w.n_poses * w.dims[0] * w.dims[1] * w.dims[2] * 48 <= 64 * 1024
+    case = Case(args.config, args, torch, binding, wl, dev)
+    case.measure(args.steps, args.warmup, args.launches)
+    w = case.w
     out = {
         "metric": "converged (point, init) root solves/sec",
-        "value": conv / (ms_per_step * 1e-3),
+        "value": case.conv / (case.ms_per_step * 1e-3),
         "unit": "solves/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": case.ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"config {args.config} ({w.name}): grid {w.dims[0]}x{w.dims[1]}x{w.dims[2]}, "
-                               f"{w.n_bones} bones, {w.n_poses} pose(s), {N} points x {K} inits, "
-                               f"max_iters {w.max_iters}, tol {w.tol}",
+        "config": {"workload": case.workload(),
                    "step": "fs_precompute + " + ("fs_init + fs_solve" if args.unfused else "fs_solve (initial states fused)")
                            + ("" if args.no_grad else " + fs_grad")
-                           + ("" if slot is None else (", cell positions handed from the solve to the backward"
-                                                       + (", J~ kept in the library" if Jarg is None else ""))),
-                   "pairs": N * K, "valid_pairs": valid, "converged_pairs": conv,
-                   "lane_iterations": evals},
-        "breakdown_ms": {"fs_precompute": float(pre_ms), "fs_init": float(init_ms), "fs_solve": float(solve_ms),
-                         "fs_grad": float(grad_ms)},
-        "solve_only": {"converged_solves_per_s": conv / (solve_ms * 1e-3),
-                       "lane_iterations_per_s": evals / (solve_ms * 1e-3)},
-        "roofline": {"kernel": "k_solve" if grid_in_lds else "k_solve_ws", "bound": "alu", "achieved": achieved, "peak": PEAK_FP32_TFLOPS,
-                     "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_TFLOPS, "traffic": None,
-                     "flop_per_launch": flops, "avg_launch_ms": float(solve_kernel_ms), "launches_timed": kernel_launches},
+                           + ("" if case.slot is None else (", cell positions handed from the solve to the backward"
+                                                            + (", J~ kept in the library" if case.Jarg is None else ""))),
+                   "pairs": case.N * case.K, "valid_pairs": case.valid, "converged_pairs": case.conv,
+                   "lane_iterations": case.evals},
+        "calls_ms": case.calls,
+        "solve_only": {"converged_solves_per_s": case.conv / (case.calls["fs_solve"]["median"] * 1e-3),
+                       "lane_iterations_per_s": case.evals / (case.calls["fs_solve"]["median"] * 1e-3)},
+        "iteration_histogram": case.iter_hist,
+        "roofline": case.roofline(),
     }
+    if case.slot is not None:
+        # one position in its grid cell's list per converged lane, handed out by integer atomics inside the Broyden kernel
+        # (requests of one wave for the same cell are sent as one atomic)
+        out["slot_requests_per_s"] = case.conv / (case.kernel_ms * 1e-3)
 
-    # ceilings of the solve kernel measured on this device by the library's micro-benchmarks
-    grid_bytes = int(w.n_poses * w.dims[0] * w.dims[1] * w.dims[2] * 48)
-    fma = binding.microbench(binding.MB_FMA)
-    gl = binding.microbench(binding.MB_GATHER_LANE, max(grid_bytes, 4096))
-    gline = binding.microbench(binding.MB_GATHER_LINE, max(grid_bytes, 4096))
-    glds = binding.microbench(binding.MB_LDS_GATHER)
-    loads = evals * LOADS_EVAL / (solve_kernel_ms * 1e-3)
-    out["roofline"].update({
-        "peak_unpacked": PEAK_FP32_UNPACKED_TFLOPS, "frac_unpacked": achieved / PEAK_FP32_UNPACKED_TFLOPS,
-        "measured_fma_tflops": fma / 1e12,
-        "gather_path": {"algorithmic_16B_loads_per_s": loads,
-                        "ceiling_lane_random_gather_same_footprint": gl, "frac_of_lane_gather": loads / gl,
-                        "ceiling_line_coalesced_gather_same_footprint": gline,
-                        "ceiling_lds_lane_random_gather": glds, "footprint_bytes": grid_bytes},
-        "traffic": (SOLVE_TRAFFIC_BYTES_NO_SLOTS if args.no_slots else SOLVE_TRAFFIC_BYTES).get(args.config)})
-    if args.config in SOLVE_L1_ACCESSES and not args.no_slots and not args.unfused:
-        # the texture path's own roofline: served gathers per second against the ceiling measured on this device for
-        # the kernel's mix of L1 hits (lane-random gathers from an L1-resident array) and L2 hits (from an array of
-        # the grid's size)
-        acc, req = SOLVE_L1_ACCESSES[args.config], SOLVE_L1_TO_L2_REQUESTS[args.config]
-        hit = 1.0 - req / acc
-        g1 = binding.microbench(binding.MB_GATHER_LANE, 8192)
-        blended = 1.0 / (hit / g1 + (1.0 - hit) / gl)
-        served = acc / (solve_kernel_ms * 1e-3)
-        out["roofline"]["gather_path"].update({
-            "l1_accesses_per_launch": acc, "l1_hit_rate": hit, "served_16B_gathers_per_s": served,
-            "ceiling_lane_random_gather_l1_resident": g1, "ceiling_for_this_hit_rate": blended,
-            "frac_of_ceiling_for_this_hit_rate": served / blended})
+    if not args.no_microbench:
+        # ceilings of the solve kernel measured on this device by the library's micro-benchmarks
+        gb = max(case.grid_bytes, 4096)
+        fma = binding.microbench(binding.MB_FMA)
+        gl = binding.microbench(binding.MB_GATHER_LANE, gb)
+        gline = binding.microbench(binding.MB_GATHER_LINE, gb)
+        glds = binding.microbench(binding.MB_LDS_GATHER)
+        loads = case.evals * LOADS_EVAL / (case.kernel_ms * 1e-3)
+        out["roofline"].update({
+            "measured_fma_tflops": fma / 1e12,
+            "gather_path": {"algorithmic_16B_loads_per_s": loads, "footprint_bytes": case.grid_bytes,
+                            "ceiling_line_coalesced_gather_same_footprint": gline,
+                            "frac_of_line_coalesced_ceiling": loads / gline,
+                            "ceiling_lds_lane_random_gather": glds, "frac_of_lds_ceiling": loads / glds,
+                            "lane_random_gather_same_footprint": gl}})
 
     if args.probe_copy_mib > 0:
-        a = torch.empty(args.probe_copy_mib << 18, dtype=f32, device=dev)
-        b = torch.ones(args.probe_copy_mib << 18, dtype=f32, device=dev)
+        a = torch.empty(args.probe_copy_mib << 18, dtype=torch.float32, device=dev)
+        b = torch.ones(args.probe_copy_mib << 18, dtype=torch.float32, device=dev)
         torch.cuda.synchronize()
         a.copy_(b)
         torch.cuda.synchronize()
 
     if not args.no_cpu_baseline:
-        import oracle
-        ncores = int(os.environ.get("OMP_NUM_THREADS", len(os.sched_getaffinity(0))))
-        pz = w.pose if w.n_poses > 1 else None
-        best = None
-        for rep in range(2):
-            c0 = time.perf_counter()
-            T = oracle.precompute(w.dims, w.W, w.B, prec="f32")
-            if w.init_mode == 0:
-                a0, b0, c0v = oracle.init_bone(w.dims, w.lo, w.hi, T, w.B, w.xq, pose=pz, prec="f32")
-            else:
-                bb, cd = oracle.corr_build(w.dims, w.lo, w.hi, T, w.corr_dims, prec="f32")
-                a0, b0, c0v = oracle.init_voxel(w.dims, w.lo, w.hi, T, w.corr_dims, bb, cd, w.xq, pose=pz, prec="f32")
-            oxc, ocv, oJ, oit = oracle.solve(w.dims, w.lo, w.hi, T, w.xq, a0, b0, c0v, pose=pz, tol=w.tol,
-                                             div_thresh=w.div_thresh, max_iters=w.max_iters, prec="f32")
-            if not args.no_grad:
-                oracle.grad(w.dims, w.lo, w.hi, T, w.W, w.B, oxc, oJ, ocv, w.upstream_grads(), pose=pz, mode=0, prec="f32")
-            dt = time.perf_counter() - c0
-            best = dt if best is None else min(best, dt)
-        out["cpu_baseline"] = {"value": int(ocv.sum()) / best, "unit": "solves/s", "cores": ncores, "kind": "oracle",
-                               "sample": "the whole workload of this run, same step (strict-fp32 oracle, best of 2 passes)",
-                               "seconds": best}
-        out["parity_spot_check"] = {"conv_equal": bool((ocv == cv.cpu().numpy()).all())}
+        out["cpu_baseline"], out["parity_spot_check"] = cpu_baseline(case, args)
+    case.close()
+    del case
+    torch.cuda.empty_cache()
+
+    if not args.no_per_config:
+        per = {}
+        for cfg in (1, 2, 3, 4, 5):
+            if cfg == args.config:
+                continue
+            c = Case(cfg, args, torch, binding, wl, dev)
+            c.measure(max(10, min(args.steps, 50)), max(3, args.warmup), min(args.launches, 50))
+            r = c.roofline()
+            per[str(cfg)] = {"workload": c.workload(), "ms_per_step": c.ms_per_step,
+                             "value": c.conv / (c.ms_per_step * 1e-3),
+                             "converged_pairs": c.conv, "valid_pairs": c.valid, "lane_iterations": c.evals,
+                             "calls_ms": {k: (v["median"] if isinstance(v, dict) else v) for k, v in c.calls.items()},
+                             "kernel": r["kernel"], "kernel_ms": r["avg_launch_ms"], "evaluations_per_s": r["evaluations_per_s"],
+                             "tflops": r["achieved"], "frac": r["frac"], "frac_unpacked": r["frac_unpacked"],
+                             "traffic": r["traffic"]}
+            c.close()
+            del c
+            torch.cuda.empty_cache()
+        out["per_config"] = per
     print(json.dumps(out))
 
 

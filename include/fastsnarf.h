@@ -99,12 +99,13 @@ fs_status fs_set_tuning(fs_ctx *ctx, int32_t chunk, int32_t refill_min, int32_t 
                         int32_t lds_grid);
 
 /* The waves of a block of the solve kernel hand work to each other through queues in LDS (one wave prepares
- * initial states, the others iterate), and every wait on such a queue is bounded: a wave that has polled
- * `polls` times in vain (about 0.2 us each; default 2^22) gives up and leaves, so the kernel always ends.
+ * initial states, the others iterate).  The preparing wave's wait for room in those queues is bounded: when it has
+ * polled `polls` times in vain (about 0.2 us each; default 2^22) it gives up and leaves, and the iterating waves,
+ * which wait for nothing but that wave, finish what they hold and leave too, so the kernel always ends.
  * The call during which that happened returns FS_OK (nothing is synchronised), its results are incomplete,
  * and every later call on the context that uses the device returns FS_E_DEVICE: destroy the context.  No healthy run
- * comes near the default; the limit exists for tests of this path (polls = 0: the consumers give up at
- * their first empty queue).  polls >= 0. */
+ * comes near the default; the limit exists for tests of this path (polls = 0: the preparing wave gives up the first
+ * time it finds every queue full).  polls >= 0. */
 fs_status fs_set_spin_limit(fs_ctx *ctx, int32_t polls);
 
 /* Pre-compute linear blend skinning on the grid nodes, Eq. (13) / Sec. 3.1 "Pre-computing
@@ -179,30 +180,12 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
 fs_status fs_dedupe(fs_ctx *ctx, const float *d_xc, const uint8_t *d_conv, int64_t N, int32_t K, float min_dist,
                     uint8_t *d_keep, int32_t *d_offsets, float *d_roots, int32_t *d_lane, int64_t cap);
 
-/* Timing of the Broyden kernel alone (k_solve, without the unpacking of its results): while enabled,
- * every fs_solve brackets that kernel with two HIP events on the context's stream.  fs_get_timing
- * synchronises the stream, returns the summed elapsed milliseconds and the number of launches since
- * the last call, and releases the events. */
-fs_status fs_set_timing(fs_ctx *ctx, int32_t enable);
-fs_status fs_get_timing(fs_ctx *ctx, double *solve_kernel_ms, int32_t *launches);
-
 /* Copy library-owned state out for inspection (device to device, on the stream).
  *   fs_get_transforms: d_T [n_poses][V][12], the pre-computed grid in node order.
  *   fs_get_corr: d_bbox [n_poses][6] (lo xyz, hi xyz), d_cand [n_poses][ncell][corr_k] node index
  *   or -1, cell index = (cx*corr_ny + cy)*corr_nz + cz.  FS_E_STATE unless FS_INIT_VOXEL. */
 fs_status fs_get_transforms(fs_ctx *ctx, float *d_T);
 fs_status fs_get_corr(fs_ctx *ctx, float *d_bbox, int32_t *d_cand);
-
-/* Measurement support (not part of the articulation path): micro-benchmarks of the ceilings that bound
- * fs_solve on the current device, run on the default stream, synchronising.
- *   FS_MB_FMA          *result = fp32 flop/s of independent fused multiply-add chains
- *   FS_MB_GATHER_LANE  *result = 16-byte loads per second when every SIMD lane reads its own random
- *                      address inside an array of array_bytes (the tri-linear lookup's access pattern)
- *   FS_MB_GATHER_LINE  same, but 8 adjacent lanes share one aligned 128-byte line
- *   FS_MB_LDS_GATHER   16-byte loads per second, every lane its own random address in 48 KiB of LDS
- * array_bytes is used by the two global gathers only (4 KiB .. 4 GiB). */
-enum { FS_MB_FMA = 0, FS_MB_GATHER_LANE = 1, FS_MB_GATHER_LINE = 2, FS_MB_LDS_GATHER = 3 };
-fs_status fs_microbench(int32_t which, int64_t array_bytes, double *result);
 
 /* Message for the last non-OK status returned on this context ("" if none). */
 const char *fs_last_error(const fs_ctx *ctx);

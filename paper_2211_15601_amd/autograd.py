@@ -30,17 +30,22 @@ class CorrespondenceSearch(torch.autograd.Function):
         slot = torch.empty((K, N), dtype=torch.int32, device=xq.device)
         fs.solve(xq, pose, N, K, None, None, None, xc, conv, Jinv, None, slot)
         ctx.fs = fs
-        ctx.slot, ctx.serial = slot, fs.solve_serial
+        ctx.slot, ctx.serial, ctx.pre_serial = slot, fs.solve_serial, fs.pre_serial
         ctx.pose = pose
-        ctx.save_for_backward(W, xc, Jinv, conv)
+        ctx.save_for_backward(W, B, xc, Jinv, conv)
         ctx.shapes = (W.shape, B.shape)
         ctx.mark_non_differentiable(conv)
         return xc, conv
 
     @staticmethod
     def backward(ctx, g_xc, _g_conv):
-        W, xc, Jinv, conv = ctx.saved_tensors
+        W, B, xc, Jinv, conv = ctx.saved_tensors
         fs = ctx.fs
+        # fs_grad multiplies by the bone transforms (and, in exact-J mode, reads the transform grid) of the last
+        # fs_precompute on the context: if another forward has replaced them since, put this one's back
+        if fs.pre_serial != ctx.pre_serial:
+            fs.precompute(W, B)
+            ctx.pre_serial = fs.pre_serial
         K, _, N = xc.shape
         gW = torch.empty(ctx.shapes[0], dtype=torch.float32, device=xc.device)
         gB = torch.empty(ctx.shapes[1], dtype=torch.float32, device=xc.device)

@@ -76,8 +76,9 @@ def load():
     L.fs_set_timing.argtypes = [vp, i32]
     L.fs_get_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
     L.fs_dedupe.argtypes = [vp, vp, vp, i64, i32, ctypes.c_float, vp, vp, vp, vp, i64]
-    for name in EXPORTS[:14]:
-        getattr(L, name).restype = ctypes.c_int
+    for name in EXPORTS:
+        if name not in ("fs_last_error", "fs_version"):
+            getattr(L, name).restype = ctypes.c_int
     _lib = L
     return L
 
@@ -150,6 +151,7 @@ class Context:
         return self._ret(self._L.fs_set_spin_limit(self._h, int(polls)), check)
 
     def precompute(self, W, B, check=True):
+        self.pre_serial = getattr(self, "pre_serial", 0) + 1          # lets a caller tell whose W and B the context holds
         return self._ret(self._L.fs_precompute(self._h, _ptr(W), _ptr(B)), check)
 
     def init(self, xq, pose, N, x0, Jinv0, valid0, check=True):

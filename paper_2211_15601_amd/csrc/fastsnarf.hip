@@ -1,6 +1,7 @@
 // C ABI of the Fast-SNARF articulation library (see include/fastsnarf.h): argument checks,
 // context-owned device buffers and kernel launches.  gfx950 only.
 #include "../../include/fastsnarf.h"
+#include "../../include/fastsnarf_bench.h"
 #include "fs_kernels.hpp"
 
 #include <hip/hip_runtime.h>
@@ -57,13 +58,15 @@ struct fs_ctx {
     size_t vcap;       // points voffs / vlist can hold
     int scan_cap;      // tiles scan_sums can hold
     int n_cus, occ_blocks_per_cu, occ_ws_blocks_per_cu, chunk, refill_min, blocks_per_cu, point_major, lds_grid;
-    int spin_limit;    // polls of a work queue before a wave of the producer / consumer solve kernel gives up
+    int spin_limit;    // polls for room in its consumers' queues before the producer wave of a solve block gives up
     int pre_serial;    // number of the last fs_precompute; cursor[2] == pre_serial: that grid has an entry that is not finite
     int *gave_up;      // pinned host word, mapped into the device: a wave that gave up sets it
     int *gave_up_dev;  // the device's address of it
     // optional timing of the Broyden kernel alone (events on the context's stream)
     bool timing;
     std::vector<std::pair<hipEvent_t, hipEvent_t>> *timed;
+    // caller pointers the runtime has already confirmed as memory of this device (direct-mapped by address)
+    const void *ptr_seen[128];
     char err[256];
 };
 
@@ -80,17 +83,27 @@ fs_status fail(fs_ctx *c, fs_status s, const char *fmt, ...)
     return s;
 }
 
-bool device_ptr_ok(const fs_ctx *c, const void *p, bool nullable)
+// Null, alignment and "is memory of this context's device".  The last needs a lookup in the runtime (about a
+// microsecond; a step makes some thirty such checks and a small step lasts 150 us), so a pointer that passed it
+// once is remembered per context: a training or serving loop passes the same buffers again and again.  A
+// remembered pointer whose memory the caller has freed since is the caller's error, as it would be one
+// instruction after a fresh check.
+bool device_ptr_ok(fs_ctx *c, const void *p, bool nullable)
 {
     if (!p) return nullable;
-    if ((reinterpret_cast<uintptr_t>(p) & 15u) != 0) return false;
+    const uintptr_t u = reinterpret_cast<uintptr_t>(p);
+    if ((u & 15u) != 0) return false;
+    const size_t h = (size_t)((u >> 4) ^ (u >> 11) ^ (u >> 20)) & 127u;
+    if (c->ptr_seen[h] == p) return true;
     hipPointerAttribute_t a;
     if (hipPointerGetAttributes(&a, p) != hipSuccess) {
         (void)hipGetLastError();
         return false;
     }
     if (a.type != hipMemoryTypeDevice && a.type != hipMemoryTypeManaged) return false;
-    return a.device == c->device;
+    if (a.device != c->device) return false;
+    c->ptr_seen[h] = p;
+    return true;
 }
 
 #define FS_CHECK_PTR(ctx, p, nullable)                                                            \
@@ -639,15 +652,14 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
     return launch_status(ctx, "fs_grad");
 }
 
-fs_status fs_dedupe(fs_ctx *ctx, const float *d_xc, const uint8_t *d_conv, int64_t N, int32_t K, float min_dist,
-                    uint8_t *d_keep, int32_t *d_offsets, float *d_roots, int32_t *d_lane, int64_t cap)
+static fs_status dedupe_impl(fs_ctx *ctx, const char *who, const float *d_xc, const uint8_t *d_conv, int64_t N,
+                             int32_t K, float min_dist, uint8_t *d_keep, int32_t *d_offsets, float *d_roots, int32_t *d_lane,
+                             int64_t cap)
 {
-    if (!ctx) return FS_E_ARG;
-    { fs_status gs = check_gave_up(ctx, "fs_dedupe"); if (gs != FS_OK) return gs; }
-    if (K < 1 || K > FS_MAX_BONES) return fail(ctx, FS_E_SHAPE, "fs_dedupe: K must be in 1..%d", (int)FS_MAX_BONES);
-    if (N < 0 || (long long)N * K >= (1ll << 31)) return fail(ctx, FS_E_SHAPE, "fs_dedupe: need 0 <= N and K*N < 2^31");
-    if (!(min_dist >= 0.0f) || !std::isfinite(min_dist)) return fail(ctx, FS_E_ARG, "fs_dedupe: min_dist must be finite and >= 0");
-    if (cap < 0) return fail(ctx, FS_E_SHAPE, "fs_dedupe: cap must be >= 0");
+    if (K < 1 || K > FS_MAX_BONES) return fail(ctx, FS_E_SHAPE, "%s: K must be in 1..%d", who, (int)FS_MAX_BONES);
+    if (N < 0 || (long long)N * K >= (1ll << 31)) return fail(ctx, FS_E_SHAPE, "%s: need 0 <= N and K*N < 2^31", who);
+    if (!(min_dist >= 0.0f) || !std::isfinite(min_dist)) return fail(ctx, FS_E_ARG, "%s: min_dist must be finite and >= 0", who);
+    if (cap < 0) return fail(ctx, FS_E_SHAPE, "%s: cap must be >= 0", who);
     FS_CHECK_PTR(ctx, d_offsets, false);
     FS_CHECK_PTR(ctx, d_roots, true);
     FS_CHECK_PTR(ctx, d_lane, true);
@@ -661,7 +673,15 @@ fs_status fs_dedupe(fs_ctx *ctx, const float *d_xc, const uint8_t *d_conv, int64
     { fs_status ss = scan_exclusive(ctx, (int)N, d_offsets); if (ss != FS_OK) return ss; }
     if (N > 0 && (d_roots || d_lane))
         k_pack_roots<<<grid1d(N, 256), 256, 0, st>>>(N, K, cap, d_xc, d_keep, d_offsets, d_roots, d_lane);
-    return launch_status(ctx, "fs_dedupe");
+    return launch_status(ctx, who);
+}
+
+fs_status fs_dedupe(fs_ctx *ctx, const float *d_xc, const uint8_t *d_conv, int64_t N, int32_t K, float min_dist,
+                    uint8_t *d_keep, int32_t *d_offsets, float *d_roots, int32_t *d_lane, int64_t cap)
+{
+    if (!ctx) return FS_E_ARG;
+    { fs_status gs = check_gave_up(ctx, "fs_dedupe"); if (gs != FS_OK) return gs; }
+    return dedupe_impl(ctx, "fs_dedupe", d_xc, d_conv, N, K, min_dist, d_keep, d_offsets, d_roots, d_lane, cap);
 }
 
 fs_status fs_set_timing(fs_ctx *ctx, int32_t enable)

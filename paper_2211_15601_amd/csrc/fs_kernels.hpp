@@ -879,8 +879,9 @@ __global__ __launch_bounds__(256, 3) void k_solve(GridP G, SolveP S, InitP I, co
 // lanes pick states up with a few LDS reads, and its loop holds nothing but the Broyden step.  The producer
 // gives every batch to the consumer whose queue is emptiest.  Neither role ever holds the other's registers.
 // Queues: single producer, single consumer; tail is written by the producer only, head by the consumer only.
-// Every wait is bounded: a wave that has polled its queue S.spin_limit times in vain raises *give_up (host-visible)
-// and leaves; the producer raises s_done on its way out in any case, so its consumers leave too.
+// Every wait ends: a producer that has polled S.spin_limit times in vain for room in its consumers' queues raises
+// *give_up (host-visible) and leaves; it raises s_done on every way out, and its consumers, which wait for
+// nothing else, finish what their queues hold and leave too.
 // ------------------------------------------------------------------------------------------------
 constexpr int WS_RING = 128;                 // entries per queue (two batches)
 constexpr int FS_WS_CONSUMERS = 3;           // measured: one producer keeps up with three consumers, not with four
@@ -1180,7 +1181,7 @@ __global__ __launch_bounds__(64 * (NCONS + 1), SKIP ? 2 : 3) void k_solve_ws(Gri
     // ---------------------------------------------------- consumer ----------------------------------------------------
     float (&ring)[ST_FIELDS][WS_RING] = s_ring[wib];
     bool active = false;
-    int n = 0, k = 0, it = 0, pz = 0, head = 0, spins = 0;
+    int n = 0, k = 0, it = 0, pz = 0, head = 0;
     const float *Tp = T;
     float xp[3] = {0, 0, 0}, x[3] = {0, 0, 0}, xt[3] = {0, 0, 0}, g[3] = {0, 0, 0}, dx[3] = {0, 0, 0};
     float J[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
@@ -1235,18 +1236,12 @@ __global__ __launch_bounds__(64 * (NCONS + 1), SKIP ? 2 : 3) void k_solve_ws(Gri
             // nothing in flight: more to come?  (s_done is read before the tail: the producer raises it last)
             const int d = __builtin_amdgcn_readfirstlane(lds_load_acquire(&s_done));
             const int tail = __builtin_amdgcn_readfirstlane(lds_load_acquire(&s_tail[wib]));
+            // a consumer waits for nothing but its own block's producer, whose waits are all bounded and which
+            // raises s_done on every way out: this loop ends when the producer has
             if (tail == head) {
-                if (d) {
-                    run = false;
-                } else if (++spins > S.spin_limit) {
-                    if (lane == 0) *give_up = 1;
-                    run = false;
-                } else {
-                    __builtin_amdgcn_s_sleep(8);
-                }
+                if (d) run = false;
+                else __builtin_amdgcn_s_sleep(8);
             }
-        } else {
-            spins = 0;
         }
         bool want_slot = false;
         int slot_cell = 0;

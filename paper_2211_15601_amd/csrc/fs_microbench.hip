@@ -2,7 +2,7 @@
 // it runs on -- fp32 fused multiply-add issue rate, per-lane 16-byte gathers from a cache-resident
 // array (the access pattern of the tri-linear lookup: every SIMD lane its own address) and the
 // same gathers from LDS.  Not part of the articulation path itself.
-#include "../../include/fastsnarf.h"
+#include "../../include/fastsnarf_bench.h"
 
 #include <hip/hip_runtime.h>
 

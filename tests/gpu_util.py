@@ -87,6 +87,35 @@ class GpuRun:
         return gW.cpu().numpy(), gB.cpu().numpy(), gxq.cpu().numpy() if want_gxq else None
 
 
+# Element-wise bar for gradient tensors.  Every output entry is an fp32 sum of n products omega * lambda_r * [x*; 1]_j
+# (n up to ~10^4 lanes around a crowded grid node, times 12 entries x P poses for dL/dW, times V nodes for dL/dB) added
+# in an order that differs from the oracle's, so its error is about sqrt(n) 2^-24 times the SUM OF MAGNITUDES of its
+# terms, not times the entry itself: entries that are small through cancellation carry the error of their large
+# terms.  The magnitude sum is bounded by that of the tensor's largest entries, hence an absolute part tied to the
+# tensor's maximum: sqrt(1e4) * 6e-8 = 6e-6, doubled for the two stages (G_T, then the contraction with B or W),
+# plus a relative part of the same size for the rounding of lambda itself (a 3x3 product: a few 2^-24).
+GRAD_ATOL_OF_MAX = 1.2e-5
+GRAD_RTOL = 1.2e-5
+
+
+def assert_grad_close(name, a, b, label="", atol_of_max=GRAD_ATOL_OF_MAX, rtol=GRAD_RTOL):
+    """|a - b| <= atol_of_max * max|b| + rtol * |b| for every element; prints the relative L2 distance and how much
+    of the bar the worst element used."""
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    assert a.shape == b.shape, (name, a.shape, b.shape)
+    assert np.isfinite(a).all(), f"{label} {name}: not finite"
+    bmax = float(np.abs(b).max()) if b.size else 0.0
+    bar = atol_of_max * bmax + rtol * np.abs(b)
+    err = np.abs(a - b)
+    used = float((err / np.maximum(bar, 1e-300)).max()) if b.size else 0.0
+    rel = float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+    print(f"{label} {name}: relative L2 {rel:.2e}, worst element uses {used:.3f} of its bar "
+          f"(max |b| {bmax:.3e}, max |a-b| {float(err.max()) if b.size else 0.0:.3e})")
+    assert (err <= bar).all(), (label, name, used, rel)
+    return rel, used
+
+
 def oracle_inits(w, T, prec="f32"):
     pose = w.pose if w.n_poses > 1 else None
     if w.init_mode == 0:
