@@ -16,7 +16,8 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libfs_oracle.so")
+# FS_ORACLE_LIB: load another build of the same source instead (the sanitizer-instrumented one, in its own process)
+_LIB_PATH = os.environ.get("FS_ORACLE_LIB") or os.path.join(_HERE, "libfs_oracle.so")
 _lib = None
 
 

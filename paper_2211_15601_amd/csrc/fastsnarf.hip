@@ -39,6 +39,7 @@ struct fs_ctx {
     int *fill;         // [P][V] arrival slot of a node inside its cell
     int *order;        // [P][V]
     int32_t *cand;     // [P][ncell][ck]
+    float4 *cinit;     // [P][ncell][ck][4] initial state of every candidate (k_corr_init)
     unsigned *cursor;  // work cursor of the solve kernel
     int *gcount;       // [P*ncells + 1] per-cell lane counts, then offsets (backward)
     int *gcount_solve; // [P*ncells + 1] per-cell counts of converged lanes written by the last fs_solve that gave slots
@@ -54,12 +55,14 @@ struct fs_ctx {
     size_t srec_cap;   // float4 entries srec can hold
     int *scan_sums;    // tile sums of the prefix scans
     int *voffs;        // [N + 1] candidates per point, then offsets (fused voxel solve; grows on demand)
-    int *vlist;        // [K*N] pairs that have a candidate
-    size_t vcap;       // points voffs / vlist can hold
+    uint8_t *vcnt;     // [N] candidates per point
+    int *vgcell;       // [N] pose * ncell + correspondence cell of every point
+    int2 *vlist;       // [K*N] pairs that have a candidate: {point, cell << 3 | k}
+    size_t vcap;       // points voffs / vcnt / vgcell / vlist can hold
     int scan_cap;      // tiles scan_sums can hold
-    int n_cus, occ_blocks_per_cu, occ_ws_blocks_per_cu, chunk, refill_min, blocks_per_cu, point_major, lds_grid;
+    int n_cus, occ_blocks_per_cu, occ_ws_blocks_per_cu, occ_vx_blocks_per_cu, chunk, refill_min, blocks_per_cu, point_major, lds_grid;
     int spin_limit;    // polls for room in its consumers' queues before the producer wave of a solve block gives up
-    int pre_serial;    // number of the last fs_precompute; cursor[2] == pre_serial: that grid has an entry that is not finite
+    int pre_serial;    // number of the last fs_precompute; cursor[CUR_NONFINITE] == pre_serial: that grid has an entry that is not finite
     int *gave_up;      // pinned host word, mapped into the device: a wave that gave up sets it
     int *gave_up_dev;  // the device's address of it
     // optional timing of the Broyden kernel alone (events on the context's stream)
@@ -162,7 +165,7 @@ int grid1d(long long n, int block) { return (int)((n + block - 1) / block); }
 void free_all(fs_ctx *c)
 {
     void *ptrs[] = {c->T, c->Bdev, c->Binv, c->Bok, c->GT, c->Y, c->bb_ord, c->bbox,
-                    c->cell_of, c->count, c->fill, c->order, c->cand, c->cursor, c->gcount, c->gcount_solve, c->gpos, c->grec, c->scan_sums, c->srec, c->gpart, c->voffs, c->vlist};
+                    c->cell_of, c->count, c->fill, c->order, c->cand, c->cursor, c->gcount, c->gcount_solve, c->gpos, c->grec, c->scan_sums, c->srec, c->gpart, c->voffs, c->vlist, c->cinit, c->vcnt, c->vgcell};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
 }
@@ -253,14 +256,17 @@ fs_status fs_create(const fs_grid_desc *desc, const fs_params *params, void *hip
     }
     const size_t P = desc->n_poses, nb = desc->n_bones;
     bool ok = dev_alloc(&c->T, P * V * 12) && dev_alloc(&c->Bdev, P * nb * 12) && dev_alloc(&c->Binv, P * nb * 12) &&
-              dev_alloc(&c->Bok, P * nb) && dev_alloc(&c->cursor, 4);
-    if (ok) ok = hipMemset(c->cursor, 0, 4 * sizeof(unsigned)) == hipSuccess;
+              dev_alloc(&c->Bok, P * nb) && dev_alloc(&c->cursor, CUR_WORDS);
+    if (ok) ok = hipMemset(c->cursor, 0, CUR_WORDS * sizeof(unsigned)) == hipSuccess;
     {
         int per_cu = 0, cus = 0;
         int per_cu_ws = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_solve<true, true>, 256, 0) != hipSuccess || per_cu < 1) per_cu = 2;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_ws, k_solve_ws<true, true, FS_WS_CONSUMERS, false>, 64 * (FS_WS_CONSUMERS + 1), 0) != hipSuccess || per_cu_ws < 1) per_cu_ws = 2;
         c->occ_ws_blocks_per_cu = per_cu_ws;
+        int per_cu_vx = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_vx, k_solve_ws<true, true, FS_VX_CONSUMERS, false>, 64 * (FS_VX_CONSUMERS + 1), 0) != hipSuccess || per_cu_vx < 1) per_cu_vx = 2;
+        c->occ_vx_blocks_per_cu = per_cu_vx;
         c->spin_limit = 1 << 22;   /* x about 0.2 us per poll */
         c->blocks_per_cu = 0;      /* 0: chosen per call */
         c->point_major = 1;
@@ -278,7 +284,8 @@ fs_status fs_create(const fs_grid_desc *desc, const fs_params *params, void *hip
         C.ncell = C.cx * C.cy * C.cz;
         ok = dev_alloc(&c->Y, P * V * 3) && dev_alloc(&c->bb_ord, P * 6) && dev_alloc(&c->bbox, P * 6) &&
              dev_alloc(&c->cell_of, P * V) && dev_alloc(&c->count, P * C.ncell + 1) && dev_alloc(&c->fill, P * V) &&
-             dev_alloc(&c->order, P * V) && dev_alloc(&c->cand, P * (size_t)C.ncell * C.ck);
+             dev_alloc(&c->order, P * V) && dev_alloc(&c->cand, P * (size_t)C.ncell * C.ck) &&
+             dev_alloc(&c->cinit, P * (size_t)C.ncell * C.ck * 4);
     }
     if (ok) {
         ok = hipHostMalloc(reinterpret_cast<void **>(&c->gave_up), sizeof(int), hipHostMallocMapped) == hipSuccess;
@@ -360,7 +367,7 @@ fs_status fs_precompute(fs_ctx *ctx, const float *d_W, const float *d_B)
     hipStream_t st = ctx->stream;
     ++ctx->pre_serial;
     k_precompute<<<grid1d(G.V, 256), 256, 0, st>>>(G, d_W, d_B, ctx->T, ctx->Bdev, ctx->Binv, ctx->Bok,
-                                                   reinterpret_cast<int *>(ctx->cursor + 2), ctx->pre_serial);
+                                                   reinterpret_cast<int *>(ctx->cursor + CUR_NONFINITE), ctx->pre_serial);
     if (ctx->prm.init_mode == FS_INIT_VOXEL) {
         const CorrP &C = ctx->C;
         const int ncp = G.P * C.ncell;
@@ -372,6 +379,7 @@ fs_status fs_precompute(fs_ctx *ctx, const float *d_W, const float *d_B)
         { fs_status ss = scan_exclusive(ctx, ncp, ctx->count); if (ss != FS_OK) return ss; }
         k_corr_scatter<<<gv, 256, 0, st>>>(G, C, ctx->cell_of, ctx->count, ctx->fill, ctx->order);
         k_corr_select<<<grid1d((long long)ncp * WAVE, 256), 256, 0, st>>>(G, C, ctx->Y, ctx->bbox, ctx->count, ctx->order, ctx->cand);
+        k_corr_init<<<grid1d((long long)ncp * C.ck, 256), 256, 0, st>>>(G, C, ctx->T, ctx->cand, ctx->cinit);
     }
     fs_status s = launch_status(ctx, "fs_precompute");
     if (s == FS_OK) ctx->have_T = true;
@@ -398,8 +406,8 @@ fs_status fs_init(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_t
         k_init_bone<<<grid1d(total, 256), 256, 0, ctx->stream>>>(ctx->G, ctx->T, ctx->Binv, ctx->Bok, d_xq, d_pose, N,
                                                                  d_x0, d_Jinv0, d_valid0);
     else
-        k_init_voxel<<<grid1d(total, 256), 256, 0, ctx->stream>>>(ctx->G, ctx->C, ctx->T, ctx->bbox, ctx->cand, d_xq,
-                                                                  d_pose, N, d_x0, d_Jinv0, d_valid0);
+        k_init_voxel<<<grid1d(total, 256), 256, 0, ctx->stream>>>(ctx->G, ctx->C, ctx->bbox, ctx->cinit, d_xq, d_pose, N,
+                                                                  d_x0, d_Jinv0, d_valid0);
     return launch_status(ctx, "fs_init");
 }
 
@@ -443,15 +451,17 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     const size_t grid_bytes = (size_t)ctx->G.P * ctx->G.V * 48;
     const bool lds = ctx->lds_grid && grid_bytes <= FS_LDS_GRID_MAX;
     // Launch shape.  Grid in LDS (k_solve): latency / ALU bound, every wave the registers allow, refill at 32 idle
-    // lanes.  Grid read through the caches (k_solve_ws, bound by the vector-memory path, where more waves thrash
-    // the L1): blocks of one producer and FS_WS_CONSUMERS consumers; measured fastest with 2 blocks per CU for one
-    // initial state per bone (many long trajectories) and for grids far beyond the L2, and with 3 for the shorter
-    // list of voxel-based candidates, which start near their roots, on a grid the L2 holds; consumers refill from
-    // their queue at 8 idle lanes (4 ... 16: no difference).
+    // lanes.  Grid read through the caches (k_solve_ws, bound by the vector-memory path): blocks of one producer and
+    // several consumers, 2 blocks per CU (measured: more waves that compute Eq. (8) only thrash the L1); consumers
+    // refill from their queue at 8 idle lanes (4 ... 16: no difference).
+    const bool voxel_list = fused && ctx->prm.init_mode == FS_INIT_VOXEL;     // the solve draws from the list of pairs that have a candidate
+    // fused voxel-based candidates: the producer only looks initial states up (k_corr_init computed them once per pose)
+    const bool vx = !lds && voxel_list;
     const int wpb = lds ? 4 : 1;       // waves of a block that draw chunks from the cursor
-    const int auto_blocks = lds ? 3 : ((fused && ctx->prm.init_mode == FS_INIT_VOXEL && grid_bytes <= (32u << 20)) ? 3 : 2);
+    const int auto_blocks = lds ? 3 : 2;
     const int want_blocks = ctx->blocks_per_cu ? (lds ? std::max(ctx->blocks_per_cu, 3) : ctx->blocks_per_cu) : auto_blocks;
-    const int per_cu = std::max(1, std::min(want_blocks, lds ? ctx->occ_blocks_per_cu : ctx->occ_ws_blocks_per_cu));
+    const int occ = lds ? ctx->occ_blocks_per_cu : (vx ? ctx->occ_vx_blocks_per_cu : ctx->occ_ws_blocks_per_cu);
+    const int per_cu = std::max(1, std::min(want_blocks, occ));
     S.refill_min = ctx->refill_min ? ctx->refill_min : (lds ? 32 : 8);
     const int blocks = (int)std::min<long long>(grid1d(chunks, wpb), (long long)per_cu * ctx->n_cus);
     InitP I;
@@ -461,6 +471,7 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     I.C = ctx->C;
     I.bbox = ctx->bbox;
     I.cand = ctx->cand;
+    I.cinit = ctx->cinit;
     const bool with_J = d_Jinv != nullptr || d_slot != nullptr;     // with d_slot alone J~ stays in the result records
     const size_t need = (size_t)S.total * (with_J ? 4 : 1);
     if (need > ctx->srec_cap) {
@@ -472,21 +483,25 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
         ctx->srec_cap = need;
     }
     hipStream_t st = ctx->stream;
-    const int *list = nullptr, *list_len = nullptr;
-    if (fused && ctx->prm.init_mode == FS_INIT_VOXEL) {
+    const int2 *list = nullptr;
+    const int *list_len = nullptr;
+    if (voxel_list) {
         if ((size_t)N > ctx->vcap) {
             (void)hipStreamSynchronize(st);
-            if (ctx->voffs) (void)hipFree(ctx->voffs);
-            if (ctx->vlist) (void)hipFree(ctx->vlist);
-            ctx->voffs = ctx->vlist = nullptr;
+            for (void *q : {(void *)ctx->voffs, (void *)ctx->vlist, (void *)ctx->vcnt, (void *)ctx->vgcell})
+                if (q) (void)hipFree(q);
+            ctx->voffs = ctx->vgcell = nullptr;
+            ctx->vlist = nullptr;
+            ctx->vcnt = nullptr;
             ctx->vcap = 0;
-            if (!dev_alloc(&ctx->voffs, (size_t)N + 1) || !dev_alloc(&ctx->vlist, (size_t)N * K))
+            if (!dev_alloc(&ctx->voffs, (size_t)N + 1) || !dev_alloc(&ctx->vlist, (size_t)N * K) ||
+                !dev_alloc(&ctx->vcnt, (size_t)N) || !dev_alloc(&ctx->vgcell, (size_t)N))
                 return fail(ctx, FS_E_ALLOC, "fs_solve: out of device memory for the pair list");
             ctx->vcap = (size_t)N;
         }
-        k_voxel_count<<<grid1d(N, 256), 256, 0, st>>>(ctx->G, I, N, d_xq, d_pose, ctx->voffs);
+        k_voxel_count<<<grid1d(N, 256), 256, 0, st>>>(ctx->G, I, N, d_xq, d_pose, ctx->voffs, ctx->vcnt, ctx->vgcell);
         { fs_status ss = scan_exclusive(ctx, (int)N, ctx->voffs); if (ss != FS_OK) return ss; }
-        k_voxel_expand<<<grid1d(N, 256), 256, 0, st>>>(N, K, ctx->voffs, ctx->vlist);
+        k_voxel_expand<<<grid1d(N, 256), 256, 0, st>>>(N, ctx->voffs, ctx->vgcell, ctx->vlist);
         list = ctx->vlist;
         list_len = ctx->voffs + N;
     }
@@ -511,31 +526,32 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
 #define FS_LAUNCH_SOLVE(F, J)                                                                                          \
     k_solve<F, J><<<dim3(blocks), dim3(4 * WAVE), grid_bytes, st>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, d_x0, d_Jinv0, \
                                                                     d_valid0, ctx->srec, ctx->cursor, list, list_len,  \
-                                                                    cell_count, ncell, d_slot)
+                                                                    cell_count, ncell)
         if (fused && with_J) FS_LAUNCH_SOLVE(true, true);
         else if (fused) FS_LAUNCH_SOLVE(true, false);
         else if (with_J) FS_LAUNCH_SOLVE(false, true);
         else FS_LAUNCH_SOLVE(false, false);
 #undef FS_LAUNCH_SOLVE
     } else {
-#define FS_LAUNCH_SOLVE(F, J, Z)                                                                                       \
-    k_solve_ws<F, J, FS_WS_CONSUMERS, Z><<<dim3(blocks), dim3((FS_WS_CONSUMERS + 1) * WAVE), 0, st>>>(                 \
+#define FS_LAUNCH_SOLVE(F, J, NC, Z)                                                                                   \
+    k_solve_ws<F, J, NC, Z><<<dim3(blocks), dim3((NC + 1) * WAVE), 0, st>>>(                                           \
         ctx->G, S, I, ctx->T, d_xq, d_pose, d_x0, d_Jinv0, d_valid0, ctx->srec, ctx->cursor, list, list_len, cell_count,  \
-        ncell, d_slot, ctx->gave_up_dev, reinterpret_cast<const int *>(ctx->cursor + 2), ctx->pre_serial)
-        // one state per bone starts many lanes outside the box (51 % of the evaluations on the SMPL-scale scene
-        // have a clamped coordinate): there the consumers skip the corner records of weight zero (kernel -8 %);
-        // voxel-based candidates start inside it, and the bookkeeping costs more than it saves (+15 %)
+        ncell, ctx->gave_up_dev, reinterpret_cast<const int *>(ctx->cursor + CUR_NONFINITE), ctx->pre_serial)
+        // Z = true: contexts with one state per bone.  Many of those lanes start outside the box (51 % of the
+        // evaluations on the SMPL-scale scene have a clamped coordinate): the consumers skip the corner records of
+        // weight zero (kernel -8 %).  Z = false: voxel-based candidates, which start inside it, where the bookkeeping
+        // costs more than it saves (+15 %); with fused initial states the producer reads them from the table
         const bool skip = ctx->prm.init_mode == FS_INIT_BONE;
         if (skip) {
-            if (fused && with_J) FS_LAUNCH_SOLVE(true, true, true);
-            else if (fused) FS_LAUNCH_SOLVE(true, false, true);
-            else if (with_J) FS_LAUNCH_SOLVE(false, true, true);
-            else FS_LAUNCH_SOLVE(false, false, true);
+            if (fused && with_J) FS_LAUNCH_SOLVE(true, true, FS_WS_CONSUMERS, true);
+            else if (fused) FS_LAUNCH_SOLVE(true, false, FS_WS_CONSUMERS, true);
+            else if (with_J) FS_LAUNCH_SOLVE(false, true, FS_WS_CONSUMERS, true);
+            else FS_LAUNCH_SOLVE(false, false, FS_WS_CONSUMERS, true);
         } else {
-            if (fused && with_J) FS_LAUNCH_SOLVE(true, true, false);
-            else if (fused) FS_LAUNCH_SOLVE(true, false, false);
-            else if (with_J) FS_LAUNCH_SOLVE(false, true, false);
-            else FS_LAUNCH_SOLVE(false, false, false);
+            if (fused && with_J) FS_LAUNCH_SOLVE(true, true, FS_VX_CONSUMERS, false);
+            else if (fused) FS_LAUNCH_SOLVE(true, false, FS_VX_CONSUMERS, false);
+            else if (with_J) FS_LAUNCH_SOLVE(false, true, FS_WS_CONSUMERS, false);
+            else FS_LAUNCH_SOLVE(false, false, FS_WS_CONSUMERS, false);
         }
 #undef FS_LAUNCH_SOLVE
     }
@@ -543,16 +559,15 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
         (void)hipEventRecord(ev1, st);
         ctx->timed->emplace_back(ev0, ev1);
     }
-    const bool nocand = fused && ctx->prm.init_mode == FS_INIT_VOXEL;
     const int ub = grid1d(S.total, 256);
-    if (with_J && nocand)
-        k_solve_unpack<true, true><<<ub, 256, 0, st>>>(N, S.total, ctx->voffs, ctx->srec, d_xc, d_conv, d_Jinv, d_iters, d_slot);
+    if (with_J && voxel_list)
+        k_solve_unpack<true, true><<<ub, 256, 0, st>>>(N, S.total, ctx->vcnt, ctx->srec, d_xc, d_conv, d_Jinv, d_iters, d_slot);
     else if (with_J)
-        k_solve_unpack<true, false><<<ub, 256, 0, st>>>(N, S.total, ctx->voffs, ctx->srec, d_xc, d_conv, d_Jinv, d_iters, d_slot);
-    else if (nocand)
-        k_solve_unpack<false, true><<<ub, 256, 0, st>>>(N, S.total, ctx->voffs, ctx->srec, d_xc, d_conv, d_Jinv, d_iters, d_slot);
+        k_solve_unpack<true, false><<<ub, 256, 0, st>>>(N, S.total, nullptr, ctx->srec, d_xc, d_conv, d_Jinv, d_iters, d_slot);
+    else if (voxel_list)
+        k_solve_unpack<false, true><<<ub, 256, 0, st>>>(N, S.total, ctx->vcnt, ctx->srec, d_xc, d_conv, d_Jinv, d_iters, d_slot);
     else
-        k_solve_unpack<false, false><<<ub, 256, 0, st>>>(N, S.total, ctx->voffs, ctx->srec, d_xc, d_conv, d_Jinv, d_iters, d_slot);
+        k_solve_unpack<false, false><<<ub, 256, 0, st>>>(N, S.total, nullptr, ctx->srec, d_xc, d_conv, d_Jinv, d_iters, d_slot);
     fs_status lst = launch_status(ctx, "fs_solve");
     if (lst == FS_OK && d_slot) {
         ctx->slots_N = N;
@@ -627,7 +642,7 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
         float4 *grec4 = reinterpret_cast<float4 *>(ctx->grec);
         if (from_rec)   // the solve's own result records are still in the context: one 64-byte read per pair
             k_grad_records<true><<<rg, 256, 0, st>>>(G, mode, ctx->T, d_xc, d_Jinv, d_conv, d_gxc, d_pose, N, K, ncell, ctx->gcount, pos,
-                                                    grec4, d_gxq, groups, ctx->srec, ctx->slots_list ? ctx->voffs : nullptr);
+                                                    grec4, d_gxq, groups, ctx->srec, ctx->slots_list ? ctx->vcnt : nullptr);
         else
             k_grad_records<false><<<rg, 256, 0, st>>>(G, mode, ctx->T, d_xc, d_Jinv, d_conv, d_gxc, d_pose, N, K, ncell, ctx->gcount, pos,
                                                      grec4, d_gxq, groups, nullptr, nullptr);

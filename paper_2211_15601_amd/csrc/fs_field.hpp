@@ -20,6 +20,7 @@ struct GridP {
 
 struct Cell {
     int base;        // float offset of corner (0,0,0) inside one pose's grid
+    int ci[3];       // the cell's index along x, y, z
     float f[3];
     bool cl[3];      // coordinate was clamped to the box along this axis
 };
@@ -45,7 +46,16 @@ __device__ __forceinline__ Cell locate(const GridP &G, const float x[3])
     locate_axis(x[1], G.lo[1], G.inv_h[1], G.m[1], G.ny, iy, c.f[1], c.cl[1]);
     locate_axis(x[2], G.lo[2], G.inv_h[2], G.m[2], G.nz, iz, c.f[2], c.cl[2]);
     c.base = ix * G.sx + iy * G.sy + iz * 12;
+    c.ci[0] = ix;
+    c.ci[1] = iy;
+    c.ci[2] = iz;
     return c;
+}
+
+// linear index of the cell among the (nx-1)(ny-1)(nz-1) cells of one pose
+__device__ __forceinline__ int cell_linear(const GridP &G, const Cell &c)
+{
+    return (c.ci[0] * (G.ny - 1) + c.ci[1]) * (G.nz - 1) + c.ci[2];
 }
 
 // corner c = a + 2b + 4cz with offsets (a, b, cz) along (x, y, z)

@@ -169,12 +169,13 @@ __device__ __forceinline__ int cell_index(const CorrP &C, const float *__restric
            cell_coord(y[2], bb[2], cs2, C.cz);
 }
 
-__global__ __launch_bounds__(256) void k_init_voxel(GridP G, CorrP C, const float *__restrict__ T,
-                                                    const float *__restrict__ bbox, const int32_t *__restrict__ cand,
-                                                    const float *__restrict__ xq, const int32_t *__restrict__ pose,
-                                                    long long N, float *__restrict__ o_x0, float *__restrict__ o_J,
+__global__ __launch_bounds__(256) void k_init_voxel(GridP G, CorrP C, const float *__restrict__ bbox,
+                                                    const float4 *__restrict__ cinit, const float *__restrict__ xq,
+                                                    const int32_t *__restrict__ pose, long long N,
+                                                    float *__restrict__ o_x0, float *__restrict__ o_J,
                                                     uint8_t *__restrict__ o_v)
 {
+    // the candidate's initial state was computed once per pose by k_corr_init
     const long long q = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (q >= N * C.ck) return;
     const int k = (int)(q / N);
@@ -182,16 +183,11 @@ __global__ __launch_bounds__(256) void k_init_voxel(GridP G, CorrP C, const floa
     const int p = pose_of(pose, n, G.P);
     const float y[3] = {xq[n], xq[N + n], xq[2 * N + n]};
     const int cell = cell_index(C, bbox + p * 6, y);
-    const int v = cand[((long long)p * C.ncell + cell) * C.ck + k];
-    float x0[3] = {0, 0, 0}, Ji[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
-    bool ok = false;
-    if (v >= 0) {
-        node_pos(G, v, x0);
-        float d[3], J[9];
-        field_dJ(T + (long long)p * G.V * 12, G, x0, d, J);
-        ok = inv3(J, Ji);
-    }
-    write_init(q, N, k, n, x0, Ji, ok, o_x0, o_J, o_v);
+    const float4 *ci = cinit + (((long long)p * C.ncell + cell) * C.ck + k) * 4;
+    const float4 a = ci[0], b = ci[1], c = ci[2], d = ci[3];
+    const float x0[3] = {a.x, a.y, a.z};
+    const float Ji[9] = {b.w, c.x, c.y, c.z, c.w, d.x, d.y, d.z, d.w};
+    write_init(q, N, k, n, x0, Ji, (__float_as_int(a.w) & 1) != 0, o_x0, o_J, o_v);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -470,6 +466,44 @@ __global__ __launch_bounds__(256) void k_corr_select(GridP G, CorrP C, const flo
         for (int j = na; j < C.ck; ++j) out[j] = -1;
 }
 
+// Initial state of every candidate of the correspondence grid, once per fs_precompute instead of once per pair: a
+// candidate is a grid node, so its x0, its image d(x0) and J~0 = (dd/dx at x0)^-1 depend on the pose alone, not on
+// the query point.  Entry (4 float4) of candidate k of cell gc, at [(gc * ck + k) * 4]:
+// {x0[3], flags | d(x0)[3], J~0[0] | J~0[1..4] | J~0[5..8]}, flags (integer bits) = 0: no such candidate,
+// 1: usable, 2: Jacobian singular (J~0 = 0), plus the linear index of x0's grid cell << 2.
+// Same arithmetic as a lane computing it for itself (node_pos, the 8 corner records of x0's cell,
+// jacobian_from_corners, inv3).
+__global__ __launch_bounds__(256) void k_corr_init(GridP G, CorrP C, const float *__restrict__ T,
+                                                   const int32_t *__restrict__ cand, float4 *__restrict__ cinit)
+{
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (long long)G.P * C.ncell * C.ck) return;
+    const int p = (int)(i / ((long long)C.ncell * C.ck));
+    const int v = cand[i];
+    float x0[3] = {0, 0, 0}, d[3] = {0, 0, 0}, Ji[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+    int flags = 0;
+    if (v >= 0) {
+        node_pos(G, v, x0);
+        const float *Tp = T + (long long)p * G.V * 12;
+        const Cell c0 = locate(G, x0);
+        float q[8][12], Jac[9];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) load12(Tp + c0.base + corner_off(G, c), q[c]);
+        jacobian_from_corners(G, c0, q, x0, d, Jac);
+        const bool ok = inv3(Jac, Ji);
+        if (!ok) {
+#pragma unroll
+            for (int e = 0; e < 9; ++e) Ji[e] = 0.0f;
+        }
+        flags = (ok ? 1 : 2) | (cell_linear(G, c0) << 2);
+    }
+    float4 *o = cinit + i * 4;
+    o[0] = make_float4(x0[0], x0[1], x0[2], __int_as_float(flags));
+    o[1] = make_float4(d[0], d[1], d[2], Ji[0]);
+    o[2] = make_float4(Ji[1], Ji[2], Ji[3], Ji[4]);
+    o[3] = make_float4(Ji[5], Ji[6], Ji[7], Ji[8]);
+}
+
 // ------------------------------------------------------------------------------------------------
 // Broyden solve.  Lanes are persistent: a wave draws chunks of consecutive lanes q = k*N + n from a
 // global cursor and hands a new one to each SIMD lane that has finished, so that a wave does not
@@ -489,14 +523,6 @@ struct SolveP {
     int spin_limit;      // producer / consumer kernel: polls of a work queue before a wave gives up
 };
 
-__device__ __forceinline__ int cell_linear(const GridP &G, const Cell &c)
-{
-    // c.base = ((ix*ny + iy)*nz + iz)*12 in node strides; recover the cell's own linear index
-    const int ix = c.base / G.sx, rem = c.base - ix * G.sx;
-    const int iy = rem / G.sy, iz = (rem - iy * G.sy) / 12;
-    return (ix * (G.ny - 1) + iy) * (G.nz - 1) + iz;
-}
-
 // What the fused variant needs to compute initial states itself (same arithmetic as k_init_*).
 struct InitP {
     int mode;                 // 0: one state per bone (Eq. (8)); 1: candidates of the correspondence grid
@@ -505,8 +531,13 @@ struct InitP {
     CorrP C;
     const float *bbox;        // [P][6]
     const int32_t *cand;      // [P][ncell][ck]
+    const float4 *cinit;      // [P][ncell][ck][4]: initial state of every candidate (k_corr_init)
 };
 
+// Result record of one pair.  WITH_J: 16 floats {x*[3], flags | pos, J~[0..2] | J~[3..6] | J~[7], J~[8], pad[2]}, else 4 floats
+// {x*[3], flags}; flags = conv | iters << 8 (as an integer bit pattern).  `pos` (the lane's position in its grid cell's
+// list, for the backward) is not written here but later, by flush_slots, for converged lanes only: this store leaves
+// that word alone, so the two never write the same address.  x*, flags and pos share the record's first 32-byte sector.
 template <bool WITH_J>
 __device__ __forceinline__ void write_record(float4 *__restrict__ rec, long long pq, const float x[3], const float J[9],
                                              int flags)
@@ -514,45 +545,62 @@ __device__ __forceinline__ void write_record(float4 *__restrict__ rec, long long
     if (WITH_J) {
         float4 *o = rec + pq * 4;
         o[0] = make_float4(x[0], x[1], x[2], __int_as_float(flags));
-        o[1] = make_float4(J[0], J[1], J[2], J[3]);
-        o[2] = make_float4(J[4], J[5], J[6], J[7]);
-        o[3] = make_float4(J[8], 0.0f, 0.0f, 0.0f);
+        float *j = reinterpret_cast<float *>(o) + 5;
+        j[0] = J[0];
+        j[1] = J[1];
+        j[2] = J[2];
+        o[2] = make_float4(J[3], J[4], J[5], J[6]);
+        o[3] = make_float4(J[7], J[8], 0.0f, 0.0f);
     } else {
         rec[pq] = make_float4(x[0], x[1], x[2], __int_as_float(flags));
     }
+}
+constexpr int REC_POS = 4;      // float index of `pos` inside a 16-float record
+
+__device__ __forceinline__ void read_record_J(const float4 *__restrict__ r, float (&J)[9])
+{
+    const float4 b = r[1], c = r[2], d = r[3];
+    J[0] = b.y; J[1] = b.z; J[2] = b.w; J[3] = c.x; J[4] = c.y; J[5] = c.z; J[6] = c.w; J[7] = d.x; J[8] = d.y;
 }
 
 // Voxel-based initial states leave most lanes without a candidate (a ray sample in empty space has
 // none).  Pre-pass for the fused solve: candidates per point, prefix sum, then the list of pairs
 // that do have one, so that the solve kernel draws only those.
 __global__ __launch_bounds__(256) void k_voxel_count(GridP G, InitP I, long long N, const float *__restrict__ xq,
-                                                     const int32_t *__restrict__ pose, int *__restrict__ cnt)
+                                                     const int32_t *__restrict__ pose, int *__restrict__ cnt,
+                                                     uint8_t *__restrict__ cnt8, int *__restrict__ gcell)
 {
     const long long n = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (n >= N) return;
     const int p = pose_of(pose, n, G.P);
     const float xp[3] = {xq[n], xq[N + n], xq[2 * N + n]};
-    const int32_t *c = I.cand + ((long long)p * I.C.ncell + cell_index(I.C, I.bbox + p * 6, xp)) * I.C.ck;
+    const int gc = p * I.C.ncell + cell_index(I.C, I.bbox + p * 6, xp);
+    const int32_t *c = I.cand + (long long)gc * I.C.ck;
     int m = 0;
     for (int k = 0; k < I.C.ck; ++k) m += c[k] >= 0 ? 1 : 0;     // candidates are packed at the front
     cnt[n] = m;
+    cnt8[n] = (uint8_t)m;
+    gcell[n] = gc;
 }
 
-__global__ __launch_bounds__(256) void k_voxel_expand(long long N, int K, const int *__restrict__ offs,
-                                                      int *__restrict__ list)
+// list entry of a pair: {point n, (pose * ncell + correspondence cell) << 3 | k}
+__global__ __launch_bounds__(256) void k_voxel_expand(long long N, const int *__restrict__ offs, const int *__restrict__ gcell,
+                                                      int2 *__restrict__ list)
 {
     const long long n = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (n >= N) return;
-    const int b = offs[n], e = offs[n + 1];
-    for (int j = b; j < e; ++j) list[j] = (int)(n * K + (j - b));
+    const int b = offs[n], e = offs[n + 1], gc = gcell[n];
+    for (int j = b; j < e; ++j) list[j] = make_int2((int)n, (gc << 3) | (j - b));
 }
 
 // records -> caller's layout: one thread per pair q = k*N + n, consecutive threads consecutive n.
 // NOCAND: the solve ran with fused voxel-based initial states and wrote no record for lanes whose
-// cell holds no k-th candidate (cand_offs[n+1] - cand_offs[n] = candidates of point n, packed at the front);
+// cell holds no k-th candidate (cand_cnt[n] = candidates of point n, packed at the front);
 // those get the answer of an invalid lane (x0 = 0, J~ = 0, not converged).
+// o_slot (may be null): the positions of the converged lanes in their grid cells' lists, which the solve kernel
+// left in the records, -1 for every other lane.
 template <bool WITH_J, bool NOCAND>
-__global__ __launch_bounds__(256) void k_solve_unpack(long long N, long long total, const int *__restrict__ cand_offs,
+__global__ __launch_bounds__(256) void k_solve_unpack(long long N, long long total, const uint8_t *__restrict__ cand_cnt,
                                                       const float4 *__restrict__ rec, float *__restrict__ o_x,
                                                       uint8_t *__restrict__ o_conv, float *__restrict__ o_J,
                                                       uint8_t *__restrict__ o_it, int32_t *__restrict__ o_slot)
@@ -561,8 +609,8 @@ __global__ __launch_bounds__(256) void k_solve_unpack(long long N, long long tot
     if (pq >= total) return;
     const long long k = pq / N, n = pq - k * N;
     bool have = true;
-    if (NOCAND) have = k < cand_offs[n + 1] - cand_offs[n];
-    float4 a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    if (NOCAND) have = k < cand_cnt[n];
+    float4 a = make_float4(0.0f, 0.0f, 0.0f, 0.0f), b = a;
     if (have) a = WITH_J ? rec[pq * 4] : rec[pq];
     o_x[(k * 3 + 0) * N + n] = a.x;
     o_x[(k * 3 + 1) * N + n] = a.y;
@@ -570,22 +618,26 @@ __global__ __launch_bounds__(256) void k_solve_unpack(long long N, long long tot
     const int flags = __float_as_int(a.w);
     o_conv[pq] = (uint8_t)(flags & 1);
     if (o_it) o_it[pq] = (uint8_t)(flags >> 8);
-    // the solve wrote the positions of its converged lanes into o_slot itself; the others are marked here
-    if (o_slot && !(flags & 1)) o_slot[pq] = -1;
+    if (WITH_J && (o_slot || o_J) && have) b = rec[pq * 4 + 1];
+    if (WITH_J && o_slot) o_slot[pq] = (flags & 1) ? __float_as_int(b.x) : -1;
     if (WITH_J && o_J) {
         float J[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
         if (have) {
-            const float4 b = rec[pq * 4 + 1], c = rec[pq * 4 + 2], d = rec[pq * 4 + 3];
-            J[0] = b.x; J[1] = b.y; J[2] = b.z; J[3] = b.w; J[4] = c.x; J[5] = c.y; J[6] = c.z; J[7] = c.w; J[8] = d.x;
+            const float4 c = rec[pq * 4 + 2], d = rec[pq * 4 + 3];
+            J[0] = b.y; J[1] = b.z; J[2] = b.w; J[3] = c.x; J[4] = c.y; J[5] = c.z; J[6] = c.w; J[7] = d.x; J[8] = d.y;
         }
 #pragma unroll
         for (int e = 0; e < 9; ++e) o_J[(k * 9 + e) * N + n] = J[e];
     }
 }
 
+// Words of the context's cursor array: CUR_ALL is the work cursor of the solve kernels; CUR_NONFINITE holds the serial
+// number of the last fs_precompute whose grid had an entry that is not finite.
+constexpr int CUR_ALL = 0, CUR_NONFINITE = 2, CUR_WORDS = 4;
+
 __global__ void k_reset_cursor(unsigned *__restrict__ cursor, unsigned start)
 {
-    if (threadIdx.x == 0 && blockIdx.x == 0) *cursor = start;
+    if (blockIdx.x == 0 && threadIdx.x == 0) cursor[CUR_ALL] = start;
 }
 
 // The parked requests of one wave: entry i = {cell, pair}, one per SIMD lane.  Lanes of one point that reach
@@ -595,7 +647,7 @@ constexpr int PEND = 128;       // requests a wave parks before it sends them
 constexpr int PEND_SEND = 112;  // ... at least this many
 
 __device__ __forceinline__ void flush_slots(int (&pend)[2][PEND], int npend, int lane, int *__restrict__ cell_count,
-                                            int32_t *__restrict__ slot_out)
+                                            float4 *__restrict__ rec)
 {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");      // the LDS writes of the wave's other lanes
     __builtin_amdgcn_wave_barrier();
@@ -628,7 +680,8 @@ __device__ __forceinline__ void flush_slots(int (&pend)[2][PEND], int npend, int
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
         const int bs = __shfl(base[b], leader[b]);
-        if (valid[b]) slot_out[pq[b]] = bs + rank[b];
+        // into the pair's own result record (written a few passes ago, still in the L2), not into an array of its own
+        if (valid[b]) reinterpret_cast<int *>(rec)[(long long)pq[b] * 16 + REC_POS] = bs + rank[b];
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");      // before the entries are overwritten
     __builtin_amdgcn_wave_barrier();
@@ -645,17 +698,15 @@ __device__ __forceinline__ void flush_slots(int (&pend)[2][PEND], int npend, int
 // Results leave the kernel as one contiguous record per pair (lanes finish at different times, so
 // writing the caller's structure-of-arrays layout from here would touch 14 cache lines per pair with
 // 4 bytes each); k_solve_unpack then moves the records into that layout with coalesced stores.
-// Record: WITH_J ? 16 floats {x*[3], flags, J~[9], pad[3]} : 4 floats {x*[3], flags} (who needs no J~ reads only
-// the first 16 bytes);
-// flags = conv | iters << 8 (as an integer bit pattern).
+// (record layout: see write_record).
 template <bool FUSED, bool WITH_J>
 __global__ __launch_bounds__(256, 3) void k_solve(GridP G, SolveP S, InitP I, const float *__restrict__ Tglobal,
                                                const float *__restrict__ xq, const int32_t *__restrict__ pose,
                                                const float *__restrict__ x0, const float *__restrict__ J0,
                                                const uint8_t *__restrict__ valid0, float4 *__restrict__ rec,
-                                               unsigned *__restrict__ cursor, const int *__restrict__ list,
+                                               unsigned *__restrict__ cursor, const int2 *__restrict__ list,
                                                const int *__restrict__ list_len, int *__restrict__ cell_count,
-                                               int ncell, int32_t *__restrict__ slot_out)
+                                               int ncell)
 {
     extern __shared__ float4 s_grid[];
     // converged lanes waiting for their position in their grid cell's list: {cell, pair} per wave
@@ -667,7 +718,7 @@ __global__ __launch_bounds__(256, 3) void k_solve(GridP G, SolveP S, InitP I, co
         __syncthreads();
     }
     const float *T = reinterpret_cast<const float *>(s_grid);
-    // with a list only the pairs list[0 .. *list_len) (encoded n*K + k) are solved
+    // with a list only the pairs list[0 .. *list_len) ({point, cell << 3 | k}) are solved
     const long long total = list ? (long long)*list_len : S.total;
     const int lane = threadIdx.x & 63;
     // wave-uniform: the wave's current chunk is [next, c1).  The first chunk of wave w is chunk w (the cursor
@@ -696,7 +747,7 @@ __global__ __launch_bounds__(256, 3) void k_solve(GridP G, SolveP S, InitP I, co
         while (!exhausted && nidle >= S.refill_min) {
             if (next >= c1) {
                 unsigned b = 0;
-                if (lane == 0) b = atomicAdd(cursor, (unsigned)S.chunk);
+                if (lane == 0) b = atomicAdd(cursor + CUR_ALL, (unsigned)S.chunk);
                 b = (unsigned)__builtin_amdgcn_readfirstlane((int)b);
                 if ((long long)b >= total) {
                     exhausted = true;
@@ -711,9 +762,9 @@ __global__ __launch_bounds__(256, 3) void k_solve(GridP G, SolveP S, InitP I, co
                 if (!active && pq < c1) {
                     // K * N < 2^31: 32-bit division
                     if (list) {
-                        const unsigned e = (unsigned)list[pq];
-                        n = e / (unsigned)S.K;
-                        k = (int)(e - (unsigned)n * (unsigned)S.K);
+                        const int2 e = list[pq];
+                        n = e.x;
+                        k = e.y & 7;
                     } else if (S.point_major) {   // consecutive SIMD lanes: the K initial states of one point
                         n = (unsigned)pq / (unsigned)S.K;
                         k = (int)((unsigned)pq - (unsigned)n * (unsigned)S.K);
@@ -851,7 +902,7 @@ __global__ __launch_bounds__(256, 3) void k_solve(GridP G, SolveP S, InitP I, co
             const unsigned long long m = __ballot(want_slot);
             if (m) {
                 if (npend + __popcll(m) > PEND) {
-                    flush_slots(s_pend[wib], npend, lane, cell_count, slot_out);
+                    flush_slots(s_pend[wib], npend, lane, cell_count, rec);
                     npend = 0;
                 }
                 if (want_slot) {
@@ -862,12 +913,12 @@ __global__ __launch_bounds__(256, 3) void k_solve(GridP G, SolveP S, InitP I, co
                 npend += __popcll(m);
             }
             if (npend >= PEND_SEND) {
-                flush_slots(s_pend[wib], npend, lane, cell_count, slot_out);
+                flush_slots(s_pend[wib], npend, lane, cell_count, rec);
                 npend = 0;
             }
         }
     }
-    if (WITH_J && cell_count && npend > 0) flush_slots(s_pend[wib], npend, lane, cell_count, slot_out);
+    if (WITH_J && cell_count && npend > 0) flush_slots(s_pend[wib], npend, lane, cell_count, rec);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -884,7 +935,11 @@ __global__ __launch_bounds__(256, 3) void k_solve(GridP G, SolveP S, InitP I, co
 // nothing else, finish what their queues hold and leave too.
 // ------------------------------------------------------------------------------------------------
 constexpr int WS_RING = 128;                 // entries per queue (two batches)
-constexpr int FS_WS_CONSUMERS = 3;           // measured: one producer keeps up with three consumers, not with four
+constexpr int FS_WS_CONSUMERS = 3;           // measured: a producer that computes Eq. (8) keeps up with three consumers, not with four
+// A producer that only looks up voxel-based candidates could serve more consumers, but more iterating waves per CU
+// only compete for the vector cache: measured on the multi-pose / training / ray batches, kernel ms with 2 blocks per
+// CU: 3 consumers 1.73 / 0.175 / 0.120, 4 consumers 1.87 / 0.196 / 0.124, 5 consumers 1.92 / 0.213 / 0.138.
+constexpr int FS_VX_CONSUMERS = 3;
 constexpr int ST_XP = 0, ST_X = 3, ST_G = 6, ST_DX = 9, ST_J = 12, ST_N = 21, ST_K = 22, ST_P = 23, ST_FIELDS = 24;
 
 __device__ __forceinline__ int lds_load_acquire(const int *p)
@@ -897,12 +952,12 @@ __device__ __forceinline__ void lds_store_release(int *p, int v)
 }
 
 __device__ __forceinline__ void park_slots(bool want_slot, int slot_cell, int pair, int (&pend)[2][PEND], int &npend, int lane,
-                                           int *__restrict__ cell_count, int32_t *__restrict__ slot_out)
+                                           int *__restrict__ cell_count, float4 *__restrict__ rec)
 {
     const unsigned long long m = __ballot(want_slot);
     if (m) {
         if (npend + __popcll(m) > PEND) {
-            flush_slots(pend, npend, lane, cell_count, slot_out);
+            flush_slots(pend, npend, lane, cell_count, rec);
             npend = 0;
         }
         if (want_slot) {
@@ -913,7 +968,7 @@ __device__ __forceinline__ void park_slots(bool want_slot, int slot_cell, int pa
         npend += __popcll(m);
     }
     if (npend >= PEND_SEND) {
-        flush_slots(pend, npend, lane, cell_count, slot_out);
+        flush_slots(pend, npend, lane, cell_count, rec);
         npend = 0;
     }
 }
@@ -962,13 +1017,13 @@ __device__ __forceinline__ bool blend_apply_z(const Cell &c, const float (&q)[8]
 }
 
 template <bool FUSED, bool WITH_J, int NCONS, bool SKIP>
-__global__ __launch_bounds__(64 * (NCONS + 1), SKIP ? 2 : 3) void k_solve_ws(GridP G, SolveP S, InitP I, const float *__restrict__ T,
+__global__ __launch_bounds__(64 * (NCONS + 1), (SKIP || NCONS > 3) ? 2 : 3) void k_solve_ws(GridP G, SolveP S, InitP I, const float *__restrict__ T,
                                                const float *__restrict__ xq, const int32_t *__restrict__ pose,
                                                const float *__restrict__ x0, const float *__restrict__ J0,
                                                const uint8_t *__restrict__ valid0, float4 *__restrict__ rec,
-                                               unsigned *__restrict__ cursor, const int *__restrict__ list,
+                                               unsigned *__restrict__ cursor, const int2 *__restrict__ list,
                                                const int *__restrict__ list_len, int *__restrict__ cell_count,
-                                               int ncell, int32_t *__restrict__ slot_out, int *__restrict__ give_up,
+                                               int ncell, int *__restrict__ give_up,
                                                const int *__restrict__ nonfinite, int serial)
 {
     __shared__ float s_ring[NCONS][ST_FIELDS][WS_RING];
@@ -988,7 +1043,11 @@ __global__ __launch_bounds__(64 * (NCONS + 1), SKIP ? 2 : 3) void k_solve_ws(Gri
 
     if (wib == NCONS) {
         // ------------------------------------------------ producer ------------------------------------------------
-        // the first chunk of block b is chunk b; the shared cursor starts behind those
+        // the first chunk of block b is chunk b; the shared cursor starts behind those.  (One cursor for the whole chip
+        // on purpose: all XCDs then work through the same stretch of the points at the same time, and what one of them
+        // brought into the memory-side cache serves the others.  With a cursor per XCD over its own eighth of the
+        // points -- one pose per XCD on the multi-pose batch -- the kernel was 13 % slower: eight transform grids
+        // instead of one compete for that cache.)
         long long next = (long long)blockIdx.x * S.chunk;
         long long c1 = min(total, next + S.chunk);
         int tails[NCONS];
@@ -999,7 +1058,7 @@ __global__ __launch_bounds__(64 * (NCONS + 1), SKIP ? 2 : 3) void k_solve_ws(Gri
         while (!lost) {
             if (next >= c1) {
                 unsigned b = 0;
-                if (lane == 0) b = atomicAdd(cursor, (unsigned)S.chunk);
+                if (lane == 0) b = atomicAdd(cursor + CUR_ALL, (unsigned)S.chunk);
                 b = (unsigned)__builtin_amdgcn_readfirstlane((int)b);
                 if ((long long)b >= total) break;
                 next = b;
@@ -1014,10 +1073,12 @@ __global__ __launch_bounds__(64 * (NCONS + 1), SKIP ? 2 : 3) void k_solve_ws(Gri
             float nJ[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
             if (pq < c1) {
                 const unsigned upq = (unsigned)pq;        // K * N < 2^31
+                int gcell = -1;                           // pose * ncell + correspondence cell, when the list gives it
                 if (list) {
-                    const unsigned e = (unsigned)list[pq];
-                    nn = (int)(e / (unsigned)S.K);
-                    nk = (int)(e - (unsigned)nn * (unsigned)S.K);
+                    const int2 e = list[pq];
+                    nn = e.x;
+                    nk = e.y & 7;
+                    gcell = e.y >> 3;
                 } else if (S.point_major) {   // consecutive SIMD lanes: the K initial states of one point
                     nn = (int)(upq / (unsigned)S.K);
                     nk = (int)(upq - (unsigned)nn * (unsigned)S.K);
@@ -1029,37 +1090,22 @@ __global__ __launch_bounds__(64 * (NCONS + 1), SKIP ? 2 : 3) void k_solve_ws(Gri
                 pair = (int)((long long)nk * N + nn);
                 const float *Tn = T + (long long)np * G.V * 12;
                 bool ok, norec = false;     // norec: no record needed, k_solve_unpack knows the answer
+                float d[3] = {0, 0, 0};
+                int c0lin = 0;              // grid cell of the initial state
 #pragma unroll
                 for (int r = 0; r < 3; ++r) nxp[r] = xq[r * N + nn];
-                if (FUSED) {
-                    if (I.mode == 0) {
-                        const float *bi = I.Binv + ((long long)np * G.nb + nk) * 12;
-                        ok = I.Bok[np * G.nb + nk] != 0;
-                        if (ok) {
-                            const float y[3] = {nxp[0] - bi[9], nxp[1] - bi[10], nxp[2] - bi[11]};
+                if (FUSED && SKIP) {
+                    // one state per bone, Eq. (8)
+                    const float *bi = I.Binv + ((long long)np * G.nb + nk) * 12;
+                    ok = I.Bok[np * G.nb + nk] != 0;
+                    if (ok) {
+                        const float y[3] = {nxp[0] - bi[9], nxp[1] - bi[10], nxp[2] - bi[11]};
 #pragma unroll
-                            for (int r = 0; r < 3; ++r)
-                                nx[r] = FS_FMA(bi[r * 3 + 0], y[0], FS_FMA(bi[r * 3 + 1], y[1], bi[r * 3 + 2] * y[2]));
-                        }
-                    } else {
-                        const int cidx = cell_index(I.C, I.bbox + np * 6, nxp);
-                        const int v = I.cand[((long long)np * I.C.ncell + cidx) * I.C.ck + nk];
-                        ok = v >= 0;
-                        norec = !ok;
-                        if (ok) node_pos(G, v, nx);
-                    }
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 3; ++r) nx[r] = x0[((long long)nk * 3 + r) * N + nn];
-#pragma unroll
-                    for (int e = 0; e < 9; ++e) nJ[e] = J0[((long long)nk * 9 + e) * N + nn];
-                    ok = valid0[(long long)nk * N + nn] != 0;
-                }
-                if (ok) {
-                    const Cell c0 = locate(G, nx);
-                    float qn[8][12];
-                    float d[3];
-                    if (FUSED && SKIP) {
+                        for (int r = 0; r < 3; ++r)
+                            nx[r] = FS_FMA(bi[r * 3 + 0], y[0], FS_FMA(bi[r * 3 + 1], y[1], bi[r * 3 + 2] * y[2]));
+                        const Cell c0 = locate(G, nx);
+                        c0lin = cell_linear(G, c0);
+                        float qn[8][12];
                         // corner records of weight zero contribute nothing to the Jacobian either (the derivative of
                         // their weight vanishes along the clamped axis by definition and carries the zero factor
                         // along the others): fetch the rest, zeros in their place, and if an entry of the blend
@@ -1090,38 +1136,52 @@ __global__ __launch_bounds__(64 * (NCONS + 1), SKIP ? 2 : 3) void k_solve_ws(Gri
 #pragma unroll
                             for (int e = 0; e < 9; ++e) nJ[e] = 0.0f;
                         }
-                    } else if (FUSED) {
+                    }
+                } else if (FUSED) {
+                    // voxel-based candidates: x0, d(x0) and J~0 of a candidate do not depend on the query point and
+                    // were computed once per pose (k_corr_init); a lane only looks its candidate up
+                    if (gcell < 0) gcell = np * I.C.ncell + cell_index(I.C, I.bbox + np * 6, nxp);
+                    const float4 *ci = I.cinit + ((long long)gcell * I.C.ck + nk) * 4;
+                    const float4 a = ci[0], b = ci[1], c = ci[2], e = ci[3];
+                    const int fl = __float_as_int(a.w);
+                    ok = (fl & 1) != 0;
+                    norec = (fl & 3) == 0;
+                    c0lin = fl >> 2;
+                    nx[0] = a.x; nx[1] = a.y; nx[2] = a.z;
+                    d[0] = b.x; d[1] = b.y; d[2] = b.z;
+                    nJ[0] = b.w; nJ[1] = c.x; nJ[2] = c.y; nJ[3] = c.z; nJ[4] = c.w;
+                    nJ[5] = e.x; nJ[6] = e.y; nJ[7] = e.z; nJ[8] = e.w;
+                } else {
 #pragma unroll
-                        for (int c = 0; c < 8; ++c) load12(Tn + c0.base + corner_off(G, c), qn[c]);
-                        float Jac[9];
-                        jacobian_from_corners(G, c0, qn, nx, d, Jac);      // d: the same arithmetic as blend_apply
-                        ok = inv3(Jac, nJ);
-                        if (!ok) {
+                    for (int r = 0; r < 3; ++r) nx[r] = x0[((long long)nk * 3 + r) * N + nn];
 #pragma unroll
-                            for (int e = 0; e < 9; ++e) nJ[e] = 0.0f;
-                        }
-                    } else {
+                    for (int e = 0; e < 9; ++e) nJ[e] = J0[((long long)nk * 9 + e) * N + nn];
+                    ok = valid0[(long long)nk * N + nn] != 0;
+                    if (ok) {
+                        const Cell c0 = locate(G, nx);
+                        c0lin = cell_linear(G, c0);
+                        float qn[8][12];
 #pragma unroll
                         for (int c = 0; c < 8; ++c) load12(Tn + c0.base + corner_off(G, c), qn[c]);
                         blend_apply(c0, qn, nx, d);
                     }
-                    if (ok) {
+                }
+                if (ok) {
 #pragma unroll
-                        for (int r = 0; r < 3; ++r) ng[r] = d[r] - nxp[r];
-                        const float r2 = FS_FMA(ng[2], ng[2], FS_FMA(ng[1], ng[1], ng[0] * ng[0]));
-                        const bool conv = r2 < S.tol2;
-                        if (conv || !(r2 < S.div2) || 0 >= S.max_iters) {
-                            write_record<WITH_J>(rec, pair, nx, nJ, conv ? 1 : 0);
-                            if (WITH_J && cell_count && conv) {
-                                want_slot = true;
-                                slot_cell = np * ncell + cell_linear(G, c0);
-                            }
-                        } else {
-                            keep = true;
-#pragma unroll
-                            for (int r = 0; r < 3; ++r)
-                                ndx[r] = -FS_FMA(nJ[r * 3 + 2], ng[2], FS_FMA(nJ[r * 3 + 1], ng[1], nJ[r * 3] * ng[0]));
+                    for (int r = 0; r < 3; ++r) ng[r] = d[r] - nxp[r];
+                    const float r2 = FS_FMA(ng[2], ng[2], FS_FMA(ng[1], ng[1], ng[0] * ng[0]));
+                    const bool conv = r2 < S.tol2;
+                    if (conv || !(r2 < S.div2) || 0 >= S.max_iters) {
+                        write_record<WITH_J>(rec, pair, nx, nJ, conv ? 1 : 0);
+                        if (WITH_J && cell_count && conv) {
+                            want_slot = true;
+                            slot_cell = np * ncell + c0lin;
                         }
+                    } else {
+                        keep = true;
+#pragma unroll
+                        for (int r = 0; r < 3; ++r)
+                            ndx[r] = -FS_FMA(nJ[r * 3 + 2], ng[2], FS_FMA(nJ[r * 3 + 1], ng[1], nJ[r * 3] * ng[0]));
                     }
                 }
                 if (!ok && !norec) write_record<WITH_J>(rec, pair, nx, nJ, 0);
@@ -1169,10 +1229,10 @@ __global__ __launch_bounds__(64 * (NCONS + 1), SKIP ? 2 : 3) void k_solve_ws(Gri
                 for (int c = 0; c < NCONS; ++c) if (c == best) tails[c] = tl;
                 if (lane == 0) lds_store_release(&s_tail[best], tl);
             }
-            if (WITH_J && cell_count) park_slots(want_slot, slot_cell, pair, s_pend[wib], npend, lane, cell_count, slot_out);
+            if (WITH_J && cell_count) park_slots(want_slot, slot_cell, pair, s_pend[wib], npend, lane, cell_count, rec);
         }
         if (lost && lane == 0) *give_up = 1;
-        if (WITH_J && cell_count && npend > 0) flush_slots(s_pend[wib], npend, lane, cell_count, slot_out);
+        if (WITH_J && cell_count && npend > 0) flush_slots(s_pend[wib], npend, lane, cell_count, rec);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         if (lane == 0) lds_store_release(&s_done, 1);
         return;
@@ -1314,9 +1374,9 @@ __global__ __launch_bounds__(64 * (NCONS + 1), SKIP ? 2 : 3) void k_solve_ws(Gri
             }
         }
         if (WITH_J && cell_count)
-            park_slots(want_slot, slot_cell, (int)((long long)k * N + n), s_pend[wib], npend, lane, cell_count, slot_out);
+            park_slots(want_slot, slot_cell, (int)((long long)k * N + n), s_pend[wib], npend, lane, cell_count, rec);
     }
-    if (WITH_J && cell_count && npend > 0) flush_slots(s_pend[wib], npend, lane, cell_count, slot_out);
+    if (WITH_J && cell_count && npend > 0) flush_slots(s_pend[wib], npend, lane, cell_count, rec);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1328,12 +1388,13 @@ __global__ __launch_bounds__(64 * (NCONS + 1), SKIP ? 2 : 3) void k_solve_ws(Gri
 // cell of x* (pass 1 below, or the positions k_solve hands out), crowded cells are summed once per
 // corner (k_grad_pieces), and every grid node then adds what its 8 adjacent cells hold (k_grad_nodes_p).
 
-__global__ void k_fill_zero_i32(long long n, int *__restrict__ a, unsigned *__restrict__ also_set = nullptr,
+// a[0..n) = 0; `cursors` (may be null): the solve kernels' work cursor is reset on the way (as k_reset_cursor does)
+__global__ void k_fill_zero_i32(long long n, int *__restrict__ a, unsigned *__restrict__ cursors = nullptr,
                                 unsigned value = 0u)
 {
     long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     const long long stride = (long long)gridDim.x * blockDim.x;
-    if (also_set && i == 0) *also_set = value;
+    if (cursors && i == 0) cursors[CUR_ALL] = value;
     for (; i < n; i += stride) a[i] = 0;
 }
 
@@ -1362,7 +1423,7 @@ __global__ __launch_bounds__(256) void k_grad_count(GridP G, const float *__rest
 constexpr int GREC = 8;           // floats per record
 // FROM_REC: roots, masks, J~ and positions are taken from the result records the last solve left in the
 // context (one contiguous 64-byte record per pair) instead of the caller's arrays; when that solve drew its
-// pairs from the candidate list, only the first cand_offs[n+1] - cand_offs[n] lanes of point n have a record.
+// pairs from the candidate list, only the first cand_cnt[n] lanes of point n have a record.
 template <bool FROM_REC>
 __global__ __launch_bounds__(256) void k_grad_records(GridP G, int mode, const float *__restrict__ T,
                                                       const float *__restrict__ xc, const float *__restrict__ Jinv,
@@ -1370,7 +1431,7 @@ __global__ __launch_bounds__(256) void k_grad_records(GridP G, int mode, const f
                                                       const int32_t *__restrict__ pose, long long N, int K, int ncell,
                                                       const int *__restrict__ offset, const int *__restrict__ pos,
                                                       float4 *__restrict__ rec, float *__restrict__ gxq, int groups,
-                                                      const float4 *__restrict__ srec, const int *__restrict__ cand_offs)
+                                                      const float4 *__restrict__ srec, const uint8_t *__restrict__ cand_cnt)
 {
     // `groups` (a power of two <= 8) threads share a point and take its lanes k = g, g + groups, ...;
     // consecutive threads of a group are consecutive points, so every load is coalesced
@@ -1381,7 +1442,7 @@ __global__ __launch_bounds__(256) void k_grad_records(GridP G, int mode, const f
     float gq[3] = {0.0f, 0.0f, 0.0f};
     if (n < N) {
         const int p = pose_of(pose, n, G.P);
-        const int nk = (FROM_REC && cand_offs) ? min(K, cand_offs[n + 1] - cand_offs[n]) : K;
+        const int nk = (FROM_REC && cand_cnt) ? min(K, (int)cand_cnt[n]) : K;
         for (int k = g; k < nk; k += groups) {
             const long long q = (long long)k * N + n;
             float x[3], gx[3], M[9];
@@ -1390,11 +1451,8 @@ __global__ __launch_bounds__(256) void k_grad_records(GridP G, int mode, const f
                 const float4 a = srec[q * 4];
                 if (!(__float_as_int(a.w) & 1)) continue;
                 x[0] = a.x; x[1] = a.y; x[2] = a.z;
-                pq = pos[q];
-                if (mode == 0) {
-                    const float4 b = srec[q * 4 + 1], c = srec[q * 4 + 2], d = srec[q * 4 + 3];
-                    M[0] = b.x; M[1] = b.y; M[2] = b.z; M[3] = b.w; M[4] = c.x; M[5] = c.y; M[6] = c.z; M[7] = c.w; M[8] = d.x;
-                }
+                pq = __float_as_int(srec[q * 4 + 1].x);      // the position the solve kernel left in the record
+                if (mode == 0) read_record_J(srec + q * 4, M);
             } else {
                 if (!conv[q]) continue;
 #pragma unroll

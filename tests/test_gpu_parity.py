@@ -77,6 +77,7 @@ def test_precompute_init_solve_parity(lib, case):
 
 
 DET_FLOOR = 1e-2      # exact-J mode vs float64: lanes whose |det dd/dx(x*)| is below this are left out (see the test)
+FACE_BAND = 1e-4      # ... and lanes whose root lies this close (in cell widths) to a cell face
 
 
 @pytest.mark.parametrize("mode", [binding.FS_GRAD_BROYDEN_J, binding.FS_GRAD_EXACT_J])
@@ -103,13 +104,14 @@ def test_grad_parity(lib, case, mode):
             for name, a, b in zip(("gW", "gB", "gxq"), got, ref):
                 gu.assert_grad_close(name, a, b, f"{label} call {rep} vs f64")
         return
-    # Exact-J mode inverts the analytic Jacobian at x* in fp32: the relative error of lambda is about cond(J) 2^-24, and a
-    # few lanes have |det J| ~ 1e-4 and gradient entries ~1e4, so on those fp32 and float64 legitimately disagree (the
-    # strict-fp32 oracle itself is 4e-3 from float64 on config 2).  (i) All lanes: the GPU is held, element by element,
-    # to the strict-fp32 oracle, whose lambda it reproduces operation by operation (only the order of the sums
-    # differs).  (ii) Lanes with |det J(x*)| >= DET_FLOOR (float64 Jacobian; |J|_F is 1.7 ... 3 on these scenes, so
-    # cond(J) <= |J|^3 / |det| ~ 1e3 and lambda is good to ~1e-4 relative): the GPU against float64, element by element,
-    # with the bar widened by that factor.
+    # Exact-J mode inverts the analytic Jacobian at x* in fp32.  (i) All lanes: the GPU is held, element by element, to
+    # the strict-fp32 oracle, whose lambda it reproduces operation by operation (only the order of the sums differs).
+    # (ii) Against float64, two kinds of lanes legitimately disagree and are left out: lanes whose root lies within
+    # FACE_BAND cell widths of a cell face or of the box (the Jacobian of a tri-linear field jumps across cell faces,
+    # the clamped field's across the box faces, and fp32 and float64 round the cell coordinate to different sides), and lanes with |det J(x*)| < DET_FLOOR (the weight-derivative
+    # part of J is a difference of corner images times 1/h: about 8 * 2^-24 * |d| / h ~ 1e-5 absolute in fp32, which
+    # the inverse amplifies by cond(J) <= |J|^2 / |det| ~ 1e3 at the floor).  What remains is compared element by
+    # element with the bar widened to 1e-3 (observed with the CPU oracles alone, fp32 against float64: <= 4.6e-4 of max|b|).
     ref32 = oracle.grad(w.dims, w.lo, w.hi, T_ref, w.W, w.B, xc, Jo, cv, gxc, pose=pose, mode=mode, prec="f32")
     got = run.grad(xc, None, cv, gxc)
     for name, a, b in zip(("gW", "gB", "gxq"), got, ref32):
@@ -119,13 +121,17 @@ def test_grad_parity(lib, case, mode):
     for k in range(w.K):
         _, J = oracle.forward(w.dims, w.lo, w.hi, T64, np.nan_to_num(xc[k].astype(np.float64)), pose=pose, jac=True, prec="f64")
         det[k] = np.linalg.det(np.moveaxis(J.reshape(3, 3, -1), 2, 0))
-    cv_ok = (cv.astype(bool) & (np.abs(det) >= DET_FLOOR)).astype(np.uint8)
-    print(f"{label}: {int(cv.sum() - cv_ok.sum())} of {int(cv.sum())} converged lanes below the determinant floor")
-    assert cv_ok.sum() > 0.9 * cv.sum()
+    lo, hi, nn = (np.asarray(v, np.float64) for v in (w.lo, w.hi, w.dims))
+    u = (np.nan_to_num(xc.astype(np.float64)) - lo[None, :, None]) * ((nn - 1) / (hi - lo))[None, :, None]
+    near_face = ((u > -FACE_BAND) & (u < (nn - 1)[None, :, None] + FACE_BAND) & (np.abs(u - np.round(u)) < FACE_BAND)).any(axis=1)
+    cv_ok = (cv.astype(bool) & (np.abs(det) >= DET_FLOOR) & ~near_face).astype(np.uint8)
+    print(f"{label}: {int(cv.sum() - cv_ok.sum())} of {int(cv.sum())} converged lanes left out "
+          f"(|det| < {DET_FLOOR} or within {FACE_BAND} cell widths of a face)")
+    assert cv_ok.sum() > 0.99 * cv.sum()
     ref64 = oracle.grad(w.dims, w.lo, w.hi, T_ref, w.W, w.B, xc, Jo, cv_ok, gxc, pose=pose, mode=mode, prec="f64")
     got = run.grad(xc, None, cv_ok, gxc)
     for name, a, b in zip(("gW", "gB", "gxq"), got, ref64):
-        gu.assert_grad_close(name, a, b, f"{label} vs f64, well-conditioned lanes", atol_of_max=2e-4, rtol=2e-4)
+        gu.assert_grad_close(name, a, b, f"{label} vs f64, well-posed lanes", atol_of_max=1e-3, rtol=1e-3)
 
 
 @pytest.mark.parametrize("case", [(2, 5003, (32, 32, 8), None), (3, 16 * 255, (32, 32, 8), None), (5, 8 * 1003, (32, 32, 16), 8),
