@@ -180,6 +180,17 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
 fs_status fs_dedupe(fs_ctx *ctx, const float *d_xc, const uint8_t *d_conv, int64_t N, int32_t K, float min_dist,
                     uint8_t *d_keep, int32_t *d_offsets, float *d_roots, int32_t *d_lane, int64_t cap);
 
+/* fs_dedupe for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same results (bit for bit) as fs_dedupe.  The partial sums of
+ * its prefix scan live in a fixed 16 KiB device array inside the library (one copy per GPU, held until the process
+ * ends) instead of a context buffer that grows on demand, so this call never allocates, frees or synchronises.
+ * Limit: N <= 16,777,216 points (4096 scan tiles of 4096); larger N returns FS_E_SHAPE and touches nothing.
+ * The context's device must be the current device.  All calls on one GPU share that array, whatever their context
+ * or stream: calls that overlap on one GPU race; calls on one stream, or otherwise ordered, do not (every call
+ * overwrites what it reads before reading it, nothing is carried over from the call before). */
+fs_status fs_dedupe_noalloc(fs_ctx *ctx, const float *d_xc, const uint8_t *d_conv, int64_t N, int32_t K, float min_dist,
+                            uint8_t *d_keep, int32_t *d_offsets, float *d_roots, int32_t *d_lane, int64_t cap);
+
 /* Copy library-owned state out for inspection (device to device, on the stream).
  *   fs_get_transforms: d_T [n_poses][V][12], the pre-computed grid in node order.
  *   fs_get_corr: d_bbox [n_poses][6] (lo xyz, hi xyz), d_cand [n_poses][ncell][corr_k] node index

@@ -21,7 +21,7 @@ FS_INIT_BONE, FS_INIT_VOXEL = 0, 1
 FS_GRAD_BROYDEN_J, FS_GRAD_EXACT_J = 0, 1
 
 EXPORTS = ["fs_create", "fs_destroy", "fs_set_params", "fs_set_tuning", "fs_set_spin_limit", "fs_precompute", "fs_init", "fs_solve", "fs_grad",
-           "fs_dedupe", "fs_get_transforms", "fs_get_corr", "fs_microbench", "fs_set_timing", "fs_get_timing", "fs_last_error",
+           "fs_dedupe", "fs_dedupe_noalloc", "fs_get_transforms", "fs_get_corr", "fs_microbench", "fs_set_timing", "fs_get_timing", "fs_last_error",
            "fs_version"]
 
 
@@ -76,6 +76,7 @@ def load():
     L.fs_set_timing.argtypes = [vp, i32]
     L.fs_get_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
     L.fs_dedupe.argtypes = [vp, vp, vp, i64, i32, ctypes.c_float, vp, vp, vp, vp, i64]
+    L.fs_dedupe_noalloc.argtypes = L.fs_dedupe.argtypes
     for name in EXPORTS:
         if name not in ("fs_last_error", "fs_version"):
             getattr(L, name).restype = ctypes.c_int
@@ -169,6 +170,10 @@ class Context:
     def dedupe(self, xc, conv, N, K, min_dist, keep, offsets, roots=None, lane=None, cap=0, check=True):
         return self._ret(self._L.fs_dedupe(self._h, _ptr(xc), _ptr(conv), N, K, float(min_dist), _ptr(keep),
                                            _ptr(offsets), _ptr(roots), _ptr(lane), cap), check)
+
+    def dedupe_noalloc(self, xc, conv, N, K, min_dist, keep, offsets, roots=None, lane=None, cap=0, check=True):
+        return self._ret(self._L.fs_dedupe_noalloc(self._h, _ptr(xc), _ptr(conv), N, K, float(min_dist), _ptr(keep),
+                                                   _ptr(offsets), _ptr(roots), _ptr(lane), cap), check)
 
     def set_timing(self, enable=True, check=True):
         return self._ret(self._L.fs_set_timing(self._h, int(bool(enable))), check)

@@ -10,6 +10,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <utility>
 #include <vector>
@@ -72,6 +73,9 @@ struct fs_ctx {
     const void *ptr_seen[128];
     char err[256];
 };
+
+constexpr int FS_NOALLOC_TILES = 4096;
+static __device__ __align__(256) int scratch[FS_NOALLOC_TILES + 64];     // see scratch_on_device()
 
 namespace {
 
@@ -194,6 +198,37 @@ fs_status scan_exclusive(fs_ctx *c, int n, int *a, const int *src = nullptr, int
         k_scan_tiles<true><<<m, 1024, 0, c->stream>>>(n, src ? src : a, a, c->scan_sums, m, nullptr);
     }
     return FS_OK;
+}
+
+// ---- scratch memory of fs_dedupe_noalloc: a file-scope device array instead of a context-owned allocation ----
+// The prefix scan over the per-point counts of kept roots needs one partial sum per tile of SCAN_TILE points.
+// FS_NOALLOC_MAX_N points = FS_NOALLOC_TILES tiles; every GPU the library runs on holds its own 16 KiB copy of the
+// array until the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress: the
+// device address is looked up once per device (with that device current) and kept in g_scratch_ptr.
+constexpr long long FS_NOALLOC_MAX_N = (long long)FS_NOALLOC_TILES * SCAN_TILE;     // 2^24 points
+constexpr int FS_MAX_DEVICES = 64;
+int *g_scratch_ptr[FS_MAX_DEVICES];       // device address of `scratch` on device i, nullptr until looked up
+std::mutex g_scratch_mutex;
+
+// address of `scratch` on the context's device (which must be the current one); nullptr on failure
+int *scratch_on_device(fs_ctx *c)
+{
+    if (c->device < 0 || c->device >= FS_MAX_DEVICES) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[c->device]) {
+        int cur = -1;
+        if (hipGetDevice(&cur) != hipSuccess || cur != c->device) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_scratch_ptr[c->device] = static_cast<int *>(p);
+    }
+    return g_scratch_ptr[c->device];
 }
 
 constexpr size_t FS_LDS_GRID_MAX = 64 * 1024;   // largest transform grid (all poses) kept in LDS by the solve
@@ -667,12 +702,17 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
     return launch_status(ctx, "fs_grad");
 }
 
-static fs_status dedupe_impl(fs_ctx *ctx, const char *who, const float *d_xc, const uint8_t *d_conv, int64_t N,
+// shared body of fs_dedupe and fs_dedupe_noalloc: `sums` = nullptr: the tile sums of the scan live in the context's
+// buffer, which grows on demand; otherwise they live in `sums` (room for FS_NOALLOC_TILES) and nothing is allocated
+static fs_status dedupe_impl(fs_ctx *ctx, const char *who, int *sums, const float *d_xc, const uint8_t *d_conv, int64_t N,
                              int32_t K, float min_dist, uint8_t *d_keep, int32_t *d_offsets, float *d_roots, int32_t *d_lane,
                              int64_t cap)
 {
     if (K < 1 || K > FS_MAX_BONES) return fail(ctx, FS_E_SHAPE, "%s: K must be in 1..%d", who, (int)FS_MAX_BONES);
     if (N < 0 || (long long)N * K >= (1ll << 31)) return fail(ctx, FS_E_SHAPE, "%s: need 0 <= N and K*N < 2^31", who);
+    if (sums && N > FS_NOALLOC_MAX_N)
+        return fail(ctx, FS_E_SHAPE, "%s: N = %lld exceeds the %lld points its fixed scratch memory is sized for; use fs_dedupe",
+                    who, (long long)N, FS_NOALLOC_MAX_N);
     if (!(min_dist >= 0.0f) || !std::isfinite(min_dist)) return fail(ctx, FS_E_ARG, "%s: min_dist must be finite and >= 0", who);
     if (cap < 0) return fail(ctx, FS_E_SHAPE, "%s: cap must be >= 0", who);
     FS_CHECK_PTR(ctx, d_offsets, false);
@@ -685,7 +725,20 @@ static fs_status dedupe_impl(fs_ctx *ctx, const char *who, const float *d_xc, co
         FS_CHECK_PTR(ctx, d_keep, false);
         k_dedupe<<<grid1d(N, 256), 256, 0, st>>>(N, K, min_dist * min_dist, d_xc, d_conv, d_keep, d_offsets);
     }
-    { fs_status ss = scan_exclusive(ctx, (int)N, d_offsets); if (ss != FS_OK) return ss; }
+    if (sums) {
+        // at most FS_NOALLOC_TILES tiles: every block of the second pass adds up the tile sums before its own, all
+        // of which the first pass has just written (nothing of an earlier call is read)
+        if (N > 0) {
+            const int m = (int)((N + SCAN_TILE - 1) / SCAN_TILE);
+            k_scan_tile_sums<<<m, 1024, 0, st>>>((int)N, d_offsets, sums);
+            k_scan_tiles<false><<<m, 1024, 0, st>>>((int)N, d_offsets, d_offsets, sums, m, nullptr);
+        } else {
+            k_fill_zero_i32<<<1, 64, 0, st>>>(1, d_offsets, nullptr);
+        }
+    } else {
+        fs_status ss = scan_exclusive(ctx, (int)N, d_offsets);
+        if (ss != FS_OK) return ss;
+    }
     if (N > 0 && (d_roots || d_lane))
         k_pack_roots<<<grid1d(N, 256), 256, 0, st>>>(N, K, cap, d_xc, d_keep, d_offsets, d_roots, d_lane);
     return launch_status(ctx, who);
@@ -696,7 +749,18 @@ fs_status fs_dedupe(fs_ctx *ctx, const float *d_xc, const uint8_t *d_conv, int64
 {
     if (!ctx) return FS_E_ARG;
     { fs_status gs = check_gave_up(ctx, "fs_dedupe"); if (gs != FS_OK) return gs; }
-    return dedupe_impl(ctx, "fs_dedupe", d_xc, d_conv, N, K, min_dist, d_keep, d_offsets, d_roots, d_lane, cap);
+    return dedupe_impl(ctx, "fs_dedupe", nullptr, d_xc, d_conv, N, K, min_dist, d_keep, d_offsets, d_roots, d_lane, cap);
+}
+
+fs_status fs_dedupe_noalloc(fs_ctx *ctx, const float *d_xc, const uint8_t *d_conv, int64_t N, int32_t K, float min_dist,
+                            uint8_t *d_keep, int32_t *d_offsets, float *d_roots, int32_t *d_lane, int64_t cap)
+{
+    if (!ctx) return FS_E_ARG;
+    { fs_status gs = check_gave_up(ctx, "fs_dedupe_noalloc"); if (gs != FS_OK) return gs; }
+    int *sums = scratch_on_device(ctx);
+    if (!sums) return fail(ctx, FS_E_DEVICE, "fs_dedupe_noalloc: the address of the library's scratch array could not be obtained "
+                                             "(the context's device must be the current one)");
+    return dedupe_impl(ctx, "fs_dedupe_noalloc", sums, d_xc, d_conv, N, K, min_dist, d_keep, d_offsets, d_roots, d_lane, cap);
 }
 
 fs_status fs_set_timing(fs_ctx *ctx, int32_t enable)
