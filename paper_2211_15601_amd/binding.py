@@ -20,7 +20,7 @@ STATUS_NAMES = ["FS_OK", "FS_E_ARG", "FS_E_SHAPE", "FS_E_STATE", "FS_E_ALLOC", "
 FS_INIT_BONE, FS_INIT_VOXEL = 0, 1
 FS_GRAD_BROYDEN_J, FS_GRAD_EXACT_J = 0, 1
 
-EXPORTS = ["fs_create", "fs_destroy", "fs_set_params", "fs_set_tuning", "fs_set_spin_limit", "fs_precompute", "fs_init", "fs_solve", "fs_grad",
+EXPORTS = ["fs_create", "fs_destroy", "fs_set_params", "fs_set_tuning", "fs_set_list_order", "fs_set_spin_limit", "fs_precompute", "fs_init", "fs_solve", "fs_grad",
            "fs_dedupe", "fs_dedupe_noalloc", "fs_get_transforms", "fs_get_corr", "fs_microbench", "fs_set_timing", "fs_get_timing", "fs_last_error",
            "fs_version"]
 
@@ -72,6 +72,7 @@ def load():
     L.fs_version.restype = ctypes.c_char_p
     L.fs_set_tuning.argtypes = [vp, i32, i32, i32, i32, i32]
     L.fs_set_spin_limit.argtypes = [vp, i32]
+    L.fs_set_list_order.argtypes = [vp, i32]
     L.fs_microbench.argtypes = [i32, i64, ctypes.POINTER(ctypes.c_double)]
     L.fs_set_timing.argtypes = [vp, i32]
     L.fs_get_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
@@ -147,6 +148,9 @@ class Context:
     def set_tuning(self, chunk=0, refill_min=0, blocks_per_cu=0, point_major=-1, lds_grid=-1, check=True):
         return self._ret(self._L.fs_set_tuning(self._h, int(chunk), int(refill_min), int(blocks_per_cu),
                                                int(point_major), int(lds_grid)), check)
+
+    def set_list_order(self, by_place, check=True):
+        return self._ret(self._L.fs_set_list_order(self._h, int(by_place)), check)
 
     def set_spin_limit(self, polls, check=True):
         return self._ret(self._L.fs_set_spin_limit(self._h, int(polls)), check)

@@ -60,8 +60,11 @@ struct fs_ctx {
     int *vgcell;       // [N] pose * ncell + correspondence cell of every point
     int2 *vlist;       // [K*N] pairs that have a candidate: {point, cell << 3 | k}
     size_t vcap;       // points voffs / vcnt / vgcell / vlist can hold
+    int *vhist;        // [buckets][blocks] + 1: counts, then places, of the counting sort that orders the list by place
+    size_t vhist_cap;
     int scan_cap;      // tiles scan_sums can hold
     int n_cus, occ_blocks_per_cu, occ_ws_blocks_per_cu, occ_vx_blocks_per_cu, chunk, refill_min, blocks_per_cu, point_major, lds_grid;
+    int sort_list;     // order the list of (point, candidate) pairs by place (large voxel-mode batches)
     int spin_limit;    // polls for room in its consumers' queues before the producer wave of a solve block gives up
     int pre_serial;    // number of the last fs_precompute; cursor[CUR_NONFINITE] == pre_serial: that grid has an entry that is not finite
     int *gave_up;      // pinned host word, mapped into the device: a wave that gave up sets it
@@ -169,7 +172,7 @@ int grid1d(long long n, int block) { return (int)((n + block - 1) / block); }
 void free_all(fs_ctx *c)
 {
     void *ptrs[] = {c->T, c->Bdev, c->Binv, c->Bok, c->GT, c->Y, c->bb_ord, c->bbox,
-                    c->cell_of, c->count, c->fill, c->order, c->cand, c->cursor, c->gcount, c->gcount_solve, c->gpos, c->grec, c->scan_sums, c->srec, c->gpart, c->voffs, c->vlist, c->cinit, c->vcnt, c->vgcell};
+                    c->cell_of, c->count, c->fill, c->order, c->cand, c->cursor, c->gcount, c->gcount_solve, c->gpos, c->grec, c->scan_sums, c->srec, c->gpart, c->voffs, c->vlist, c->cinit, c->vcnt, c->vgcell, c->vhist};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
 }
@@ -231,7 +234,12 @@ int *scratch_on_device(fs_ctx *c)
     return g_scratch_ptr[c->device];
 }
 
-constexpr size_t FS_LDS_GRID_MAX = 64 * 1024;   // largest transform grid (all poses) kept in LDS by the solve
+#ifndef FS_TPN8_AT
+#define FS_TPN8_AT 8
+#endif
+// largest transform grid (all poses) kept in LDS by the solve: a block may ask for 64 KiB in all, and k_solve has 4 KiB of
+// its own (the parked cell-position requests of its four waves)
+constexpr size_t FS_LDS_GRID_MAX = 60 * 1024;
 
 int lanes_K(const fs_ctx *c) { return c->prm.init_mode == FS_INIT_BONE ? c->desc.n_bones : c->prm.corr_k; }
 
@@ -296,7 +304,9 @@ fs_status fs_create(const fs_grid_desc *desc, const fs_params *params, void *hip
     {
         int per_cu = 0, cus = 0;
         int per_cu_ws = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_solve<true, true>, 256, 0) != hipSuccess || per_cu < 1) per_cu = 2;
+        // resident blocks of the LDS-grid kernel with the LDS this context's grid needs (the grid's size never changes)
+        const size_t gb = (size_t)desc->n_poses * V * 48;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_solve<true, true>, 256, gb <= FS_LDS_GRID_MAX ? gb : 0) != hipSuccess || per_cu < 1) per_cu = 1;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_ws, k_solve_ws<true, true, FS_WS_CONSUMERS, false>, 64 * (FS_WS_CONSUMERS + 1), 0) != hipSuccess || per_cu_ws < 1) per_cu_ws = 2;
         c->occ_ws_blocks_per_cu = per_cu_ws;
         int per_cu_vx = 0;
@@ -305,7 +315,8 @@ fs_status fs_create(const fs_grid_desc *desc, const fs_params *params, void *hip
         c->spin_limit = 1 << 22;   /* x about 0.2 us per poll */
         c->blocks_per_cu = 0;      /* 0: chosen per call */
         c->point_major = 1;
-        c->lds_grid = 1;   /* the kernel is bound by the vector-memory path: more waves only thrash the L1 */
+        c->lds_grid = 1;
+        c->sort_list = 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
         (void)hipGetLastError();
         c->n_cus = cus;
@@ -384,6 +395,14 @@ fs_status fs_set_tuning(fs_ctx *ctx, int32_t chunk, int32_t refill_min, int32_t 
     return FS_OK;
 }
 
+fs_status fs_set_list_order(fs_ctx *ctx, int32_t by_place)
+{
+    if (!ctx) return FS_E_ARG;
+    if (by_place != 0 && by_place != 1) return fail(ctx, FS_E_ARG, "fs_set_list_order: by_place must be 0 or 1");
+    ctx->sort_list = by_place;
+    return FS_OK;
+}
+
 fs_status fs_set_spin_limit(fs_ctx *ctx, int32_t polls)
 {
     if (!ctx) return FS_E_ARG;
@@ -401,14 +420,19 @@ fs_status fs_precompute(fs_ctx *ctx, const float *d_W, const float *d_B)
     const GridP &G = ctx->G;
     hipStream_t st = ctx->stream;
     ++ctx->pre_serial;
+    const bool voxel = ctx->prm.init_mode == FS_INIT_VOXEL;
+    if (voxel) {
+        const int ncp0 = G.P * ctx->C.ncell;
+        k_corr_reset<<<grid1d(ncp0 > G.P * 3 ? ncp0 : G.P * 3, 256), 256, 0, st>>>(G.P, ctx->C.ncell, ctx->bb_ord, ctx->count);
+    }
     k_precompute<<<grid1d(G.V, 256), 256, 0, st>>>(G, d_W, d_B, ctx->T, ctx->Bdev, ctx->Binv, ctx->Bok,
-                                                   reinterpret_cast<int *>(ctx->cursor + CUR_NONFINITE), ctx->pre_serial);
-    if (ctx->prm.init_mode == FS_INIT_VOXEL) {
+                                                   reinterpret_cast<int *>(ctx->cursor + CUR_NONFINITE), ctx->pre_serial,
+                                                   voxel ? ctx->Y : nullptr);
+    if (voxel) {
         const CorrP &C = ctx->C;
         const int ncp = G.P * C.ncell;
-        k_corr_reset<<<grid1d(ncp > G.P * 3 ? ncp : G.P * 3, 256), 256, 0, st>>>(G.P, C.ncell, ctx->bb_ord, ctx->count);
         const dim3 gv(grid1d(G.V, 256), G.P);
-        k_corr_warp<<<dim3(std::min(grid1d(G.V, 256), 256), G.P), 256, 0, st>>>(G, ctx->T, ctx->Y, ctx->bb_ord);
+        k_corr_extent<<<dim3(std::min(grid1d(G.V, 256), 256), G.P), 256, 0, st>>>(G, ctx->Y, ctx->bb_ord);
         k_corr_bbox<<<1, 64 * ((G.P * 6 + 63) / 64), 0, st>>>(G.P, ctx->bb_ord, ctx->bbox);
         k_corr_count<<<gv, 256, 0, st>>>(G, C, ctx->Y, ctx->bbox, ctx->cell_of, ctx->count, ctx->fill);
         { fs_status ss = scan_exclusive(ctx, ncp, ctx->count); if (ss != FS_OK) return ss; }
@@ -535,10 +559,32 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
             ctx->vcap = (size_t)N;
         }
         k_voxel_count<<<grid1d(N, 256), 256, 0, st>>>(ctx->G, I, N, d_xq, d_pose, ctx->voffs, ctx->vcnt, ctx->vgcell);
-        { fs_status ss = scan_exclusive(ctx, (int)N, ctx->voffs); if (ss != FS_OK) return ss; }
-        k_voxel_expand<<<grid1d(N, 256), 256, 0, st>>>(N, ctx->voffs, ctx->vgcell, ctx->vlist);
+        // On request (fs_set_list_order) large batches are ordered by place (pose, then column of correspondence cells)
+        // with a counting sort; small ones, or correspondence grids with more columns than the sort's LDS counters hold,
+        // keep the order of the points.
+        const int nb = ctx->G.P * ctx->C.cx * ctx->C.cy;
+        const long long sblk = (N + SORT_TILE - 1) / SORT_TILE;
+        const bool sorted = ctx->sort_list && N >= 4 * SORT_TILE && nb <= SORT_MAX_BUCKETS && (long long)nb * sblk < (1ll << 24);
+        if (sorted) {
+            const size_t need_h = (size_t)nb * sblk + 1;
+            if (need_h > ctx->vhist_cap) {
+                (void)hipStreamSynchronize(st);
+                if (ctx->vhist) (void)hipFree(ctx->vhist);
+                ctx->vhist = nullptr;
+                ctx->vhist_cap = 0;
+                if (!dev_alloc(&ctx->vhist, need_h)) return fail(ctx, FS_E_ALLOC, "fs_solve: out of device memory for the pair list");
+                ctx->vhist_cap = need_h;
+            }
+            k_sort_hist<<<(unsigned)sblk, 1024, nb * sizeof(int), st>>>(N, ctx->C.cz, nb, ctx->vgcell, ctx->vcnt, ctx->vhist);
+            { fs_status ss = scan_exclusive(ctx, (int)((long long)nb * sblk), ctx->vhist); if (ss != FS_OK) return ss; }
+            k_sort_scatter<<<(unsigned)sblk, 1024, nb * sizeof(int), st>>>(N, ctx->C.cz, nb, ctx->vgcell, ctx->vcnt, ctx->vhist, ctx->vlist);
+            list_len = ctx->vhist + (long long)nb * sblk;
+        } else {
+            { fs_status ss = scan_exclusive(ctx, (int)N, ctx->voffs); if (ss != FS_OK) return ss; }
+            k_voxel_expand<<<grid1d(N, 256), 256, 0, st>>>(N, ctx->voffs, ctx->vgcell, ctx->vlist);
+            list_len = ctx->voffs + N;
+        }
         list = ctx->vlist;
-        list_len = ctx->voffs + N;
     }
     const int ncell = (ctx->G.nx - 1) * (ctx->G.ny - 1) * (ctx->G.nz - 1);
     int *cell_count = nullptr;
@@ -685,7 +731,7 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
     if (N > 0) k_grad_pieces<<<grid1d((long long)lanes, PIECE_R), 64 * PIECE_WAVES, 0, st>>>(G, ncp, ctx->gcount, ctx->grec);
     // crowded grids: one thread per (node, adjacent cell); sparse ones: one thread per node
     const long long nodes = (long long)G.P * G.V;
-    if ((long long)lanes >= 8 * nodes)
+    if ((long long)lanes >= FS_TPN8_AT * nodes)
         k_grad_nodes_p<8><<<grid1d(nodes * 8, 256), 256, 0, st>>>(G, ncell, ctx->gcount, ctx->grec, ctx->GT);
     else
         k_grad_nodes_p<1><<<grid1d(nodes, 256), 256, 0, st>>>(G, ncell, ctx->gcount, ctx->grec, ctx->GT);

@@ -186,12 +186,14 @@ __device__ __forceinline__ bool inv3(const float m[9], float o[9])
     return true;
 }
 
-// Canonical position of node v.
-__device__ __forceinline__ void node_pos(const GridP &G, long long v, float x[3])
+// Canonical position of node v (V < 2^28: 32-bit arithmetic; a 64-bit division costs some hundred instructions).
+__device__ __forceinline__ void node_pos(const GridP &G, long long v64, float x[3])
 {
-    const int iz = (int)(v % G.nz);
-    const int iy = (int)((v / G.nz) % G.ny);
-    const int ix = (int)(v / ((long long)G.nz * G.ny));
+    const unsigned v = (unsigned)v64, nz = (unsigned)G.nz, ny = (unsigned)G.ny;
+    const unsigned t = v / nz;
+    const int iz = (int)(v - t * nz);
+    const unsigned ixu = t / ny;
+    const int iy = (int)(t - ixu * ny), ix = (int)ixu;
     x[0] = FS_FMA((float)ix, G.h[0], G.lo[0]);
     x[1] = FS_FMA((float)iy, G.h[1], G.lo[1]);
     x[2] = FS_FMA((float)iz, G.h[2], G.lo[2]);

@@ -24,13 +24,27 @@ constexpr int FS_MAX_CORR_K_DEV = 8;
 __device__ __forceinline__ void bone_inverse(int i, const float *__restrict__ B, float *__restrict__ Bcopy,
                                              float *__restrict__ Binv, uint8_t *__restrict__ ok);
 
+// monotone float <-> uint mapping so that min / max can use integer atomics (exact, order-free)
+__device__ __forceinline__ unsigned f2ord(float f)
+{
+    const unsigned u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float ord2f(unsigned o)
+{
+    return __uint_as_float((o & 0x80000000u) ? (o & 0x7fffffffu) : ~o);
+}
+
 // The first n_poses*n_bones threads also invert their bone's linear part for Eq. (8) and keep a copy
 // of the bone transforms for the backward.
+// Y (may be null; voxel-based initial states): the image y_v = T_v x_v of every node is written as well -- the
+// correspondence grid is built on those, and the transforms are in registers here anyway (a pass of its own would
+// read all of T again).
 __global__ __launch_bounds__(256) void k_precompute(GridP G, const float *__restrict__ W,
                                                     const float *__restrict__ B, float *__restrict__ T,
                                                     float *__restrict__ Bcopy, float *__restrict__ Binv,
                                                     uint8_t *__restrict__ Bok, int *__restrict__ nonfinite,
-                                                    int serial)
+                                                    int serial, float *__restrict__ Y)
 {
     // *nonfinite = serial (the number of this call) tells the solve that this grid holds an entry that is not
     // finite: a record with weight zero may then not be skipped (0 * inf is not 0)
@@ -40,6 +54,8 @@ __global__ __launch_bounds__(256) void k_precompute(GridP G, const float *__rest
     if (v >= G.V) return;
     const float *w = W + v * G.nb;
     const bool vec = (G.nb & 3) == 0;        // weight rows are 16-byte aligned: read them four at a time
+    float xv[3] = {0.0f, 0.0f, 0.0f};
+    if (Y) node_pos(G, v, xv);
     // four poses share one pass over the node's weights; per pose the sum runs over the bones in order,
     // first term a product, the rest fused multiply-adds
     for (int p0 = 0; p0 < G.P; p0 += 4) {
@@ -85,6 +101,12 @@ __global__ __launch_bounds__(256) void k_precompute(GridP G, const float *__rest
                 o[0] = make_float4(acc[q][0], acc[q][1], acc[q][2], acc[q][3]);
                 o[1] = make_float4(acc[q][4], acc[q][5], acc[q][6], acc[q][7]);
                 o[2] = make_float4(acc[q][8], acc[q][9], acc[q][10], acc[q][11]);
+                if (Y) {
+                    float y[3];
+                    apply12(acc[q], xv, y);
+                    float *yo = Y + ((long long)(p0 + q) * G.V + v) * 3;
+                    yo[0] = y[0]; yo[1] = y[1]; yo[2] = y[2];
+                }
             }
         }
     }
@@ -193,17 +215,6 @@ __global__ __launch_bounds__(256) void k_init_voxel(GridP G, CorrP C, const floa
 // ------------------------------------------------------------------------------------------------
 // Correspondence grid build (voxel-based initialisation).
 // ------------------------------------------------------------------------------------------------
-// monotone float <-> uint mapping so that min / max can use integer atomics (exact, order-free)
-__device__ __forceinline__ unsigned f2ord(float f)
-{
-    const unsigned u = __float_as_uint(f);
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-__device__ __forceinline__ float ord2f(unsigned o)
-{
-    return __uint_as_float((o & 0x80000000u) ? (o & 0x7fffffffu) : ~o);
-}
-
 __global__ void k_corr_reset(int P, int ncell, unsigned *__restrict__ bb_ord, int *__restrict__ count)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -212,21 +223,14 @@ __global__ void k_corr_reset(int P, int ncell, unsigned *__restrict__ bb_ord, in
     if (i == 0) count[P * ncell] = 0;
 }
 
-// images of all nodes, y_v = T_v x_v, and their bounding box per pose (grid-stride; one set of
-// atomics per block)
-__global__ __launch_bounds__(256) void k_corr_warp(GridP G, const float *__restrict__ T, float *__restrict__ Y,
-                                                   unsigned *__restrict__ bb_ord)
+// bounding box per pose of the images of all nodes (grid-stride; one set of atomics per block)
+__global__ __launch_bounds__(256) void k_corr_extent(GridP G, const float *__restrict__ Y, unsigned *__restrict__ bb_ord)
 {
     __shared__ unsigned smn[4][3], smx[4][3];
     const int p = blockIdx.y;
     unsigned mn[3] = {0xffffffffu, 0xffffffffu, 0xffffffffu}, mx[3] = {0u, 0u, 0u};
     for (long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x; v < G.V; v += (long long)gridDim.x * blockDim.x) {
-        float x[3], y[3], t[12];
-        node_pos(G, v, x);
-        load12(T + ((long long)p * G.V + v) * 12, t);
-        apply12(t, x, y);
-        float *o = Y + ((long long)p * G.V + v) * 3;
-        o[0] = y[0]; o[1] = y[1]; o[2] = y[2];
+        const float *y = Y + ((long long)p * G.V + v) * 3;
 #pragma unroll
         for (int a = 0; a < 3; ++a) {
             const unsigned ov = f2ord(y[a]);
@@ -237,9 +241,9 @@ __global__ __launch_bounds__(256) void k_corr_warp(GridP G, const float *__restr
 #pragma unroll
     for (int a = 0; a < 3; ++a) {
 #pragma unroll
-        for (int s = 32; s >= 1; s >>= 1) {
-            mn[a] = min(mn[a], (unsigned)__shfl_xor((int)mn[a], s));
-            mx[a] = max(mx[a], (unsigned)__shfl_xor((int)mx[a], s));
+        for (int sft = 32; sft >= 1; sft >>= 1) {
+            mn[a] = min(mn[a], (unsigned)__shfl_xor((int)mn[a], sft));
+            mx[a] = max(mx[a], (unsigned)__shfl_xor((int)mx[a], sft));
         }
     }
     const int wid = threadIdx.x >> 6;
@@ -591,6 +595,50 @@ __global__ __launch_bounds__(256) void k_voxel_expand(long long N, const int *__
     if (n >= N) return;
     const int b = offs[n], e = offs[n + 1], gc = gcell[n];
     for (int j = b; j < e; ++j) list[j] = make_int2((int)n, (gc << 3) | (j - b));
+}
+
+// The list of pairs, ordered by place: all pairs whose query point falls into the same column of correspondence cells
+// (bucket = (pose * ncell + cell) / cz, i.e. the cell index without its fastest coordinate) are made neighbours, so
+// that the lanes at work at any one time -- on every XCD, since all blocks draw from one cursor -- read the same
+// stretch of one pose's transform grid and of the candidate table, and the caches serve what memory served before.
+// A counting sort without global atomics: every block counts the candidates of its tile of SORT_TILE points per
+// bucket in LDS and leaves the counts in hist[bucket][block]; an exclusive scan over that matrix (bucket-major)
+// gives every (bucket, block) the place where its pairs start; the blocks then hand out places within that from LDS
+// counters.  The order inside a bucket is the order in which the lanes of a block arrive: any order is a valid list.
+constexpr int SORT_TILE = 16384;          // points per block
+constexpr int SORT_MAX_BUCKETS = 16384;   // 64 KiB of LDS counters
+
+__global__ __launch_bounds__(1024) void k_sort_hist(long long N, int cz, int nb, const int *__restrict__ gcell,
+                                                    const uint8_t *__restrict__ cnt8, int *__restrict__ hist)
+{
+    extern __shared__ int s_cnt[];
+    for (int i = threadIdx.x; i < nb; i += blockDim.x) s_cnt[i] = 0;
+    __syncthreads();
+    const long long n0 = (long long)blockIdx.x * SORT_TILE, n1 = min(N, n0 + SORT_TILE);
+    for (long long n = n0 + threadIdx.x; n < n1; n += blockDim.x) {
+        const int c = cnt8[n];
+        if (c) atomicAdd(&s_cnt[gcell[n] / cz], c);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < nb; i += blockDim.x) hist[(long long)i * gridDim.x + blockIdx.x] = s_cnt[i];
+}
+
+// list entry of a pair: {point n, (pose * ncell + correspondence cell) << 3 | k}
+__global__ __launch_bounds__(1024) void k_sort_scatter(long long N, int cz, int nb, const int *__restrict__ gcell,
+                                                       const uint8_t *__restrict__ cnt8, const int *__restrict__ start,
+                                                       int2 *__restrict__ list)
+{
+    extern __shared__ int s_cnt[];
+    for (int i = threadIdx.x; i < nb; i += blockDim.x) s_cnt[i] = start[(long long)i * gridDim.x + blockIdx.x];
+    __syncthreads();
+    const long long n0 = (long long)blockIdx.x * SORT_TILE, n1 = min(N, n0 + SORT_TILE);
+    for (long long n = n0 + threadIdx.x; n < n1; n += blockDim.x) {
+        const int c = cnt8[n];
+        if (!c) continue;
+        const int gc = gcell[n];
+        const int at = atomicAdd(&s_cnt[gc / cz], c);
+        for (int k = 0; k < c; ++k) list[at + k] = make_int2((int)n, (gc << 3) | k);
+    }
 }
 
 // records -> caller's layout: one thread per pair q = k*N + n, consecutive threads consecutive n.
@@ -1720,6 +1768,12 @@ __global__ __launch_bounds__(64 * PIECE_WAVES) void k_grad_pieces(GridP G, long 
 
 // G_T of every node from the pieces of its 8 adjacent cells; TPN threads share a node (1, or 8 = one
 // per adjacent cell followed by a butterfly sum).
+// Measured on the multi-pose batch (7.7 M records over 4.2 M nodes, TPN = 1: 450 us) and not adopted: a block per brick
+// of 4 x 4 x 16 nodes that first copies the records of the cells around it into LDS and gathers from there, same loops:
+// 450 .. 518 us (fewer resident threads, three barriers per block); the same with one loop over all records of a node's
+// 8 cells instead of a loop per cell: 751 us (the bookkeeping costs more than the shorter loop saves); a block per brick
+// that adds every record's 8 x 12 contributions into LDS sums with LDS float atomics: 4.5 ms (about 0.5 SIMD lanes per
+// clock and CU).
 template <int TPN>
 __global__ __launch_bounds__(256) void k_grad_nodes_p(GridP G, int ncell, const int *__restrict__ offset,
                                                       const float *__restrict__ rec, float *__restrict__ GT)

@@ -324,14 +324,16 @@ def test_autograd_hook_matches_oracle_gradient(lib):
 
 
 @pytest.mark.parametrize("shape", [((2, 2, 2), 1, 1, 40), ((5, 4, 3), 5, 3, 1000), ((7, 3, 9), 17, 2, 777),
-                                   ((4, 6, 5), 33, 1, 513), ((3, 3, 3), 64, 2, 300), ((9, 8, 7), 3, 4, 20011)],
+                                   ((4, 6, 5), 33, 1, 513), ((3, 3, 3), 64, 2, 300), ((9, 8, 7), 3, 4, 20011),
+                                   ((8, 10, 16), 6, 1, 4099), ((8, 10, 16), 5, 2, 1500)],
                          ids=lambda t: f"g{t[0]}-b{t[1]}-p{t[2]}-n{t[3]}")
 @pytest.mark.parametrize("lds_grid", [1, 0], ids=["grid_in_lds", "grid_cached"])
 def test_odd_shapes_full_path(lib, shape, lds_grid):
     # bone counts on both sides of the 16-bone MFMA tiles and of the 4-wide weight reads, grids down to one cell,
     # several poses, ragged N: transform grid, solve (both solve kernels: the one that holds these small grids
     # in LDS, and the producer / consumer one that reads them through the caches) and both gradient paths
-    # against the oracle
+    # against the oracle.  8 x 10 x 16 nodes x 1 pose = 60 KiB is the largest grid the LDS kernel takes (one block per
+    # CU at that size); with 2 poses it is twice that and goes through the caches whatever lds_grid says
     dims, nb, P, n = shape
     s = wl.random_affine_scene(100 + nb, dims=dims, n_bones=nb, n_poses=P, n_points=n)
     w = wl.Workload("odd", s["dims"], nb, P, s["lo"], s["hi"], s["W"], s["B"], s["x"], s["pose"], s["x"],
@@ -594,3 +596,32 @@ def test_autograd_two_forwards_then_backward(lib, mode):
         ref = oracle.grad(w.dims, w.lo, w.hi, T_ref, w.W, w.B, oxc, oJ, ocv, w.upstream_grads(), mode=mode, prec=prec)
         for name, a, b in zip(("gW", "gB", "gxq"), (Wt.grad, Bt.grad, qt.grad), ref):
             gu.assert_grad_close(name, a.cpu().numpy(), b, f"{w.name} autograd mode {mode}")
+
+
+def test_list_order_does_not_change_results(lib):
+    # voxel-based candidates, fused: on request batches of 65,536 points and more are ordered by place with a counting
+    # sort before the solve; every pair's result must be the same bits as with the list in point order, every lane must be written,
+    # and the backward (cell positions from the solve) must agree with the oracle in both orders
+    w = wl.make_config(5, n_points=4 * 40000, dims=(32, 32, 16), n_poses=4)       # 160,000 points: ten sort tiles, ragged
+    pose = w.pose
+    run = gu.GpuRun(w)
+    T = run.precompute()
+    outs = []
+    for by_place in (1, 0, 1):
+        run.ctx.set_list_order(by_place)
+        xc, cv, Jo, it = run.solve(fused=True, slots=True)
+        outs.append((xc, cv, Jo, it))
+    for o in outs[1:]:
+        for a, b in zip(o, outs[0]):
+            np.testing.assert_array_equal(a.view(np.uint8), b.view(np.uint8))
+    T_ref = oracle.precompute(w.dims, w.W, w.B, prec="f32")
+    x0, J0, v0 = gu.oracle_inits(w, T_ref)
+    ref = gu.oracle_solve(w, T_ref, x0, J0, v0)
+    np.testing.assert_array_equal(outs[0][1], ref[1])
+    np.testing.assert_array_equal(outs[0][3], ref[3])
+    np.testing.assert_array_equal(outs[0][0].view(np.uint32), ref[0].view(np.uint32))
+    gxc = w.upstream_grads()
+    rW, rB, rq = oracle.grad(w.dims, w.lo, w.hi, T_ref, w.W, w.B, ref[0], ref[2], ref[1], gxc, pose=pose, mode=0, prec="f64")
+    gW, gB, gxq = run.grad(outs[0][0], None, outs[0][1], gxc, slot=run.slot)
+    for name, a, b in (("gW", gW, rW), ("gB", gB, rB), ("gxq", gxq, rq)):
+        gu.assert_grad_close(name, a, b, "list ordered by place")
