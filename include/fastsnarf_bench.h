@@ -28,8 +28,11 @@ fs_status fs_get_timing(fs_ctx *ctx, double *solve_kernel_ms, int32_t *launches)
  *                      address inside an array of array_bytes (the tri-linear lookup's access pattern)
  *   FS_MB_GATHER_LINE  same, but 8 adjacent lanes share one aligned 128-byte line
  *   FS_MB_LDS_GATHER   16-byte loads per second, every lane its own random address in 48 KiB of LDS
- * array_bytes is used by the two global gathers only (4 KiB .. 4 GiB). */
-enum { FS_MB_FMA = 0, FS_MB_GATHER_LANE = 1, FS_MB_GATHER_LINE = 2, FS_MB_LDS_GATHER = 3 };
+ *   FS_MB_GATHER_SEGMENT  16-byte loads per second when every lane reads the six pieces of a random pair of adjacent
+ *                      48-byte records with six consecutive instructions: the solve kernel's own pattern (two
+ *                      z-neighbours of the transform grid), so that this is its ceiling for a grid of array_bytes
+ * array_bytes is used by the three global gathers only (4 KiB .. 4 GiB). */
+enum { FS_MB_FMA = 0, FS_MB_GATHER_LANE = 1, FS_MB_GATHER_LINE = 2, FS_MB_LDS_GATHER = 3, FS_MB_GATHER_SEGMENT = 4 };
 fs_status fs_microbench(int32_t which, int64_t array_bytes, double *result);
 
 #ifdef __cplusplus

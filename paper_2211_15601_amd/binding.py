@@ -195,7 +195,7 @@ class Context:
         return self._ret(self._L.fs_get_corr(self._h, _ptr(bbox), _ptr(cand)), check)
 
 
-MB_FMA, MB_GATHER_LANE, MB_GATHER_LINE, MB_LDS_GATHER = range(4)
+MB_FMA, MB_GATHER_LANE, MB_GATHER_LINE, MB_LDS_GATHER, MB_GATHER_SEGMENT = range(5)
 
 
 def microbench(which: int, array_bytes: int = 3 << 20) -> float:

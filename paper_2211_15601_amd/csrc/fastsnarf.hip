@@ -729,12 +729,13 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
                                                      grec4, d_gxq, groups, nullptr, nullptr);
     }
     if (N > 0) k_grad_pieces<<<grid1d((long long)lanes, PIECE_R), 64 * PIECE_WAVES, 0, st>>>(G, ncp, ctx->gcount, ctx->grec);
-    // crowded grids: one thread per (node, adjacent cell); sparse ones: one thread per node
+    // crowded grids: one thread per (node, adjacent cell); sparse ones: one thread per node, which walks the 4 cells at
+    // its height and hands their share for the node above to the next SIMD lane
     const long long nodes = (long long)G.P * G.V;
     if ((long long)lanes >= FS_TPN8_AT * nodes)
         k_grad_nodes_p<8><<<grid1d(nodes * 8, 256), 256, 0, st>>>(G, ncell, ctx->gcount, ctx->grec, ctx->GT);
     else
-        k_grad_nodes_p<1><<<grid1d(nodes, 256), 256, 0, st>>>(G, ncell, ctx->gcount, ctx->grec, ctx->GT);
+        k_grad_nodes_z<<<grid1d(nodes, 256), 256, 0, st>>>(G, ncell, ctx->gcount, ctx->grec, ctx->GT);
     k_grad_weights_node<<<grid1d(G.V * ((G.nb + 7) / 8), 256), 256, sizeof(float) * G.P * G.nb * 12, st>>>(G, ctx->GT, ctx->Bdev, d_gW);
     const int nout = G.nb * 12, nparts = ctx->gb_blocks * 4;
     const dim3 gbg(ctx->gb_blocks, (G.P + GB_POSES - 1) / GB_POSES);

@@ -1827,6 +1827,118 @@ __global__ __launch_bounds__(256) void k_grad_nodes_p(GridP G, int ncell, const 
     }
 }
 
+// What the records of cell (cx, cy, cz), list entries [a, b), add to the two nodes at its (x, y) corner `ab`
+// (= a + 2b): `lo` is the node at cz, `hi` the one at cz + 1.  Pieces that k_grad_pieces replaced by their corner
+// sums enter as those sums.  Either output may be switched off.
+template <bool LO, bool HI>
+__device__ __forceinline__ void grad_cell_pair(const GridP &G, const float *__restrict__ rec, int a, int b, int ab, int cx,
+                                               int cy, int cz, float (&lo)[12], float (&hi)[12])
+{
+    for (int j = a / PIECE_R; j <= (b - 1) / PIECE_R; ++j) {
+        const int ps = max(a, j * PIECE_R), pe = min(b, (j + 1) * PIECE_R);
+        if (pe - ps >= PIECE_MIN) {
+            const float4 *q0 = reinterpret_cast<const float4 *>(rec + (long long)ps * GREC + ab * 12);
+            const float4 *q1 = q0 + 12;                   // corner ab + 4
+#pragma unroll
+            for (int h = 0; h < 3; ++h) {
+                if (LO) {
+                    const float4 u = q0[h];
+                    lo[4 * h] += u.x; lo[4 * h + 1] += u.y; lo[4 * h + 2] += u.z; lo[4 * h + 3] += u.w;
+                }
+                if (HI) {
+                    const float4 u = q1[h];
+                    hi[4 * h] += u.x; hi[4 * h + 1] += u.y; hi[4 * h + 2] += u.z; hi[4 * h + 3] += u.w;
+                }
+            }
+        } else {
+            for (int s = ps; s < pe; ++s) {
+                const float4 *r = reinterpret_cast<const float4 *>(rec + (long long)s * GREC);
+                const float4 r0 = r[0], r1 = r[1];
+                const float x[3] = {r0.x, r0.y, r0.z};
+                const float lam[3] = {r0.w, r1.x, r1.y};
+                const float fx = frac_in_cell(x[0], G.lo[0], G.inv_h[0], G.m[0], cx);
+                const float fy = frac_in_cell(x[1], G.lo[1], G.inv_h[1], G.m[1], cy);
+                const float fz = frac_in_cell(x[2], G.lo[2], G.inv_h[2], G.m[2], cz);
+                const float wxy = ((ab & 1) ? fx : 1.0f - fx) * ((ab & 2) ? fy : 1.0f - fy);
+                const float w0 = wxy * (1.0f - fz), w1 = wxy * fz;
+#pragma unroll
+                for (int rr = 0; rr < 3; ++rr) {
+                    if (LO) {
+                        const float wl = w0 * lam[rr];
+                        lo[rr * 4 + 0] = FS_FMA(wl, x[0], lo[rr * 4 + 0]);
+                        lo[rr * 4 + 1] = FS_FMA(wl, x[1], lo[rr * 4 + 1]);
+                        lo[rr * 4 + 2] = FS_FMA(wl, x[2], lo[rr * 4 + 2]);
+                        lo[rr * 4 + 3] += wl;
+                    }
+                    if (HI) {
+                        const float wl = w1 * lam[rr];
+                        hi[rr * 4 + 0] = FS_FMA(wl, x[0], hi[rr * 4 + 0]);
+                        hi[rr * 4 + 1] = FS_FMA(wl, x[1], hi[rr * 4 + 1]);
+                        hi[rr * 4 + 2] = FS_FMA(wl, x[2], hi[rr * 4 + 2]);
+                        hi[rr * 4 + 3] += wl;
+                    }
+                }
+            }
+        }
+    }
+}
+
+// G_T of every node for sparse lists (a few records per cell): one thread per node, consecutive SIMD lanes consecutive
+// nodes along z.  A node-by-node gather over its 8 adjacent cells reads every record 8 times, and a wave runs as long
+// as the sum over the 8 cells of the longest list among its lanes.  Here a lane walks only the 4 cells at its own height
+// (cz = iz), adds each record's share for the lower z-corner to its own node and collects the share for the upper
+// z-corner, which belongs to the node above it: the next SIMD lane, which receives it with one shuffle per entry.  Every
+// record is read 4 times and the loops are half as long.  A lane whose lower neighbour sits in another wave (lane 0 of
+// a wave that starts inside a column) walks that neighbour's 4 cells itself.
+__global__ __launch_bounds__(256) void k_grad_nodes_z(GridP G, int ncell, const int *__restrict__ offset,
+                                                      const float *__restrict__ rec, float *__restrict__ GT)
+{
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const bool valid = i < (long long)G.P * G.V;
+    int p = 0, ix = 0, iy = 0, iz = 0;
+    if (valid) {
+        p = (int)(i / G.V);
+        const unsigned v = (unsigned)(i - (long long)p * G.V), t = v / (unsigned)G.nz;
+        iz = (int)(v - t * (unsigned)G.nz);
+        ix = (int)(t / (unsigned)G.ny);
+        iy = (int)(t - (unsigned)ix * (unsigned)G.ny);
+    }
+    float acc[12], up[12];
+#pragma unroll
+    for (int e = 0; e < 12; ++e) acc[e] = up[e] = 0.0f;
+    if (valid && iz <= G.nz - 2) {
+        for (int ab = 0; ab < 4; ++ab) {
+            const int cx = ix - (ab & 1), cy = iy - (ab >> 1);
+            if (cx < 0 || cy < 0 || cx > G.nx - 2 || cy > G.ny - 2) continue;
+            const int c = p * ncell + (cx * (G.ny - 1) + cy) * (G.nz - 1) + iz;
+            const int a = offset[c], b = offset[c + 1];
+            if (a != b) grad_cell_pair<true, true>(G, rec, a, b, ab, cx, cy, iz, acc, up);
+        }
+    }
+    // what the node below collected for this one (lane - 1 is node i - 1: the same column when iz > 0)
+    const bool from_lane = lane > 0 && valid && iz > 0;
+#pragma unroll
+    for (int e = 0; e < 12; ++e) {
+        const float below = __shfl_up(up[e], 1);
+        if (from_lane) acc[e] += below;
+    }
+    if (valid && iz > 0 && !from_lane) {
+        for (int ab = 0; ab < 4; ++ab) {
+            const int cx = ix - (ab & 1), cy = iy - (ab >> 1);
+            if (cx < 0 || cy < 0 || cx > G.nx - 2 || cy > G.ny - 2) continue;
+            const int c = p * ncell + (cx * (G.ny - 1) + cy) * (G.nz - 1) + iz - 1;
+            const int a = offset[c], b = offset[c + 1];
+            if (a != b) grad_cell_pair<false, true>(G, rec, a, b, ab, cx, cy, iz - 1, up, acc);
+        }
+    }
+    if (!valid) return;
+    float4 *o = reinterpret_cast<float4 *>(GT + i * 12);
+    o[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    o[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+    o[2] = make_float4(acc[8], acc[9], acc[10], acc[11]);
+}
+
 // gW[v][b] = sum_p sum_e G_T[p][v][e] B[p][b][e]: one thread per node and group of 8 bones (groups of a node
 // in neighbouring threads, so the node's G_T records come from the same cache lines and the stores are
 // contiguous); the bone transforms are staged in LDS.

@@ -14,7 +14,9 @@ __device__ __forceinline__ unsigned lcg(unsigned &s)
     return s >> 8;
 }
 
-// pattern 0: every lane reads a random 16-byte piece; 1: 8 adjacent lanes read one aligned 128-byte line
+// pattern 0: every lane reads a random 16-byte piece; 1: 8 adjacent lanes read one aligned 128-byte line;
+// 2: every lane reads, with six consecutive instructions, the six 16-byte pieces of a random pair of adjacent 48-byte
+// records (what a lane of the solve kernel does for each of the four (x, y) corners of a grid cell)
 template <int PAT>
 __global__ __launch_bounds__(256) void mb_gather(const float4 *__restrict__ a, unsigned npieces, int iters,
                                                  float4 *__restrict__ sink)
@@ -24,6 +26,15 @@ __global__ __launch_bounds__(256) void mb_gather(const float4 *__restrict__ a, u
     unsigned s8 = (tid >> 3) * 2654435761u + 77u;
     float4 acc = make_float4(0, 0, 0, 0);
     for (int i = 0; i < iters; ++i) {
+        if (PAT == 2) {
+            const float4 *p = a + (lcg(s) % (npieces / 3 - 2)) * 3;
+#pragma unroll
+            for (int u = 0; u < 6; ++u) {
+                const float4 v = p[u];
+                acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+            }
+            continue;
+        }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const unsigned idx = PAT == 0 ? lcg(s) % npieces : (lcg(s8) % (npieces / 8)) * 8 + (lane & 7);
@@ -100,7 +111,7 @@ extern "C" fs_status fs_microbench(int32_t which, int64_t array_bytes, double *r
     float ms = 0.0f;
     bool ok = false;
     fs_status st = FS_OK;
-    if (which == FS_MB_GATHER_LANE || which == FS_MB_GATHER_LINE) {
+    if (which == FS_MB_GATHER_LANE || which == FS_MB_GATHER_LINE || which == FS_MB_GATHER_SEGMENT) {
         if (array_bytes < 4096 || array_bytes > (1ll << 32)) {
             st = FS_E_SHAPE;
         } else {
@@ -113,10 +124,13 @@ extern "C" fs_status fs_microbench(int32_t which, int64_t array_bytes, double *r
                 const unsigned np = (unsigned)(array_bytes / 16);
                 if (which == FS_MB_GATHER_LANE)
                     ok = time_ms([&] { mb_gather<0><<<blocks, 256>>>(a, np, iters, sink); }, &ms);
-                else
+                else if (which == FS_MB_GATHER_LINE)
                     ok = time_ms([&] { mb_gather<1><<<blocks, 256>>>(a, np, iters, sink); }, &ms);
+                else
+                    ok = time_ms([&] { mb_gather<2><<<blocks, 256>>>(a, np, iters, sink); }, &ms);
                 (void)hipFree(a);
-                if (ok) *result = (double)blocks * 256 * iters * 8 / (ms * 1e-3);     // lane accesses per second
+                // lane accesses per second (8 per round, 6 for the record pairs)
+                if (ok) *result = (double)blocks * 256 * iters * (which == FS_MB_GATHER_SEGMENT ? 6 : 8) / (ms * 1e-3);
             }
         }
     } else if (which == FS_MB_LDS_GATHER) {
