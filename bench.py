@@ -309,20 +309,31 @@ def main():
         out["slot_requests_per_s"] = case.conv / (case.kernel_ms * 1e-3)
 
     if not args.no_microbench:
-        # ceilings of the solve kernel measured on this device by the library's micro-benchmarks
+        # Ceilings of the Broyden kernel measured on this device by the library's micro-benchmarks.  The kernel's own
+        # access pattern is FS_MB_GATHER_SEGMENT: every SIMD lane reads the six 16-byte pieces of a random pair of adjacent
+        # 48-byte records.  Its rate depends on where the records come from, so it is measured for an array the size of
+        # one pose's transform grid (what all waves work on at a time when the points are grouped by pose) and of all of them.
+        pose_bytes = max(case.grid_bytes // w.n_poses, 4096)
         gb = max(case.grid_bytes, 4096)
-        fma = binding.microbench(binding.MB_FMA)
-        gl = binding.microbench(binding.MB_GATHER_LANE, gb)
-        gline = binding.microbench(binding.MB_GATHER_LINE, gb)
-        glds = binding.microbench(binding.MB_LDS_GATHER)
-        loads = case.evals * LOADS_EVAL / (case.kernel_ms * 1e-3)
-        out["roofline"].update({
-            "measured_fma_tflops": fma / 1e12,
-            "gather_path": {"algorithmic_16B_loads_per_s": loads, "footprint_bytes": case.grid_bytes,
-                            "ceiling_line_coalesced_gather_same_footprint": gline,
-                            "frac_of_line_coalesced_ceiling": loads / gline,
-                            "ceiling_lds_lane_random_gather": glds, "frac_of_lds_ceiling": loads / glds,
-                            "lane_random_gather_same_footprint": gl}})
+        ks = case.kernel_ms * 1e-3
+        loads = case.evals * LOADS_EVAL / ks
+        seg_pose = binding.microbench(binding.MB_GATHER_SEGMENT, pose_bytes)
+        seg_all = seg_pose if gb == pose_bytes else binding.microbench(binding.MB_GATHER_SEGMENT, gb)
+        gp = {"algorithmic_16B_loads_per_s": loads, "grid_bytes": case.grid_bytes, "grid_bytes_per_pose": pose_bytes,
+              # rates of the library's micro-benchmarks on this device: references for the kernel's gather path, not bounds
+              # (the kernel's lanes are not independent random readers: neighbouring evaluations of a lane share cache lines)
+              "reference_rates_16B_loads_per_s": {
+                  "segment_gather_one_pose_grid": seg_pose, "segment_gather_whole_grid": seg_all,
+                  "line_coalesced_gather_whole_grid": binding.microbench(binding.MB_GATHER_LINE, gb),
+                  "lane_random_gather_whole_grid": binding.microbench(binding.MB_GATHER_LANE, gb),
+                  "segment_gather_l1_resident": binding.microbench(binding.MB_GATHER_SEGMENT, 8192),
+                  "lds_lane_random_gather": binding.microbench(binding.MB_LDS_GATHER)}}
+        issued = profile_value(args.config, "l1_accesses_per_launch") if not (args.no_slots or args.unfused) else None
+        if issued is not None:
+            # loads the kernel really issues (rocprofv3 TCP_TOTAL_CACHE_ACCESSES, profiles/): fewer than the algorithmic
+            # 24 per evaluation, since a lane that stays in its grid cell keeps the 8 records in registers
+            gp.update({"issued_16B_loads_per_launch": issued, "issued_16B_loads_per_s": issued / ks})
+        out["roofline"].update({"measured_fma_tflops": binding.microbench(binding.MB_FMA) / 1e12, "gather_path": gp})
 
     if args.probe_copy_mib > 0:
         a = torch.empty(args.probe_copy_mib << 18, dtype=torch.float32, device=dev)

@@ -1021,6 +1021,90 @@ __device__ __forceinline__ void park_slots(bool want_slot, int slot_cell, int pa
     }
 }
 
+// ---- result records of k_solve_ws leave through LDS ---------------------------------------------------------------
+// A lane that finishes does not store its 64-byte record itself (four 16-byte stores to an address of its own: four
+// vector-memory instructions in nearly every pass of the wave, each of which reaches memory as a partial write of a
+// 32-byte sector).  The wave parks finished records in LDS, OUT_PEND per wave, together with the grid cell of the
+// converged ones; when OUT_SEND have gathered it asks for their positions in their cells' lists (one atomic per cell
+// and round of 64, as flush_slots does), puts each position into its record, and writes the records out with four
+// consecutive lanes per record: every record reaches memory once, whole, as 64 contiguous bytes.
+constexpr int OUT_PEND = 128, OUT_SEND = 112;
+struct OutQ {
+    float4 rec[OUT_PEND][4];
+    int cell[OUT_PEND];      // grid cell (pose * ncell + cell) of a converged lane that wants a position, else -1
+    int pair[OUT_PEND];
+};
+
+__device__ __forceinline__ void out_flush(OutQ &q, int npend, int lane, int *__restrict__ cell_count, float4 *__restrict__ rec)
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");      // the LDS writes of the wave's other lanes
+    __builtin_amdgcn_wave_barrier();
+    if (cell_count) {
+        // two rounds of 64 entries; the atomics of both are on their way before either answer is used
+        bool valid[2];
+        int leader[2], rank[2], base[2];
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int c = 64 * b + lane < npend ? q.cell[64 * b + lane] : -1;
+            valid[b] = c >= 0;
+            int members = 1;
+            leader[b] = lane;
+            rank[b] = 0;
+            unsigned long long todo = __ballot(valid[b]);
+            while (todo) {
+                const int first = __ffsll((long long)todo) - 1;
+                const int key = __builtin_amdgcn_readlane(c, first);
+                const unsigned long long same = __ballot(valid[b] && c == key);
+                if (valid[b] && c == key) {
+                    leader[b] = first;
+                    rank[b] = __popcll(same & ((1ull << lane) - 1ull));
+                    members = __popcll(same);
+                }
+                todo &= ~same;
+            }
+            base[b] = 0;
+            if (valid[b] && leader[b] == lane) base[b] = atomicAdd(cell_count + c, members);
+        }
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int bs = __shfl(base[b], leader[b]);
+            if (valid[b]) reinterpret_cast<int *>(&q.rec[64 * b + lane][1])[0] = bs + rank[b];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+    for (int i = lane; i < npend * 4; i += 64) rec[(long long)q.pair[i >> 2] * 4 + (i & 3)] = q.rec[i >> 2][i & 3];
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");      // before the entries are overwritten
+    __builtin_amdgcn_wave_barrier();
+}
+
+// park the record of every lane with `want` (wave-wide call); cell < 0: no position wanted
+__device__ __forceinline__ void out_park(bool want, const float x[3], const float J[9], int flags, int cell, int pair, OutQ &q,
+                                         int &npend, int lane, int *__restrict__ cell_count, float4 *__restrict__ rec)
+{
+    const unsigned long long m = __ballot(want);
+    if (m) {
+        if (npend + __popcll(m) > OUT_PEND) {
+            out_flush(q, npend, lane, cell_count, rec);
+            npend = 0;
+        }
+        if (want) {
+            const int at = npend + __popcll(m & ((1ull << lane) - 1ull));
+            q.rec[at][0] = make_float4(x[0], x[1], x[2], __int_as_float(flags));
+            q.rec[at][1] = make_float4(__int_as_float(-1), J[0], J[1], J[2]);
+            q.rec[at][2] = make_float4(J[3], J[4], J[5], J[6]);
+            q.rec[at][3] = make_float4(J[7], J[8], 0.0f, 0.0f);
+            q.cell[at] = cell;
+            q.pair[at] = pair;
+        }
+        npend += __popcll(m);
+    }
+    if (npend >= OUT_SEND) {
+        out_flush(q, npend, lane, cell_count, rec);
+        npend = 0;
+    }
+}
+
 // ---- corner records with zero weight need not be fetched ------------------------------------------------
 // A coordinate outside the box is clamped, so its fraction is exactly 0 or 1 and the four corners on the far
 // side of that axis get the weight 0: their records contribute 0 * T_c, i.e. nothing but possibly the sign of
@@ -1093,7 +1177,7 @@ __device__ __forceinline__ bool blend_apply_z(const Cell &c, const float (&q)[8]
 }
 
 template <bool FUSED, bool WITH_J, int NCONS, bool SKIP>
-__global__ __launch_bounds__(64 * (NCONS + 1), (SKIP || NCONS > 3) ? 2 : 3) void k_solve_ws(GridP G, SolveP S, InitP I, const float *__restrict__ T,
+__global__ __launch_bounds__(64 * (NCONS + 1), 2) void k_solve_ws(GridP G, SolveP S, InitP I, const float *__restrict__ T,
                                                const float *__restrict__ xq, const int32_t *__restrict__ pose,
                                                const float *__restrict__ x0, const float *__restrict__ J0,
                                                const uint8_t *__restrict__ valid0, float4 *__restrict__ rec,
@@ -1104,7 +1188,7 @@ __global__ __launch_bounds__(64 * (NCONS + 1), (SKIP || NCONS > 3) ? 2 : 3) void
 {
     __shared__ float s_ring[NCONS][ST_FIELDS][WS_RING];
     __shared__ int s_tail[NCONS], s_head[NCONS], s_done;
-    __shared__ int s_pend[NCONS + 1][2][PEND];
+    __shared__ OutQ s_out[WITH_J ? NCONS + 1 : 1];      // records on their way out, per wave (only full records are parked)
     if (threadIdx.x < NCONS) {
         s_tail[threadIdx.x] = 0;
         s_head[threadIdx.x] = 0;
@@ -1115,7 +1199,8 @@ __global__ __launch_bounds__(64 * (NCONS + 1), (SKIP || NCONS > 3) ? 2 : 3) void
     const int lane = threadIdx.x & 63;
     const int wib = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const long long N = S.N;
-    int npend = 0;                   // wave-uniform: entries of s_pend in use
+    int npend = 0;                   // wave-uniform: entries of the wave's s_out in use
+    OutQ &outq = s_out[WITH_J ? wib : 0];
 
     if (wib == NCONS) {
         // ------------------------------------------------ producer ------------------------------------------------
@@ -1142,8 +1227,8 @@ __global__ __launch_bounds__(64 * (NCONS + 1), (SKIP || NCONS > 3) ? 2 : 3) void
             }
             const long long pq = next + lane;
             next += min(64ll, c1 - next);
-            bool keep = false, want_slot = false;
-            int slot_cell = 0, pair = 0;
+            bool keep = false, want_out = false;
+            int out_cell = -1, out_flags = 0, pair = 0;
             int nn = 0, nk = 0, np = 0;
             float nxp[3] = {0, 0, 0}, nx[3] = {0, 0, 0}, ng[3] = {0, 0, 0}, ndx[3] = {0, 0, 0};
             float nJ[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
@@ -1248,10 +1333,12 @@ __global__ __launch_bounds__(64 * (NCONS + 1), (SKIP || NCONS > 3) ? 2 : 3) void
                     const float r2 = FS_FMA(ng[2], ng[2], FS_FMA(ng[1], ng[1], ng[0] * ng[0]));
                     const bool conv = r2 < S.tol2;
                     if (conv || !(r2 < S.div2) || 0 >= S.max_iters) {
-                        write_record<WITH_J>(rec, pair, nx, nJ, conv ? 1 : 0);
-                        if (WITH_J && cell_count && conv) {
-                            want_slot = true;
-                            slot_cell = np * ncell + c0lin;
+                        if (WITH_J) {
+                            want_out = true;
+                            out_flags = conv ? 1 : 0;
+                            if (cell_count && conv) out_cell = np * ncell + c0lin;
+                        } else {
+                            write_record<false>(rec, pair, nx, nJ, conv ? 1 : 0);
                         }
                     } else {
                         keep = true;
@@ -1260,7 +1347,10 @@ __global__ __launch_bounds__(64 * (NCONS + 1), (SKIP || NCONS > 3) ? 2 : 3) void
                             ndx[r] = -FS_FMA(nJ[r * 3 + 2], ng[2], FS_FMA(nJ[r * 3 + 1], ng[1], nJ[r * 3] * ng[0]));
                     }
                 }
-                if (!ok && !norec) write_record<WITH_J>(rec, pair, nx, nJ, 0);
+                if (!ok && !norec) {
+                    if (WITH_J) want_out = true;         // out_flags = 0, no position
+                    else write_record<false>(rec, pair, nx, nJ, 0);
+                }
             }
             const unsigned long long km = __ballot(keep);
             const int nkeep = __popcll(km);
@@ -1305,10 +1395,10 @@ __global__ __launch_bounds__(64 * (NCONS + 1), (SKIP || NCONS > 3) ? 2 : 3) void
                 for (int c = 0; c < NCONS; ++c) if (c == best) tails[c] = tl;
                 if (lane == 0) lds_store_release(&s_tail[best], tl);
             }
-            if (WITH_J && cell_count) park_slots(want_slot, slot_cell, pair, s_pend[wib], npend, lane, cell_count, rec);
+            if (WITH_J) out_park(want_out, nx, nJ, out_flags, out_cell, pair, outq, npend, lane, cell_count, rec);
         }
         if (lost && lane == 0) *give_up = 1;
-        if (WITH_J && cell_count && npend > 0) flush_slots(s_pend[wib], npend, lane, cell_count, rec);
+        if (WITH_J && npend > 0) out_flush(outq, npend, lane, cell_count, rec);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         if (lane == 0) lds_store_release(&s_done, 1);
         return;
@@ -1379,8 +1469,8 @@ __global__ __launch_bounds__(64 * (NCONS + 1), (SKIP || NCONS > 3) ? 2 : 3) void
                 else __builtin_amdgcn_s_sleep(8);
             }
         }
-        bool want_slot = false;
-        int slot_cell = 0;
+        bool want_out = false;
+        int out_cell = -1, out_flags = 0;
         if (active) {
             float d[3], gn[3];
             const Cell cell = locate(G, xt);
@@ -1434,10 +1524,12 @@ __global__ __launch_bounds__(64 * (NCONS + 1), (SKIP || NCONS > 3) ? 2 : 3) void
             const bool conv = r2 < S.tol2;
             const bool done = conv || !(r2 < S.div2) || it >= S.max_iters;
             if (done) {
-                write_record<WITH_J>(rec, (long long)k * N + n, x, J, (conv ? 1 : 0) | (it << 8));
-                if (WITH_J && cell_count && conv) {
-                    want_slot = true;
-                    slot_cell = pz * ncell + cell_linear(G, cell);
+                if (WITH_J) {
+                    want_out = true;
+                    out_flags = (conv ? 1 : 0) | (it << 8);
+                    if (cell_count && conv) out_cell = pz * ncell + cell_linear(G, cell);
+                } else {
+                    write_record<false>(rec, (long long)k * N + n, x, J, (conv ? 1 : 0) | (it << 8));
                 }
                 active = false;
             } else {
@@ -1448,10 +1540,9 @@ __global__ __launch_bounds__(64 * (NCONS + 1), (SKIP || NCONS > 3) ? 2 : 3) void
                 }
             }
         }
-        if (WITH_J && cell_count)
-            park_slots(want_slot, slot_cell, (int)((long long)k * N + n), s_pend[wib], npend, lane, cell_count, rec);
+        if (WITH_J) out_park(want_out, x, J, out_flags, out_cell, (int)((long long)k * N + n), outq, npend, lane, cell_count, rec);
     }
-    if (WITH_J && cell_count && npend > 0) flush_slots(s_pend[wib], npend, lane, cell_count, rec);
+    if (WITH_J && npend > 0) out_flush(outq, npend, lane, cell_count, rec);
 }
 
 // ------------------------------------------------------------------------------------------------

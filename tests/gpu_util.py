@@ -9,6 +9,7 @@ from paper_2211_15601_amd import binding
 DEV = "cuda:0"
 ROOT_TOL = 1e-4          # converged roots agree within 1e-4 absolute (fp32)
 MASK_BAND = 1e-6         # masks may differ only where | |g| - tol | < 1e-6
+RESIDUAL_SLACK_CAP = 8e-6   # float64 re-evaluation of a converged lane: |d(x*) - x'| < tol + this (fp32 rounding of the residual)
 
 
 def dev(a, dtype=None):
@@ -183,9 +184,11 @@ def compare_solve(w, T, gpu_out, orc_out, v0, report=None):
     Tmax = max(1.0, float(np.abs(T).max()))
     xabs = 1.0 + np.abs(np.nan_to_num(xg.astype(np.float64))).sum(axis=1)
     dx = 2.0 ** -23 * float(np.max(np.asarray(w.hi, np.float64) - np.asarray(w.lo, np.float64))) * np.sqrt(3.0)
-    slack = 1.3e-6 * Tmax * xabs + dx * (jacobian_norm_f64(w, T, xg) + 3.0 * Tmax)
+    # That bound is per lane and loose (up to 1.6e-5 on the multi-pose batch); observed over all five configurations at full
+    # size the float64 residual exceeds tol by at most 3.7e-6, so the slack is also capped at about twice that.
+    slack = np.minimum(1.3e-6 * Tmax * xabs + dx * (jacobian_norm_f64(w, T, xg) + 3.0 * Tmax), RESIDUAL_SLACK_CAP)
     stats["max_excess_over_tol"] = float((res_g - tol)[cg == 1].max()) if (cg == 1).any() else 0.0
-    assert (res_g[cg == 1] < (tol + slack)[cg == 1]).all()
+    assert (res_g[cg == 1] < (tol + slack)[cg == 1]).all(), stats["max_excess_over_tol"]
     m3 = np.broadcast_to(both[:, None, :], xg.shape)
     stats["bit_equal_roots"] = bool((xg[m3] == xo[m3]).all())
     stats["iters_equal"] = bool((ig == io).all())

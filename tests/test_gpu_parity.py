@@ -111,7 +111,7 @@ def test_grad_parity(lib, case, mode):
     # the clamped field's across the box faces, and fp32 and float64 round the cell coordinate to different sides), and lanes with |det J(x*)| < DET_FLOOR (the weight-derivative
     # part of J is a difference of corner images times 1/h: about 8 * 2^-24 * |d| / h ~ 1e-5 absolute in fp32, which
     # the inverse amplifies by cond(J) <= |J|^2 / |det| ~ 1e3 at the floor).  What remains is compared element by
-    # element with the bar widened to 1e-3 (observed with the CPU oracles alone, fp32 against float64: <= 4.6e-4 of max|b|).
+    # element with the bar widened to 4e-4 of max|b| (observed on the five configurations at full size: <= 2e-4).
     ref32 = oracle.grad(w.dims, w.lo, w.hi, T_ref, w.W, w.B, xc, Jo, cv, gxc, pose=pose, mode=mode, prec="f32")
     got = run.grad(xc, None, cv, gxc)
     for name, a, b in zip(("gW", "gB", "gxq"), got, ref32):
@@ -131,7 +131,7 @@ def test_grad_parity(lib, case, mode):
     ref64 = oracle.grad(w.dims, w.lo, w.hi, T_ref, w.W, w.B, xc, Jo, cv_ok, gxc, pose=pose, mode=mode, prec="f64")
     got = run.grad(xc, None, cv_ok, gxc)
     for name, a, b in zip(("gW", "gB", "gxq"), got, ref64):
-        gu.assert_grad_close(name, a, b, f"{label} vs f64, well-posed lanes", atol_of_max=1e-3, rtol=1e-3)
+        gu.assert_grad_close(name, a, b, f"{label} vs f64, well-posed lanes", atol_of_max=4e-4, rtol=4e-4)
 
 
 @pytest.mark.parametrize("case", [(2, 5003, (32, 32, 8), None), (3, 16 * 255, (32, 32, 8), None), (5, 8 * 1003, (32, 32, 16), 8),
