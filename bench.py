@@ -69,6 +69,7 @@ class Case:
         self.ctx = binding.Context(w.dims, w.n_bones, w.lo, w.hi, n_poses=w.n_poses, tol=w.tol, div_thresh=w.div_thresh,
                                    max_iters=w.max_iters, init_mode=w.init_mode, grad_mode=binding.FS_GRAD_BROYDEN_J,
                                    corr_dims=w.corr_dims)
+        self.ctx.set_list_order({"input": 0, "place": 1, "place-xcd": 2}[getattr(args, "list_order", "input")])
         up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
         self.W, self.B, self.xq = up(w.W), up(w.B), up(w.xq)
         self.pose = up(w.pose) if w.n_poses > 1 else None
@@ -258,6 +259,10 @@ def main():
                     help="instead of the benchmark: time fs_precompute + fs_solve for 200k posed points x 24 inits on "
                          "weight grids of 16x16x4 .. 128x128x32 (the shape of the paper's grid-resolution ablation, "
                          "Table 2) and print one JSON line per grid")
+    ap.add_argument("--list-order", choices=("input", "place", "place-xcd"), default="input",
+                    help="order of the (point, candidate) pair list of voxel-based solves: as the points come (default), "
+                         "ordered by pose and correspondence cell on the device, or ordered and cut into one range "
+                         "per XCD (fs_set_list_order 0 / 1 / 2)")
     ap.add_argument("--unfused", action="store_true",
                     help="materialise the initial states with fs_init instead of computing them inside fs_solve")
     args = ap.parse_args()
@@ -295,6 +300,7 @@ def main():
                            + ("" if args.no_grad else " + fs_grad")
                            + ("" if case.slot is None else (", cell positions handed from the solve to the backward"
                                                             + (", J~ kept in the library" if case.Jarg is None else ""))),
+                   "list_order": args.list_order,
                    "pairs": case.N * case.K, "valid_pairs": case.valid, "converged_pairs": case.conv,
                    "lane_iterations": case.evals},
         "calls_ms": case.calls,

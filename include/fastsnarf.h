@@ -101,10 +101,12 @@ fs_status fs_set_tuning(fs_ctx *ctx, int32_t chunk, int32_t refill_min, int32_t 
 /* Order in which fs_solve works through the (point, candidate) pairs of voxel-based initial states computed inside the
  * kernel; results never depend on it.  by_place = 0 (default): the order of the points.  1: batches of at least 65,536
  * points are first ordered by pose and column of correspondence cells with a counting sort, so that lanes at work at the
- * same time read neighbouring parts of the transform grid.  Measured on the 8-pose batch of 4.2 M points: the memory
- * traffic of the Broyden kernel falls by more than half, its time by 2 % (query points and result records are then
- * reached in scattered order), and the sort costs 0.09 ms: a loss unless the caller's points come in an order that
- * scatters them over poses. */
+ * same time read neighbouring parts of the transform grid.  2: as 1, and the ordered list is cut into 8 ranges, one per
+ * XCD with a cursor of its own (blocks whose range is used up take chunks from the others), so that every XCD's L2
+ * sees one stretch of one pose's grid.  Measured on the 8-pose batch of 4.2 M points (Broyden kernel alone):
+ * 0: 1.36 ms, 8.6 GB read from beyond the L2 (hit rate 0.47); 1: 1.26 ms, 6.8 GB; 2: 1.29 ms, 2.9 GB (hit rate 0.72).
+ * The kernel is limited by the vector cache in front of the L2, not by what the L2 misses, and the sort costs
+ * 0.09 ms: over the whole step 1 gains 2 % on that batch and loses 7 % on batches of 1 M points, hence the default. */
 fs_status fs_set_list_order(fs_ctx *ctx, int32_t by_place);
 
 /* The waves of a block of the solve kernel hand work to each other through queues in LDS (one wave prepares

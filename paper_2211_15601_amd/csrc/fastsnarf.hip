@@ -65,6 +65,7 @@ struct fs_ctx {
     int scan_cap;      // tiles scan_sums can hold
     int n_cus, occ_blocks_per_cu, occ_ws_blocks_per_cu, occ_vx_blocks_per_cu, chunk, refill_min, blocks_per_cu, point_major, lds_grid;
     int sort_list;     // order the list of (point, candidate) pairs by place (large voxel-mode batches)
+    int xcd_ranges;    // with an ordered list: one range of it, and one cursor, per XCD
     int spin_limit;    // polls for room in its consumers' queues before the producer wave of a solve block gives up
     int pre_serial;    // number of the last fs_precompute; cursor[CUR_NONFINITE] == pre_serial: that grid has an entry that is not finite
     int *gave_up;      // pinned host word, mapped into the device: a wave that gave up sets it
@@ -182,7 +183,8 @@ void free_all(fs_ctx *c)
 fs_status scan_exclusive(fs_ctx *c, int n, int *a, const int *src = nullptr, int *also_zero = nullptr)
 {
     if (n <= 0) {
-        k_fill_zero_i32<<<1, 64, 0, c->stream>>>(1, a, reinterpret_cast<unsigned *>(also_zero));
+        k_fill_zero_i32<<<1, 64, 0, c->stream>>>(1, a);
+        if (also_zero) k_fill_zero_i32<<<1, 64, 0, c->stream>>>(1, also_zero);
         return FS_OK;
     }
     const int m = (n + SCAN_TILE - 1) / SCAN_TILE;
@@ -317,6 +319,7 @@ fs_status fs_create(const fs_grid_desc *desc, const fs_params *params, void *hip
         c->point_major = 1;
         c->lds_grid = 1;
         c->sort_list = 0;
+        c->xcd_ranges = 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
         (void)hipGetLastError();
         c->n_cus = cus;
@@ -398,8 +401,9 @@ fs_status fs_set_tuning(fs_ctx *ctx, int32_t chunk, int32_t refill_min, int32_t 
 fs_status fs_set_list_order(fs_ctx *ctx, int32_t by_place)
 {
     if (!ctx) return FS_E_ARG;
-    if (by_place != 0 && by_place != 1) return fail(ctx, FS_E_ARG, "fs_set_list_order: by_place must be 0 or 1");
-    ctx->sort_list = by_place;
+    if (by_place < 0 || by_place > 2) return fail(ctx, FS_E_ARG, "fs_set_list_order: by_place must be 0, 1 or 2");
+    ctx->sort_list = by_place != 0;
+    ctx->xcd_ranges = by_place == 2;
     return FS_OK;
 }
 
@@ -544,6 +548,7 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     hipStream_t st = ctx->stream;
     const int2 *list = nullptr;
     const int *list_len = nullptr;
+    S.xcd_ranges = 0;
     if (voxel_list) {
         if ((size_t)N > ctx->vcap) {
             (void)hipStreamSynchronize(st);
@@ -579,6 +584,7 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
             { fs_status ss = scan_exclusive(ctx, (int)((long long)nb * sblk), ctx->vhist); if (ss != FS_OK) return ss; }
             k_sort_scatter<<<(unsigned)sblk, 1024, nb * sizeof(int), st>>>(N, ctx->C.cz, nb, ctx->vgcell, ctx->vcnt, ctx->vhist, ctx->vlist);
             list_len = ctx->vhist + (long long)nb * sblk;
+            S.xcd_ranges = (!lds && ctx->xcd_ranges) ? 1 : 0;
         } else {
             { fs_status ss = scan_exclusive(ctx, (int)N, ctx->voffs); if (ss != FS_OK) return ss; }
             k_voxel_expand<<<grid1d(N, 256), 256, 0, st>>>(N, ctx->voffs, ctx->vgcell, ctx->vlist);
@@ -591,15 +597,15 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     ctx->slots_N = 0;
     // every wave that draws chunks (all four of a k_solve block, the producer of a k_solve_ws block) owns the
     // chunk of its own number to begin with; the shared cursor starts behind those
-    const unsigned cursor0 = (unsigned)((long long)blocks * wpb * S.chunk);
+    const unsigned drawers = (unsigned)(blocks * wpb);
     if (d_slot) {
         const long long ncp = (long long)ctx->G.P * ncell;
         if (ncp + 1 >= (1ll << 31)) return fail(ctx, FS_E_SHAPE, "fs_solve: too many grid cells for d_slot");
         if (!ctx->gcount_solve && !dev_alloc(&ctx->gcount_solve, (size_t)ncp + 1)) return fail(ctx, FS_E_ALLOC, "fs_solve: out of device memory");
-        k_fill_zero_i32<<<(int)std::min<long long>(grid1d(ncp + 1, 256), 4096), 256, 0, st>>>(ncp + 1, ctx->gcount_solve, ctx->cursor, cursor0);
+        k_fill_zero_i32<<<(int)std::min<long long>(grid1d(ncp + 1, 256), 4096), 256, 0, st>>>(ncp + 1, ctx->gcount_solve, ctx->cursor, drawers, (unsigned)S.chunk);
         cell_count = ctx->gcount_solve;
     } else {
-        k_reset_cursor<<<1, 64, 0, st>>>(ctx->cursor, cursor0);
+        k_reset_cursor<<<1, 64, 0, st>>>(ctx->cursor, drawers, (unsigned)S.chunk);
     }
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     if (ctx->timing && hipEventCreate(&ev0) == hipSuccess && hipEventCreate(&ev1) == hipSuccess) (void)hipEventRecord(ev0, st);

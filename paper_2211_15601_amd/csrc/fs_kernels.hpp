@@ -21,6 +21,29 @@ constexpr int FS_MAX_CORR_K_DEV = 8;
 // wave-uniform addresses, i.e. through the scalar cache into SGPR operands of the multiply-adds.
 // Reads W once (96 B / node for 24 bones), writes 48 B per node and pose.
 // ------------------------------------------------------------------------------------------------
+// Every thread of a 256-thread block holds one row of NF floats (NF = 12: a 48-byte record; NF = 3: a point) of a
+// tile whose rows are contiguous in memory (row r of the tile at dst + r * NF).  Stored straight from registers, a row goes
+// out as 16-byte pieces at a 48-byte stride: partial writes of cache lines, for which the L2 first fetches the line (on
+// the 8-pose 128x128x32 grid k_precompute fetched 386 MB to read 50 MB of weights).  Through LDS the tile leaves as
+// whole, consecutive 16-byte pieces from consecutive threads.  nrows = valid rows of the tile (block-uniform); all
+// threads of the block must call.  s_tile: 256 * NF floats of LDS.
+template <int NF>
+__device__ __forceinline__ void block_store_rows(float *__restrict__ dst, const float (&v)[NF], int nrows, float *s_tile)
+{
+    __syncthreads();                               // s_tile may still be read from the call before
+#pragma unroll
+    for (int e = 0; e < NF; ++e) s_tile[threadIdx.x * NF + e] = v[e];
+    __syncthreads();
+    const int n4 = nrows * NF / 4, tail = nrows * NF - n4 * 4;
+    if ((reinterpret_cast<uintptr_t>(dst) & 15u) == 0) {
+        for (int i = threadIdx.x; i < n4; i += 256)
+            reinterpret_cast<float4 *>(dst)[i] = reinterpret_cast<const float4 *>(s_tile)[i];
+        if ((int)threadIdx.x < tail) dst[n4 * 4 + threadIdx.x] = s_tile[n4 * 4 + threadIdx.x];
+    } else {
+        for (int i = threadIdx.x; i < nrows * NF; i += 256) dst[i] = s_tile[i];
+    }
+}
+
 __device__ __forceinline__ void bone_inverse(int i, const float *__restrict__ B, float *__restrict__ Bcopy,
                                              float *__restrict__ Binv, uint8_t *__restrict__ ok);
 
@@ -48,42 +71,50 @@ __global__ __launch_bounds__(256) void k_precompute(GridP G, const float *__rest
 {
     // *nonfinite = serial (the number of this call) tells the solve that this grid holds an entry that is not
     // finite: a record with weight zero may then not be skipped (0 * inf is not 0)
-    const long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    __shared__ float s_tile[256 * 12];
+    const long long v0 = (long long)blockIdx.x * blockDim.x, v = v0 + threadIdx.x;
     for (long long i = v; i < (long long)G.P * G.nb; i += (long long)gridDim.x * blockDim.x)
         bone_inverse((int)i, B, Bcopy, Binv, Bok);
-    if (v >= G.V) return;
-    const float *w = W + v * G.nb;
+    const bool live = v < G.V;                   // the last block: its other threads stay for the block-wide stores
+    const int nrows = (int)min(256ll, G.V - v0);
+    const float *w = W + (live ? v : 0) * G.nb;
     const bool vec = (G.nb & 3) == 0;        // weight rows are 16-byte aligned: read them four at a time
     float xv[3] = {0.0f, 0.0f, 0.0f};
-    if (Y) node_pos(G, v, xv);
+    if (Y && live) node_pos(G, v, xv);
     // four poses share one pass over the node's weights; per pose the sum runs over the bones in order,
     // first term a product, the rest fused multiply-adds
     for (int p0 = 0; p0 < G.P; p0 += 4) {
         const int np = min(4, G.P - p0);
         float acc[4][12];
-        for (int b0 = 0; b0 < G.nb; b0 += 4) {
-            float wv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-            if (vec) {
-                const float4 w4 = *reinterpret_cast<const float4 *>(w + b0);
-                wv[0] = w4.x; wv[1] = w4.y; wv[2] = w4.z; wv[3] = w4.w;
-            } else {
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (b0 + j < G.nb) wv[j] = w[b0 + j];
-            }
+        for (int q = 0; q < 4; ++q)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                if (q < np) {
-                    const float *Bp = B + (long long)(p0 + q) * G.nb * 12;
+            for (int e = 0; e < 12; ++e) acc[q][e] = 0.0f;
+        if (live) {
+            for (int b0 = 0; b0 < G.nb; b0 += 4) {
+                float wv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (vec) {
+                    const float4 w4 = *reinterpret_cast<const float4 *>(w + b0);
+                    wv[0] = w4.x; wv[1] = w4.y; wv[2] = w4.z; wv[3] = w4.w;
+                } else {
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        if (b0 + j < G.nb) {
-                            if (b0 == 0 && j == 0) {
+                    for (int j = 0; j < 4; ++j)
+                        if (b0 + j < G.nb) wv[j] = w[b0 + j];
+                }
 #pragma unroll
-                                for (int e = 0; e < 12; ++e) acc[q][e] = wv[0] * Bp[e];
-                            } else {
+                for (int q = 0; q < 4; ++q) {
+                    if (q < np) {
+                        const float *Bp = B + (long long)(p0 + q) * G.nb * 12;
 #pragma unroll
-                                for (int e = 0; e < 12; ++e) acc[q][e] = FS_FMA(wv[j], Bp[(b0 + j) * 12 + e], acc[q][e]);
+                        for (int j = 0; j < 4; ++j) {
+                            if (b0 + j < G.nb) {
+                                if (b0 == 0 && j == 0) {
+#pragma unroll
+                                    for (int e = 0; e < 12; ++e) acc[q][e] = wv[0] * Bp[e];
+                                } else {
+#pragma unroll
+                                    for (int e = 0; e < 12; ++e) acc[q][e] = FS_FMA(wv[j], Bp[(b0 + j) * 12 + e], acc[q][e]);
+                                }
                             }
                         }
                     }
@@ -92,20 +123,18 @@ __global__ __launch_bounds__(256) void k_precompute(GridP G, const float *__rest
         }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            if (q < np) {
-                float big = 0.0f;
+            if (q < np) {                        // block-uniform
+                if (live) {
+                    float big = 0.0f;
 #pragma unroll
-                for (int e = 0; e < 12; ++e) big = __builtin_fmaxf(big, __builtin_fabsf(acc[q][e]) < __builtin_inff() ? 0.0f : 1.0f);
-                if (big != 0.0f) *nonfinite = serial;
-                float4 *o = reinterpret_cast<float4 *>(T + ((long long)(p0 + q) * G.V + v) * 12);
-                o[0] = make_float4(acc[q][0], acc[q][1], acc[q][2], acc[q][3]);
-                o[1] = make_float4(acc[q][4], acc[q][5], acc[q][6], acc[q][7]);
-                o[2] = make_float4(acc[q][8], acc[q][9], acc[q][10], acc[q][11]);
+                    for (int e = 0; e < 12; ++e) big = __builtin_fmaxf(big, __builtin_fabsf(acc[q][e]) < __builtin_inff() ? 0.0f : 1.0f);
+                    if (big != 0.0f) *nonfinite = serial;
+                }
+                block_store_rows<12>(T + ((long long)(p0 + q) * G.V + v0) * 12, acc[q], nrows, s_tile);
                 if (Y) {
-                    float y[3];
-                    apply12(acc[q], xv, y);
-                    float *yo = Y + ((long long)(p0 + q) * G.V + v) * 3;
-                    yo[0] = y[0]; yo[1] = y[1]; yo[2] = y[2];
+                    float y[3] = {0.0f, 0.0f, 0.0f};
+                    if (live) apply12(acc[q], xv, y);
+                    block_store_rows<3>(Y + ((long long)(p0 + q) * G.V + v0) * 3, y, nrows, s_tile);
                 }
             }
         }
@@ -525,6 +554,7 @@ struct SolveP {
     int K;
     int point_major;     // order in which pairs are handed out
     int spin_limit;      // producer / consumer kernel: polls of a work queue before a wave gives up
+    int xcd_ranges;      // producer / consumer kernel: the list is cut into 8 ranges, one per XCD, each with its own cursor
 };
 
 // What the fused variant needs to compute initial states itself (same arithmetic as k_init_*).
@@ -681,11 +711,20 @@ __global__ __launch_bounds__(256) void k_solve_unpack(long long N, long long tot
 
 // Words of the context's cursor array: CUR_ALL is the work cursor of the solve kernels; CUR_NONFINITE holds the serial
 // number of the last fs_precompute whose grid had an entry that is not finite.
-constexpr int CUR_ALL = 0, CUR_NONFINITE = 2, CUR_WORDS = 4;
+// CUR_XCD + j (j = 0 .. 7): the cursor of the j-th eighth of an ordered pair list, relative to the start of that eighth.
+constexpr int CUR_ALL = 0, CUR_NONFINITE = 2, CUR_XCD = 4, CUR_WORDS = 12, N_XCD = 8;
 
-__global__ void k_reset_cursor(unsigned *__restrict__ cursor, unsigned start)
+// The blocks of the solve kernel own their first chunk without asking: the shared cursor starts behind `nblocks`
+// chunks, the cursor of range j behind one chunk for every block b with b mod 8 = j.
+__device__ __forceinline__ void reset_cursors(unsigned *__restrict__ cursor, int i, unsigned nblocks, unsigned chunk)
 {
-    if (blockIdx.x == 0 && threadIdx.x == 0) cursor[CUR_ALL] = start;
+    if (i == 0) cursor[CUR_ALL] = nblocks * chunk;
+    if (i < N_XCD) cursor[CUR_XCD + i] = ((nblocks + (N_XCD - 1) - (unsigned)i) / N_XCD) * chunk;
+}
+
+__global__ void k_reset_cursor(unsigned *__restrict__ cursor, unsigned nblocks, unsigned chunk)
+{
+    if (blockIdx.x == 0) reset_cursors(cursor, (int)threadIdx.x, nblocks, chunk);
 }
 
 // The parked requests of one wave: entry i = {cell, pair}, one per SIMD lane.  Lanes of one point that reach
@@ -1209,8 +1248,25 @@ __global__ __launch_bounds__(64 * (NCONS + 1), 2) void k_solve_ws(GridP G, Solve
         // brought into the memory-side cache serves the others.  With a cursor per XCD over its own eighth of the
         // points -- one pose per XCD on the multi-pose batch -- the kernel was 13 % slower: eight transform grids
         // instead of one compete for that cache.)
-        long long next = (long long)blockIdx.x * S.chunk;
-        long long c1 = min(total, next + S.chunk);
+        //
+        // On request the list, ordered by place, is cut into 8 ranges, one per XCD (blocks go to the XCDs in turn, so
+        // block b runs on XCD b mod 8); a block whose range is used up takes chunks from the next ranges in turn.  The
+        // XCD's own L2 then serves 0.72 instead of 0.47 of the requests and a third of the bytes come from beyond it,
+        // but the kernel is no faster (1.29 against 1.26 ms with the ordered list behind one cursor): the vector cache
+        // in front of the L2 is the limit.
+        const bool ranges = S.xcd_ranges != 0;
+        const int home = (int)(blockIdx.x & (N_XCD - 1));
+        const long long per = ((total + (long long)N_XCD * S.chunk - 1) / ((long long)N_XCD * S.chunk)) * S.chunk;
+        long long next, c1;
+        if (ranges) {
+            const long long r1 = min(total, (home + 1) * per);
+            next = home * per + (long long)(blockIdx.x >> 3) * S.chunk;
+            c1 = min(r1, next + S.chunk);
+        } else {
+            next = (long long)blockIdx.x * S.chunk;
+            c1 = min(total, next + S.chunk);
+        }
+        int alive = 0;                    // ranges home, home + 1, ... home + alive - 1 are known to be used up
         int tails[NCONS];
 #pragma unroll
         for (int c = 0; c < NCONS; ++c) tails[c] = 0;
@@ -1218,12 +1274,31 @@ __global__ __launch_bounds__(64 * (NCONS + 1), 2) void k_solve_ws(GridP G, Solve
         const bool prod_skip = SKIP && __builtin_amdgcn_readfirstlane(*nonfinite) != serial;
         while (!lost) {
             if (next >= c1) {
-                unsigned b = 0;
-                if (lane == 0) b = atomicAdd(cursor + CUR_ALL, (unsigned)S.chunk);
-                b = (unsigned)__builtin_amdgcn_readfirstlane((int)b);
-                if ((long long)b >= total) break;
-                next = b;
-                c1 = min(total, (long long)b + S.chunk);
+                if (ranges) {
+                    bool got = false;
+                    while (alive < N_XCD) {
+                        const int j = (home + alive) & (N_XCD - 1);
+                        unsigned b = 0;
+                        if (lane == 0) b = atomicAdd(cursor + CUR_XCD + j, (unsigned)S.chunk);
+                        b = (unsigned)__builtin_amdgcn_readfirstlane((int)b);
+                        const long long r1 = min(total, (j + 1) * per), at = j * per + (long long)b;
+                        if ((long long)b < per && at < r1) {
+                            next = at;
+                            c1 = min(r1, at + S.chunk);
+                            got = true;
+                            break;
+                        }
+                        ++alive;
+                    }
+                    if (!got) break;
+                } else {
+                    unsigned b = 0;
+                    if (lane == 0) b = atomicAdd(cursor + CUR_ALL, (unsigned)S.chunk);
+                    b = (unsigned)__builtin_amdgcn_readfirstlane((int)b);
+                    if ((long long)b >= total) break;
+                    next = b;
+                    c1 = min(total, (long long)b + S.chunk);
+                }
             }
             const long long pq = next + lane;
             next += min(64ll, c1 - next);
@@ -1556,11 +1631,11 @@ __global__ __launch_bounds__(64 * (NCONS + 1), 2) void k_solve_ws(GridP G, Solve
 
 // a[0..n) = 0; `cursors` (may be null): the solve kernels' work cursor is reset on the way (as k_reset_cursor does)
 __global__ void k_fill_zero_i32(long long n, int *__restrict__ a, unsigned *__restrict__ cursors = nullptr,
-                                unsigned value = 0u)
+                                unsigned nblocks = 0u, unsigned chunk = 0u)
 {
     long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     const long long stride = (long long)gridDim.x * blockDim.x;
-    if (cursors && i == 0) cursors[CUR_ALL] = value;
+    if (cursors && i < N_XCD) reset_cursors(cursors, (int)i, nblocks, chunk);
     for (; i < n; i += stride) a[i] = 0;
 }
 
@@ -2023,11 +2098,10 @@ __global__ __launch_bounds__(256) void k_grad_nodes_z(GridP G, int ncell, const 
             if (a != b) grad_cell_pair<false, true>(G, rec, a, b, ab, cx, cy, iz - 1, up, acc);
         }
     }
-    if (!valid) return;
-    float4 *o = reinterpret_cast<float4 *>(GT + i * 12);
-    o[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
-    o[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
-    o[2] = make_float4(acc[8], acc[9], acc[10], acc[11]);
+    // the block's 256 records are contiguous: they leave as whole cache lines
+    __shared__ float s_tile[256 * 12];
+    const long long i0 = (long long)blockIdx.x * blockDim.x;
+    block_store_rows<12>(GT + i0 * 12, acc, (int)min(256ll, (long long)G.P * G.V - i0), s_tile);
 }
 
 // gW[v][b] = sum_p sum_e G_T[p][v][e] B[p][b][e]: one thread per node and group of 8 bones (groups of a node

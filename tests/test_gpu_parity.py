@@ -607,7 +607,7 @@ def test_list_order_does_not_change_results(lib):
     run = gu.GpuRun(w)
     T = run.precompute()
     outs = []
-    for by_place in (1, 0, 1):
+    for by_place in (1, 0, 2, 1):
         run.ctx.set_list_order(by_place)
         xc, cv, Jo, it = run.solve(fused=True, slots=True)
         outs.append((xc, cv, Jo, it))
