@@ -338,7 +338,9 @@ def main():
         if issued is not None:
             # loads the kernel really issues (rocprofv3 TCP_TOTAL_CACHE_ACCESSES, profiles/): fewer than the algorithmic
             # 24 per evaluation, since a lane that stays in its grid cell keeps the 8 records in registers
-            gp.update({"issued_16B_loads_per_launch": issued, "issued_16B_loads_per_s": issued / ks})
+            gp.update({"issued_16B_loads_per_launch": issued, "issued_16B_loads_per_s": issued / ks,
+                       # the vector cache of a CU takes one access (a 64-byte block) per clock: 256 CUs at 2.4 GHz
+                       "l1_accesses_per_clk_per_cu": issued / (ks * 2.4e9 * 256), "l1_peak_accesses_per_clk_per_cu": 1.0})
         out["roofline"].update({"measured_fma_tflops": binding.microbench(binding.MB_FMA) / 1e12, "gather_path": gp})
 
     if args.probe_copy_mib > 0:
