@@ -1804,6 +1804,9 @@ constexpr int PIECE_LOAD = PIECE_OWN / 64;         // ... per SIMD lane
 // Operand layout of that instruction: lane 16k+i supplies A[i][k] and B[k][i]; lane 16g+j receives
 // D[4g+q][j] in accumulator register q.
 constexpr int PIECE_ROW = 20;     // floats per staged record: 8 weights + 12 products
+#ifndef FS_PIECES_VALU
+#define FS_PIECES_VALU 0
+#endif
 typedef float v4f __attribute__((ext_vector_type(4)));
 
 __global__ __launch_bounds__(64 * PIECE_WAVES) void k_grad_pieces(GridP G, long long ncp, const int *__restrict__ offset, float *rec)
@@ -1904,6 +1907,31 @@ __global__ __launch_bounds__(64 * PIECE_WAVES) void k_grad_pieces(GridP G, long 
             const int ps = 64 * i + src, pe = ps + __shfl(len[i], src);
             // four groups per pass into four accumulators: their LDS reads are in flight together and no
             // MFMA waits for the one before it; records outside the piece enter as zeros
+#if FS_PIECES_VALU
+            // the same sums with vector FMAs, for comparison: lane (kq, col) takes rows 2 kq, 2 kq + 1 of column col
+            {
+                float a0 = 0.0f, a1 = 0.0f, b0 = 0.0f, b1 = 0.0f;
+                if (col < 12) {
+                    int t = ps;
+                    for (; t + 1 < pe; t += 2) {
+                        const float2 w0 = *reinterpret_cast<const float2 *>(sm + t * PIECE_ROW + 2 * kq);
+                        const float2 w1 = *reinterpret_cast<const float2 *>(sm + (t + 1) * PIECE_ROW + 2 * kq);
+                        const float p0 = sm[t * PIECE_ROW + 8 + col], p1 = sm[(t + 1) * PIECE_ROW + 8 + col];
+                        a0 = FS_FMA(w0.x, p0, a0); a1 = FS_FMA(w0.y, p0, a1);
+                        b0 = FS_FMA(w1.x, p1, b0); b1 = FS_FMA(w1.y, p1, b1);
+                    }
+                    if (t < pe) {
+                        const float2 w0 = *reinterpret_cast<const float2 *>(sm + t * PIECE_ROW + 2 * kq);
+                        const float p0 = sm[t * PIECE_ROW + 8 + col];
+                        a0 = FS_FMA(w0.x, p0, a0); a1 = FS_FMA(w0.y, p0, a1);
+                    }
+                    float *o = rec + (s + ps) * GREC + (2 * kq) * 12 + col;
+                    o[0] = a0 + b0;
+                    o[12] = a1 + b1;
+                }
+                continue;
+            }
+#endif
             v4f acc4[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) acc4[u] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
