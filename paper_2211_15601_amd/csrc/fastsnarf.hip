@@ -33,7 +33,7 @@ struct fs_ctx {
     float *GT;         // [P][V][12] gradient w.r.t. the transform grid (allocated on first fs_grad)
     // correspondence grid (voxel init)
     float *Y;          // [P][V][3]
-    unsigned *bb_ord;  // [P][6]
+    unsigned *bb_ord;  // [P][EXTENT_BLOCKS][6]: per-block extents of the node images (k_corr_extent)
     float *bbox;       // [P][6]
     int *cell_of;      // [P][V]
     int *count;        // [P*ncell + 1] counts, then offsets
@@ -331,7 +331,7 @@ fs_status fs_create(const fs_grid_desc *desc, const fs_params *params, void *hip
         CorrP &C = c->C;
         C.cx = params->corr_nx; C.cy = params->corr_ny; C.cz = params->corr_nz; C.ck = params->corr_k;
         C.ncell = C.cx * C.cy * C.cz;
-        ok = dev_alloc(&c->Y, P * V * 3) && dev_alloc(&c->bb_ord, P * 6) && dev_alloc(&c->bbox, P * 6) &&
+        ok = dev_alloc(&c->Y, P * V * 3) && dev_alloc(&c->bb_ord, P * EXTENT_BLOCKS * 6) && dev_alloc(&c->bbox, P * 6) &&
              dev_alloc(&c->cell_of, P * V) && dev_alloc(&c->count, P * C.ncell + 1) && dev_alloc(&c->fill, P * V) &&
              dev_alloc(&c->order, P * V) && dev_alloc(&c->cand, P * (size_t)C.ncell * C.ck) &&
              dev_alloc(&c->cinit, P * (size_t)C.ncell * C.ck * 4);
@@ -427,7 +427,7 @@ fs_status fs_precompute(fs_ctx *ctx, const float *d_W, const float *d_B)
     const bool voxel = ctx->prm.init_mode == FS_INIT_VOXEL;
     if (voxel) {
         const int ncp0 = G.P * ctx->C.ncell;
-        k_corr_reset<<<grid1d(ncp0 > G.P * 3 ? ncp0 : G.P * 3, 256), 256, 0, st>>>(G.P, ctx->C.ncell, ctx->bb_ord, ctx->count);
+        k_corr_reset<<<grid1d(ncp0, 256), 256, 0, st>>>(G.P, ctx->C.ncell, ctx->count);
     }
     k_precompute<<<grid1d(G.V, 256), 256, 0, st>>>(G, d_W, d_B, ctx->T, ctx->Bdev, ctx->Binv, ctx->Bok,
                                                    reinterpret_cast<int *>(ctx->cursor + CUR_NONFINITE), ctx->pre_serial,
@@ -436,8 +436,9 @@ fs_status fs_precompute(fs_ctx *ctx, const float *d_W, const float *d_B)
         const CorrP &C = ctx->C;
         const int ncp = G.P * C.ncell;
         const dim3 gv(grid1d(G.V, 256), G.P);
-        k_corr_extent<<<dim3(std::min(grid1d(G.V, 256), 256), G.P), 256, 0, st>>>(G, ctx->Y, ctx->bb_ord);
-        k_corr_bbox<<<1, 64 * ((G.P * 6 + 63) / 64), 0, st>>>(G.P, ctx->bb_ord, ctx->bbox);
+        const int eblk = std::min(grid1d(G.V, 256), EXTENT_BLOCKS);
+        k_corr_extent<<<dim3(eblk, G.P), 256, 0, st>>>(G, ctx->Y, ctx->bb_ord);
+        k_corr_bbox<<<G.P, 384, 0, st>>>(eblk, ctx->bb_ord, ctx->bbox);
         k_corr_count<<<gv, 256, 0, st>>>(G, C, ctx->Y, ctx->bbox, ctx->cell_of, ctx->count, ctx->fill);
         { fs_status ss = scan_exclusive(ctx, ncp, ctx->count); if (ss != FS_OK) return ss; }
         k_corr_scatter<<<gv, 256, 0, st>>>(G, C, ctx->cell_of, ctx->count, ctx->fill, ctx->order);
@@ -742,6 +743,8 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
         k_grad_nodes_p<8><<<grid1d(nodes * 8, 256), 256, 0, st>>>(G, ncell, ctx->gcount, ctx->grec, ctx->GT);
     else
         k_grad_nodes_z<<<grid1d(nodes, 256), 256, 0, st>>>(G, ncell, ctx->gcount, ctx->grec, ctx->GT);
+    // (dL/dW on a second stream beside dL/dB, joined before the call returns: both kernels then take twice as long,
+    // 156 + 132 us instead of 77 + 79 on the 8-pose grid, and the step gains nothing.)
     k_grad_weights_node<<<grid1d(G.V * ((G.nb + 7) / 8), 256), 256, sizeof(float) * G.P * G.nb * 12, st>>>(G, ctx->GT, ctx->Bdev, d_gW);
     const int nout = G.nb * 12, nparts = ctx->gb_blocks * 4;
     const dim3 gbg(ctx->gb_blocks, (G.P + GB_POSES - 1) / GB_POSES);

@@ -244,16 +244,20 @@ __global__ __launch_bounds__(256) void k_init_voxel(GridP G, CorrP C, const floa
 // ------------------------------------------------------------------------------------------------
 // Correspondence grid build (voxel-based initialisation).
 // ------------------------------------------------------------------------------------------------
-__global__ void k_corr_reset(int P, int ncell, unsigned *__restrict__ bb_ord, int *__restrict__ count)
+__global__ void k_corr_reset(int P, int ncell, int *__restrict__ count)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < P * 3) { bb_ord[(i / 3) * 6 + i % 3] = 0xffffffffu; bb_ord[(i / 3) * 6 + 3 + i % 3] = 0u; }
     if (i < P * ncell) count[i] = 0;
     if (i == 0) count[P * ncell] = 0;
 }
 
-// bounding box per pose of the images of all nodes (grid-stride; one set of atomics per block)
-__global__ __launch_bounds__(256) void k_corr_extent(GridP G, const float *__restrict__ Y, unsigned *__restrict__ bb_ord)
+// Bounding box per pose of the images of all nodes, in two steps without atomics: every block leaves the extent of its
+// share of the nodes in bb_part[p][block][6] (ordered-integer images of the floats: min x, y, z, max x, y, z), then one
+// wave per pose and entry reduces the blocks' values.  (With atomicMin / atomicMax on the 6 words of a pose -- all in
+// one cache line -- the atomics were the cost of the kernel: about 3 ns each, 37 of its 40 us on the 8-pose grid with
+// 256 blocks per pose, 145 us with 1024.)
+constexpr int EXTENT_BLOCKS = 512;      // blocks per pose at most
+__global__ __launch_bounds__(256) void k_corr_extent(GridP G, const float *__restrict__ Y, unsigned *__restrict__ bb_part)
 {
     __shared__ unsigned smn[4][3], smx[4][3];
     const int p = blockIdx.y;
@@ -283,15 +287,28 @@ __global__ __launch_bounds__(256) void k_corr_extent(GridP G, const float *__res
     __syncthreads();
     if (threadIdx.x < 3) {
         const int a = threadIdx.x;
-        atomicMin(bb_ord + p * 6 + a, min(min(smn[0][a], smn[1][a]), min(smn[2][a], smn[3][a])));
-        atomicMax(bb_ord + p * 6 + 3 + a, max(max(smx[0][a], smx[1][a]), max(smx[2][a], smx[3][a])));
+        unsigned *o = bb_part + ((long long)p * gridDim.x + blockIdx.x) * 6;
+        o[a] = min(min(smn[0][a], smn[1][a]), min(smn[2][a], smn[3][a]));
+        o[3 + a] = max(max(smx[0][a], smx[1][a]), max(smx[2][a], smx[3][a]));
     }
 }
 
-__global__ void k_corr_bbox(int P, const unsigned *__restrict__ bb_ord, float *__restrict__ bbox)
+// one block of 6 waves per pose: wave e reduces entry e over the nblk blocks of k_corr_extent
+__global__ __launch_bounds__(384) void k_corr_bbox(int nblk, const unsigned *__restrict__ bb_part, float *__restrict__ bbox)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < P * 6) bbox[i] = ord2f(bb_ord[i]);
+    const int p = blockIdx.x, e = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const bool is_min = e < 3;
+    unsigned r = is_min ? 0xffffffffu : 0u;
+    for (int b = lane; b < nblk; b += 64) {
+        const unsigned t = bb_part[((long long)p * nblk + b) * 6 + e];
+        r = is_min ? min(r, t) : max(r, t);
+    }
+#pragma unroll
+    for (int sft = 32; sft >= 1; sft >>= 1) {
+        const unsigned o = (unsigned)__shfl_xor((int)r, sft);
+        r = is_min ? min(r, o) : max(r, o);
+    }
+    if (lane == 0) bbox[p * 6 + e] = ord2f(r);
 }
 
 // Neighbouring nodes have neighbouring images, so the 64 nodes of a wave fall into a handful of cells: the
@@ -2180,6 +2197,10 @@ __global__ __launch_bounds__(256) void k_grad_weights_node(GridP G, const float 
 // W^T, B = 4 nodes x 12 entries of G_T), up to 8 poses against the same weights; a block of 4 waves writes one
 // partial result [n_b][12] per pose (part[p][block]) and k_grad_bones_final adds the partials.  MT = number of 16-bone tiles.
 constexpr int GB_POSES = 8;
+#ifndef FS_GB_QUADS
+#define FS_GB_QUADS 4
+#endif
+constexpr int GB_QUADS = FS_GB_QUADS;
 template <int MT>
 __global__ __launch_bounds__(256) void k_grad_bones_mfma(GridP G, const float *__restrict__ W,
                                                          const float *__restrict__ GT, float *__restrict__ part,
@@ -2196,29 +2217,28 @@ __global__ __launch_bounds__(256) void k_grad_bones_mfma(GridP G, const float *_
     for (int pc = 0; pc < GB_POSES; ++pc)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[pc][mt] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
-    // two node quads per pass: their loads are in flight together
-    for (long long q = wave; q < quads; q += 2ll * nparts) {
-        const long long v = q * 4 + kq, v2 = (q + nparts) * 4 + kq;
-        const bool inv = v < G.V, inv2 = v2 < G.V;
-        float a[MT], a2[MT], bv[GB_POSES], bv2[GB_POSES];
+    // GB_QUADS node quads per pass: their loads are in flight together
+    for (long long q = wave; q < quads; q += (long long)GB_QUADS * nparts) {
+        float a[GB_QUADS][MT], bv[GB_QUADS][GB_POSES];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            a[mt] = (inv && mt * 16 + col < G.nb) ? W[v * G.nb + mt * 16 + col] : 0.0f;
-            a2[mt] = (inv2 && mt * 16 + col < G.nb) ? W[v2 * G.nb + mt * 16 + col] : 0.0f;
-        }
+        for (int u = 0; u < GB_QUADS; ++u) {
+            const long long v = (q + (long long)u * nparts) * 4 + kq;
+            const bool inv = v < G.V;
 #pragma unroll
-        for (int pc = 0; pc < GB_POSES; ++pc) {
-            bv[pc] = (pc < np && inv && col < 12) ? GT[((long long)(p0 + pc) * G.V + v) * 12 + col] : 0.0f;
-            bv2[pc] = (pc < np && inv2 && col < 12) ? GT[((long long)(p0 + pc) * G.V + v2) * 12 + col] : 0.0f;
+            for (int mt = 0; mt < MT; ++mt)
+                a[u][mt] = (inv && mt * 16 + col < G.nb) ? W[v * G.nb + mt * 16 + col] : 0.0f;
+#pragma unroll
+            for (int pc = 0; pc < GB_POSES; ++pc)
+                bv[u][pc] = (pc < np && inv && col < 12) ? GT[((long long)(p0 + pc) * G.V + v) * 12 + col] : 0.0f;
         }
 #pragma unroll
         for (int pc = 0; pc < GB_POSES; ++pc) {
             if (pc < np) {
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    acc[pc][mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[mt], bv[pc], acc[pc][mt], 0, 0, 0);
-                    acc[pc][mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[mt], bv2[pc], acc[pc][mt], 0, 0, 0);
-                }
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int u = 0; u < GB_QUADS; ++u)
+                        acc[pc][mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u][mt], bv[u][pc], acc[pc][mt], 0, 0, 0);
             }
         }
     }
