@@ -728,12 +728,16 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
         const int groups = N >= (1 << 19) ? 1 : (K >= 8 ? 8 : (K >= 4 ? 4 : (K >= 2 ? 2 : 1)));
         const dim3 rg(grid1d(N, 256 / groups));
         float4 *grec4 = reinterpret_cast<float4 *>(ctx->grec);
-        if (from_rec)   // the solve's own result records are still in the context: one 64-byte read per pair
-            k_grad_records<true><<<rg, 256, 0, st>>>(G, mode, ctx->T, d_xc, d_Jinv, d_conv, d_gxc, d_pose, N, K, ncell, ctx->gcount, pos,
-                                                    grec4, d_gxq, groups, ctx->srec, ctx->slots_list ? ctx->vcnt : nullptr);
-        else
-            k_grad_records<false><<<rg, 256, 0, st>>>(G, mode, ctx->T, d_xc, d_Jinv, d_conv, d_gxc, d_pose, N, K, ncell, ctx->gcount, pos,
-                                                     grec4, d_gxq, groups, nullptr, nullptr);
+#define FS_LAUNCH_RECORDS(R, E)                                                                                       \
+    k_grad_records<R, E><<<rg, 256, 0, st>>>(G, ctx->T, d_xc, d_Jinv, d_conv, d_gxc, d_pose, N, K, ncell, ctx->gcount, pos, \
+                                             grec4, d_gxq, groups, (R) ? ctx->srec : nullptr,                          \
+                                             ((R) && ctx->slots_list) ? ctx->vcnt : nullptr)
+        // from_rec: the solve's own result records are still in the context: one 64-byte read per pair
+        if (from_rec && mode != 0) FS_LAUNCH_RECORDS(true, true);
+        else if (from_rec) FS_LAUNCH_RECORDS(true, false);
+        else if (mode != 0) FS_LAUNCH_RECORDS(false, true);
+        else FS_LAUNCH_RECORDS(false, false);
+#undef FS_LAUNCH_RECORDS
     }
     if (N > 0) k_grad_pieces<<<grid1d((long long)lanes, PIECE_R), 64 * PIECE_WAVES, 0, st>>>(G, ncp, ctx->gcount, ctx->grec);
     // crowded grids: one thread per (node, adjacent cell); sparse ones: one thread per node, which walks the 4 cells at

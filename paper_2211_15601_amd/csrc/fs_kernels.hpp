@@ -1682,8 +1682,10 @@ constexpr int GREC = 8;           // floats per record
 // FROM_REC: roots, masks, J~ and positions are taken from the result records the last solve left in the
 // context (one contiguous 64-byte record per pair) instead of the caller's arrays; when that solve drew its
 // pairs from the candidate list, only the first cand_cnt[n] lanes of point n have a record.
-template <bool FROM_REC>
-__global__ __launch_bounds__(256) void k_grad_records(GridP G, int mode, const float *__restrict__ T,
+// EXACT: lambda from the inverse of the exact Jacobian at x* (mode != 0) instead of J~; a kernel of its own so that
+// the J~ path does not carry the registers of a field evaluation (117 -> what the compiler reports now).
+template <bool FROM_REC, bool EXACT>
+__global__ __launch_bounds__(256) void k_grad_records(GridP G, const float *__restrict__ T,
                                                       const float *__restrict__ xc, const float *__restrict__ Jinv,
                                                       const uint8_t *__restrict__ conv, const float *__restrict__ gxc,
                                                       const int32_t *__restrict__ pose, long long N, int K, int ncell,
@@ -1710,13 +1712,13 @@ __global__ __launch_bounds__(256) void k_grad_records(GridP G, int mode, const f
                 if (!(__float_as_int(a.w) & 1)) continue;
                 x[0] = a.x; x[1] = a.y; x[2] = a.z;
                 pq = __float_as_int(srec[q * 4 + 1].x);      // the position the solve kernel left in the record
-                if (mode == 0) read_record_J(srec + q * 4, M);
+                if (!EXACT) read_record_J(srec + q * 4, M);
             } else {
                 if (!conv[q]) continue;
 #pragma unroll
                 for (int r = 0; r < 3; ++r) x[r] = xc[((long long)k * 3 + r) * N + n];
                 pq = pos[q];
-                if (mode == 0) {
+                if (!EXACT) {
 #pragma unroll
                     for (int e = 0; e < 9; ++e) M[e] = Jinv[((long long)k * 9 + e) * N + n];
                 }
@@ -1724,7 +1726,7 @@ __global__ __launch_bounds__(256) void k_grad_records(GridP G, int mode, const f
 #pragma unroll
             for (int r = 0; r < 3; ++r) gx[r] = gxc[((long long)k * 3 + r) * N + n];
             bool ok = true;
-            if (mode != 0) {
+            if (EXACT) {
                 float d[3], J[9];
                 field_dJ(T + (long long)p * G.V * 12, G, x, d, J);
                 ok = inv3(J, M);
