@@ -39,7 +39,7 @@ BYTES_EVAL = 384     # ... = 8 x 48 bytes gathered per field evaluation
 PEAK_FP32_TFLOPS = 157.3            # published fp32 vector peak (needs packed fp32 instructions)
 PEAK_FP32_UNPACKED_TFLOPS = 78.6    # 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz: one FMA per lane per clock
 PEAK_HBM_BPS = 8.0e12
-LDS_GRID_MAX = 60 * 1024            # transform grids (all poses) up to this size are held in LDS by k_solve
+LDS_GRID_MAX = 148 * 1024           # transform grids (all poses) up to this size are held in LDS by k_solve
 
 
 def profile_value(cfg, key):

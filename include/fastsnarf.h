@@ -93,7 +93,7 @@ fs_status fs_set_params(fs_ctx *ctx, const fs_params *params);
  * voxel-based candidates on a grid of at most 32 MiB, or holds the grid in LDS); for these a value of 0
  * keeps the current setting.  point_major = 1: consecutive SIMD
  * lanes take the K initial states of one point, 0: consecutive points with the same initial state,
- * -1: keep.  lds_grid = 1: transform grids of at most 60 KiB (all poses) are copied into LDS by every
+ * -1: keep.  lds_grid = 1: transform grids of at most 148 KiB (all poses; blocks of 4 waves up to 60 KiB, above that one block of 12 waves per CU) are copied into LDS by every
  * block of the solve and read from there, 0: always read through the caches, -1: keep. */
 fs_status fs_set_tuning(fs_ctx *ctx, int32_t chunk, int32_t refill_min, int32_t blocks_per_cu, int32_t point_major,
                         int32_t lds_grid);

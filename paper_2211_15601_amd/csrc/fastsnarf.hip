@@ -64,6 +64,7 @@ struct fs_ctx {
     size_t vhist_cap;
     int scan_cap;      // tiles scan_sums can hold
     int n_cus, occ_blocks_per_cu, occ_ws_blocks_per_cu, occ_vx_blocks_per_cu, chunk, refill_min, blocks_per_cu, point_major, lds_grid;
+    bool lds_big;      // the grid is larger than 60 KiB and fits the LDS of a CU as one block of 12 waves
     int sort_list;     // order the list of (point, candidate) pairs by place (large voxel-mode batches)
     int xcd_ranges;    // with an ordered list: one range of it, and one cursor, per XCD
     int spin_limit;    // polls for room in its consumers' queues before the producer wave of a solve block gives up
@@ -242,6 +243,9 @@ int *scratch_on_device(fs_ctx *c)
 // largest transform grid (all poses) kept in LDS by the solve: a block may ask for 64 KiB in all, and k_solve has 4 KiB of
 // its own (the parked cell-position requests of its four waves)
 constexpr size_t FS_LDS_GRID_MAX = 60 * 1024;
+// ... by one block of 12 waves per CU: the CU's 160 KiB less the 12 KiB of parked requests of those waves
+constexpr int FS_LDS_BIG_WAVES = 12;
+constexpr size_t FS_LDS_GRID_MAX_BIG = 148 * 1024;
 
 int lanes_K(const fs_ctx *c) { return c->prm.init_mode == FS_INIT_BONE ? c->desc.n_bones : c->prm.corr_k; }
 
@@ -308,7 +312,22 @@ fs_status fs_create(const fs_grid_desc *desc, const fs_params *params, void *hip
         int per_cu_ws = 0;
         // resident blocks of the LDS-grid kernel with the LDS this context's grid needs (the grid's size never changes)
         const size_t gb = (size_t)desc->n_poses * V * 48;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_solve<true, true>, 256, gb <= FS_LDS_GRID_MAX ? gb : 0) != hipSuccess || per_cu < 1) per_cu = 1;
+        if (gb > FS_LDS_GRID_MAX && gb <= FS_LDS_GRID_MAX_BIG) {
+            // the device must grant one block that much LDS; else the grid is read through the caches
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_solve<true, true, FS_LDS_BIG_WAVES>, 64 * FS_LDS_BIG_WAVES, gb) != hipSuccess) per_cu = 0;
+            c->lds_big = per_cu >= 1;
+            (void)hipGetLastError();
+            if (c->lds_big) {       // more dynamic LDS than the default limit of a block: say so for every variant
+                const void *fns[] = {(const void *)k_solve<true, true, FS_LDS_BIG_WAVES>, (const void *)k_solve<true, false, FS_LDS_BIG_WAVES>,
+                                     (const void *)k_solve<false, true, FS_LDS_BIG_WAVES>, (const void *)k_solve<false, false, FS_LDS_BIG_WAVES>};
+                for (const void *f : fns)
+                    if (hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gb) != hipSuccess) {
+                        (void)hipGetLastError();
+                        c->lds_big = false;
+                    }
+            }
+            per_cu = 1;
+        } else if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_solve<true, true>, 256, gb <= FS_LDS_GRID_MAX ? gb : 0) != hipSuccess || per_cu < 1) per_cu = 1;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_ws, k_solve_ws<true, true, FS_WS_CONSUMERS, false>, 64 * (FS_WS_CONSUMERS + 1), 0) != hipSuccess || per_cu_ws < 1) per_cu_ws = 2;
         c->occ_ws_blocks_per_cu = per_cu_ws;
         int per_cu_vx = 0;
@@ -513,7 +532,8 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     S.spin_limit = ctx->spin_limit;
     const long long chunks = (S.total + S.chunk - 1) / S.chunk;
     const size_t grid_bytes = (size_t)ctx->G.P * ctx->G.V * 48;
-    const bool lds = ctx->lds_grid && grid_bytes <= FS_LDS_GRID_MAX;
+    const bool lds_big = ctx->lds_grid && ctx->lds_big && grid_bytes > FS_LDS_GRID_MAX && grid_bytes <= FS_LDS_GRID_MAX_BIG;
+    const bool lds = (ctx->lds_grid && grid_bytes <= FS_LDS_GRID_MAX) || lds_big;
     // Launch shape.  Grid in LDS (k_solve): latency / ALU bound, every wave the registers allow, refill at 32 idle
     // lanes.  Grid read through the caches (k_solve_ws, bound by the vector-memory path): blocks of one producer and
     // several consumers, 2 blocks per CU (measured: more waves that compute Eq. (8) only thrash the L1); consumers
@@ -521,11 +541,11 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     const bool voxel_list = fused && ctx->prm.init_mode == FS_INIT_VOXEL;     // the solve draws from the list of pairs that have a candidate
     // fused voxel-based candidates: the producer only looks initial states up (k_corr_init computed them once per pose)
     const bool vx = !lds && voxel_list;
-    const int wpb = lds ? 4 : 1;       // waves of a block that draw chunks from the cursor
+    const int wpb = lds_big ? FS_LDS_BIG_WAVES : (lds ? 4 : 1);       // waves of a block that draw chunks from the cursor
     const int auto_blocks = lds ? 3 : 2;
     const int want_blocks = ctx->blocks_per_cu ? (lds ? std::max(ctx->blocks_per_cu, 3) : ctx->blocks_per_cu) : auto_blocks;
     const int occ = lds ? ctx->occ_blocks_per_cu : (vx ? ctx->occ_vx_blocks_per_cu : ctx->occ_ws_blocks_per_cu);
-    const int per_cu = std::max(1, std::min(want_blocks, occ));
+    const int per_cu = lds_big ? 1 : std::max(1, std::min(want_blocks, occ));
     S.refill_min = ctx->refill_min ? ctx->refill_min : (lds ? 32 : 8);
     const int blocks = (int)std::min<long long>(grid1d(chunks, wpb), (long long)per_cu * ctx->n_cus);
     InitP I;
@@ -611,14 +631,21 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     if (ctx->timing && hipEventCreate(&ev0) == hipSuccess && hipEventCreate(&ev1) == hipSuccess) (void)hipEventRecord(ev0, st);
     if (lds) {
-#define FS_LAUNCH_SOLVE(F, J)                                                                                          \
-    k_solve<F, J><<<dim3(blocks), dim3(4 * WAVE), grid_bytes, st>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, d_x0, d_Jinv0, \
-                                                                    d_valid0, ctx->srec, ctx->cursor, list, list_len,  \
-                                                                    cell_count, ncell)
-        if (fused && with_J) FS_LAUNCH_SOLVE(true, true);
-        else if (fused) FS_LAUNCH_SOLVE(true, false);
-        else if (with_J) FS_LAUNCH_SOLVE(false, true);
-        else FS_LAUNCH_SOLVE(false, false);
+#define FS_LAUNCH_SOLVE(F, J, NW)                                                                                      \
+    k_solve<F, J, NW><<<dim3(blocks), dim3(NW * WAVE), grid_bytes, st>>>(ctx->G, S, I, ctx->T, d_xq, d_pose, d_x0,     \
+                                                                         d_Jinv0, d_valid0, ctx->srec, ctx->cursor,    \
+                                                                         list, list_len, cell_count, ncell)
+        if (lds_big) {
+            if (fused && with_J) FS_LAUNCH_SOLVE(true, true, FS_LDS_BIG_WAVES);
+            else if (fused) FS_LAUNCH_SOLVE(true, false, FS_LDS_BIG_WAVES);
+            else if (with_J) FS_LAUNCH_SOLVE(false, true, FS_LDS_BIG_WAVES);
+            else FS_LAUNCH_SOLVE(false, false, FS_LDS_BIG_WAVES);
+        } else {
+            if (fused && with_J) FS_LAUNCH_SOLVE(true, true, 4);
+            else if (fused) FS_LAUNCH_SOLVE(true, false, 4);
+            else if (with_J) FS_LAUNCH_SOLVE(false, true, 4);
+            else FS_LAUNCH_SOLVE(false, false, 4);
+        }
 #undef FS_LAUNCH_SOLVE
     } else {
 #define FS_LAUNCH_SOLVE(F, J, NC, Z)                                                                                   \

@@ -803,8 +803,10 @@ __device__ __forceinline__ void flush_slots(int (&pend)[2][PEND], int npend, int
 // writing the caller's structure-of-arrays layout from here would touch 14 cache lines per pair with
 // 4 bytes each); k_solve_unpack then moves the records into that layout with coalesced stores.
 // (record layout: see write_record).
-template <bool FUSED, bool WITH_J>
-__global__ __launch_bounds__(256, 3) void k_solve(GridP G, SolveP S, InitP I, const float *__restrict__ Tglobal,
+// NW = waves per block.  4: grids of up to 60 KiB, three blocks per CU, each with its own copy.  12: larger grids, up
+// to what one block may hold of the CU's 160 KiB: one block per CU, the same 3 waves per SIMD, one copy.
+template <bool FUSED, bool WITH_J, int NW = 4>
+__global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 1) void k_solve(GridP G, SolveP S, InitP I, const float *__restrict__ Tglobal,
                                                const float *__restrict__ xq, const int32_t *__restrict__ pose,
                                                const float *__restrict__ x0, const float *__restrict__ J0,
                                                const uint8_t *__restrict__ valid0, float4 *__restrict__ rec,
@@ -814,7 +816,7 @@ __global__ __launch_bounds__(256, 3) void k_solve(GridP G, SolveP S, InitP I, co
 {
     extern __shared__ float4 s_grid[];
     // converged lanes waiting for their position in their grid cell's list: {cell, pair} per wave
-    __shared__ int s_pend[4][2][PEND];
+    __shared__ int s_pend[NW][2][PEND];
     {
         const int n4 = (int)((long long)G.P * G.V * 3);      // float4 per record: 3
         const float4 *src = reinterpret_cast<const float4 *>(Tglobal);

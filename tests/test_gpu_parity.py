@@ -325,15 +325,17 @@ def test_autograd_hook_matches_oracle_gradient(lib):
 
 @pytest.mark.parametrize("shape", [((2, 2, 2), 1, 1, 40), ((5, 4, 3), 5, 3, 1000), ((7, 3, 9), 17, 2, 777),
                                    ((4, 6, 5), 33, 1, 513), ((3, 3, 3), 64, 2, 300), ((9, 8, 7), 3, 4, 20011),
-                                   ((8, 10, 16), 6, 1, 4099), ((8, 10, 16), 5, 2, 1500)],
+                                   ((8, 10, 16), 6, 1, 4099), ((8, 10, 16), 5, 2, 1500), ((16, 16, 8), 24, 1, 5000),
+                                   ((13, 15, 16), 4, 1, 3001), ((13, 15, 17), 4, 1, 1200)],
                          ids=lambda t: f"g{t[0]}-b{t[1]}-p{t[2]}-n{t[3]}")
 @pytest.mark.parametrize("lds_grid", [1, 0], ids=["grid_in_lds", "grid_cached"])
 def test_odd_shapes_full_path(lib, shape, lds_grid):
     # bone counts on both sides of the 16-bone MFMA tiles and of the 4-wide weight reads, grids down to one cell,
     # several poses, ragged N: transform grid, solve (both solve kernels: the one that holds these small grids
     # in LDS, and the producer / consumer one that reads them through the caches) and both gradient paths
-    # against the oracle.  8 x 10 x 16 nodes x 1 pose = 60 KiB is the largest grid the LDS kernel takes (one block per
-    # CU at that size); with 2 poses it is twice that and goes through the caches whatever lds_grid says
+    # against the oracle.  8 x 10 x 16 nodes x 1 pose = 60 KiB is the largest grid that blocks of 4 waves hold in LDS;
+    # with 2 poses (120 KiB), as 16 x 16 x 8 (96 KiB) and 13 x 15 x 16 (146.25 KiB, just under the limit of 148) one
+    # block of 12 waves per CU holds it; 13 x 15 x 17 is too large and goes through the caches whatever lds_grid says
     dims, nb, P, n = shape
     s = wl.random_affine_scene(100 + nb, dims=dims, n_bones=nb, n_poses=P, n_points=n)
     w = wl.Workload("odd", s["dims"], nb, P, s["lo"], s["hi"], s["W"], s["B"], s["x"], s["pose"], s["x"],
