@@ -2045,6 +2045,38 @@ __global__ __launch_bounds__(256) void k_grad_nodes_p(GridP G, int ncell, const 
 // What the records of cell (cx, cy, cz), list entries [a, b), add to the two nodes at its (x, y) corner `ab`
 // (= a + 2b): `lo` is the node at cz, `hi` the one at cz + 1.  Pieces that k_grad_pieces replaced by their corner
 // sums enter as those sums.  Either output may be switched off.
+// one record {x*, lambda} of the cell with origin (cx, cy, cz): its share for the cell's (x, y) corner `ab` at the lower
+// z (into lo) and at the upper z (into hi)
+template <bool LO, bool HI>
+__device__ __forceinline__ void grad_record_pair(const GridP &G, const float4 r0, const float4 r1, int ab, int cx, int cy,
+                                                 int cz, float (&lo)[12], float (&hi)[12])
+{
+    const float x[3] = {r0.x, r0.y, r0.z};
+    const float lam[3] = {r0.w, r1.x, r1.y};
+    const float fx = frac_in_cell(x[0], G.lo[0], G.inv_h[0], G.m[0], cx);
+    const float fy = frac_in_cell(x[1], G.lo[1], G.inv_h[1], G.m[1], cy);
+    const float fz = frac_in_cell(x[2], G.lo[2], G.inv_h[2], G.m[2], cz);
+    const float wxy = ((ab & 1) ? fx : 1.0f - fx) * ((ab & 2) ? fy : 1.0f - fy);
+    const float w0 = wxy * (1.0f - fz), w1 = wxy * fz;
+#pragma unroll
+    for (int rr = 0; rr < 3; ++rr) {
+        if (LO) {
+            const float wl = w0 * lam[rr];
+            lo[rr * 4 + 0] = FS_FMA(wl, x[0], lo[rr * 4 + 0]);
+            lo[rr * 4 + 1] = FS_FMA(wl, x[1], lo[rr * 4 + 1]);
+            lo[rr * 4 + 2] = FS_FMA(wl, x[2], lo[rr * 4 + 2]);
+            lo[rr * 4 + 3] += wl;
+        }
+        if (HI) {
+            const float wl = w1 * lam[rr];
+            hi[rr * 4 + 0] = FS_FMA(wl, x[0], hi[rr * 4 + 0]);
+            hi[rr * 4 + 1] = FS_FMA(wl, x[1], hi[rr * 4 + 1]);
+            hi[rr * 4 + 2] = FS_FMA(wl, x[2], hi[rr * 4 + 2]);
+            hi[rr * 4 + 3] += wl;
+        }
+    }
+}
+
 template <bool LO, bool HI>
 __device__ __forceinline__ void grad_cell_pair(const GridP &G, const float *__restrict__ rec, int a, int b, int ab, int cx,
                                                int cy, int cz, float (&lo)[12], float (&hi)[12])
@@ -2068,31 +2100,7 @@ __device__ __forceinline__ void grad_cell_pair(const GridP &G, const float *__re
         } else {
             for (int s = ps; s < pe; ++s) {
                 const float4 *r = reinterpret_cast<const float4 *>(rec + (long long)s * GREC);
-                const float4 r0 = r[0], r1 = r[1];
-                const float x[3] = {r0.x, r0.y, r0.z};
-                const float lam[3] = {r0.w, r1.x, r1.y};
-                const float fx = frac_in_cell(x[0], G.lo[0], G.inv_h[0], G.m[0], cx);
-                const float fy = frac_in_cell(x[1], G.lo[1], G.inv_h[1], G.m[1], cy);
-                const float fz = frac_in_cell(x[2], G.lo[2], G.inv_h[2], G.m[2], cz);
-                const float wxy = ((ab & 1) ? fx : 1.0f - fx) * ((ab & 2) ? fy : 1.0f - fy);
-                const float w0 = wxy * (1.0f - fz), w1 = wxy * fz;
-#pragma unroll
-                for (int rr = 0; rr < 3; ++rr) {
-                    if (LO) {
-                        const float wl = w0 * lam[rr];
-                        lo[rr * 4 + 0] = FS_FMA(wl, x[0], lo[rr * 4 + 0]);
-                        lo[rr * 4 + 1] = FS_FMA(wl, x[1], lo[rr * 4 + 1]);
-                        lo[rr * 4 + 2] = FS_FMA(wl, x[2], lo[rr * 4 + 2]);
-                        lo[rr * 4 + 3] += wl;
-                    }
-                    if (HI) {
-                        const float wl = w1 * lam[rr];
-                        hi[rr * 4 + 0] = FS_FMA(wl, x[0], hi[rr * 4 + 0]);
-                        hi[rr * 4 + 1] = FS_FMA(wl, x[1], hi[rr * 4 + 1]);
-                        hi[rr * 4 + 2] = FS_FMA(wl, x[2], hi[rr * 4 + 2]);
-                        hi[rr * 4 + 3] += wl;
-                    }
-                }
+                grad_record_pair<LO, HI>(G, r[0], r[1], ab, cx, cy, cz, lo, hi);
             }
         }
     }
@@ -2123,13 +2131,41 @@ __global__ __launch_bounds__(256) void k_grad_nodes_z(GridP G, int ncell, const 
 #pragma unroll
     for (int e = 0; e < 12; ++e) acc[e] = up[e] = 0.0f;
     if (valid && iz <= G.nz - 2) {
+        // Cells with fewer than PIECE_MIN records hold records only (no sums): those of the 4 cells are walked side by
+        // side, record j of each in one round, so that a round's loads travel together and the loop is as long as the
+        // longest of the four lists instead of their sum.  The other cells follow one by one.
+        int a[4], b[4];
+        bool small[4];
+        int rounds = 0;
+#pragma unroll
         for (int ab = 0; ab < 4; ++ab) {
             const int cx = ix - (ab & 1), cy = iy - (ab >> 1);
-            if (cx < 0 || cy < 0 || cx > G.nx - 2 || cy > G.ny - 2) continue;
-            const int c = p * ncell + (cx * (G.ny - 1) + cy) * (G.nz - 1) + iz;
-            const int a = offset[c], b = offset[c + 1];
-            if (a != b) grad_cell_pair<true, true>(G, rec, a, b, ab, cx, cy, iz, acc, up);
+            a[ab] = b[ab] = 0;
+            if (!(cx < 0 || cy < 0 || cx > G.nx - 2 || cy > G.ny - 2)) {
+                const int c = p * ncell + (cx * (G.ny - 1) + cy) * (G.nz - 1) + iz;
+                a[ab] = offset[c];
+                b[ab] = offset[c + 1];
+            }
+            small[ab] = b[ab] - a[ab] < PIECE_MIN;
+            if (small[ab]) rounds = max(rounds, b[ab] - a[ab]);
         }
+        for (int j = 0; j < rounds; ++j) {
+            float4 r0[4], r1[4];
+            bool on[4];
+#pragma unroll
+            for (int ab = 0; ab < 4; ++ab) {
+                on[ab] = small[ab] && a[ab] + j < b[ab];
+                const float4 *r = reinterpret_cast<const float4 *>(rec + (long long)(on[ab] ? a[ab] + j : 0) * GREC);
+                r0[ab] = r1[ab] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                if (on[ab]) { r0[ab] = r[0]; r1[ab] = r[1]; }
+            }
+#pragma unroll
+            for (int ab = 0; ab < 4; ++ab)
+                if (on[ab]) grad_record_pair<true, true>(G, r0[ab], r1[ab], ab, ix - (ab & 1), iy - (ab >> 1), iz, acc, up);
+        }
+#pragma unroll
+        for (int ab = 0; ab < 4; ++ab)
+            if (!small[ab]) grad_cell_pair<true, true>(G, rec, a[ab], b[ab], ab, ix - (ab & 1), iy - (ab >> 1), iz, acc, up);
     }
     // what the node below collected for this one (lane - 1 is node i - 1: the same column when iz > 0)
     const bool from_lane = lane > 0 && valid && iz > 0;
