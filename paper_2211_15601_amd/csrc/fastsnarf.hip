@@ -761,6 +761,9 @@ fs_status fs_grad(fs_ctx *ctx, const float *d_W, const float *d_xc, const float 
                                              ((R) && ctx->slots_list) ? ctx->vcnt : nullptr)
         // from_rec: the solve's own result records are still in the context: one 64-byte read per pair
         if (from_rec && mode != 0) FS_LAUNCH_RECORDS(true, true);
+        else if (from_rec && groups == 1)     // large batches: three lanes of a point in flight, stage by stage
+            k_grad_records<true, false, 3><<<rg, 256, 0, st>>>(G, ctx->T, d_xc, d_Jinv, d_conv, d_gxc, d_pose, N, K, ncell, ctx->gcount,
+                                                               pos, grec4, d_gxq, groups, ctx->srec, ctx->slots_list ? ctx->vcnt : nullptr);
         else if (from_rec) FS_LAUNCH_RECORDS(true, false);
         else if (mode != 0) FS_LAUNCH_RECORDS(false, true);
         else FS_LAUNCH_RECORDS(false, false);

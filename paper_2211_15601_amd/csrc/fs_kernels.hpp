@@ -1686,7 +1686,10 @@ constexpr int GREC = 8;           // floats per record
 // pairs from the candidate list, only the first cand_cnt[n] lanes of point n have a record.
 // EXACT: lambda from the inverse of the exact Jacobian at x* (mode != 0) instead of J~; a kernel of its own so that
 // the J~ path does not carry the registers of a field evaluation (117 -> what the compiler reports now).
-template <bool FROM_REC, bool EXACT>
+// REC_DEPTH (with FROM_REC and the J~ gradient only): lanes of a point in flight together, see below; 1 = one by one.
+// Measured: depth 3 takes k_grad_records from 425 to 376 us on the 8-pose batch (one thread per point) and from 41 to
+// 52 us on the SMPL-scale batch (8 threads per point, 5 instead of 8 waves per SIMD), hence a choice per launch.
+template <bool FROM_REC, bool EXACT, int REC_DEPTH = 1>
 __global__ __launch_bounds__(256) void k_grad_records(GridP G, const float *__restrict__ T,
                                                       const float *__restrict__ xc, const float *__restrict__ Jinv,
                                                       const uint8_t *__restrict__ conv, const float *__restrict__ gxc,
@@ -1705,6 +1708,66 @@ __global__ __launch_bounds__(256) void k_grad_records(GridP G, const float *__re
     if (n < N) {
         const int p = pose_of(pose, n, G.P);
         const int nk = (FROM_REC && cand_cnt) ? min(K, (int)cand_cnt[n]) : K;
+        if constexpr (FROM_REC && !EXACT && REC_DEPTH > 1) {
+            // REC_DEPTH lanes of the point at a time, stage by stage, so that the dependent loads of a stage (record head,
+            // rest of the record and g_x, cell offsets) travel together
+            for (int k0 = g; k0 < nk; k0 += REC_DEPTH * groups) {
+                float4 ra[REC_DEPTH], rb[REC_DEPTH], rc[REC_DEPTH], rd[REC_DEPTH];
+                float gx[REC_DEPTH][3];
+                bool on[REC_DEPTH];
+                long long q[REC_DEPTH];
+#pragma unroll
+                for (int u = 0; u < REC_DEPTH; ++u) {
+                    const int k = k0 + u * groups;
+                    on[u] = k < nk;
+                    q[u] = (long long)(on[u] ? k : 0) * N + n;
+                    ra[u] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                    if (on[u]) ra[u] = srec[q[u] * 4];
+                }
+#pragma unroll
+                for (int u = 0; u < REC_DEPTH; ++u) {
+                    on[u] = on[u] && (__float_as_int(ra[u].w) & 1);
+                    rb[u] = rc[u] = rd[u] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                    gx[u][0] = gx[u][1] = gx[u][2] = 0.0f;
+                    if (on[u]) {
+                        rb[u] = srec[q[u] * 4 + 1];
+                        rc[u] = srec[q[u] * 4 + 2];
+                        rd[u] = srec[q[u] * 4 + 3];
+                        const int k = k0 + u * groups;
+#pragma unroll
+                        for (int r = 0; r < 3; ++r) gx[u][r] = gxc[((long long)k * 3 + r) * N + n];
+                    }
+                }
+                float lam[REC_DEPTH][3];
+                int cl[REC_DEPTH], o0[REC_DEPTH], o1[REC_DEPTH];
+#pragma unroll
+                for (int u = 0; u < REC_DEPTH; ++u) {
+                    const float M[9] = {rb[u].y, rb[u].z, rb[u].w, rc[u].x, rc[u].y, rc[u].z, rc[u].w, rd[u].x, rd[u].y};
+                    const float x[3] = {ra[u].x, ra[u].y, ra[u].z};
+                    cl[u] = 0;
+                    o0[u] = o1[u] = 0;
+#pragma unroll
+                    for (int r = 0; r < 3; ++r) {
+                        lam[u][r] = -FS_FMA(M[6 + r], gx[u][2], FS_FMA(M[3 + r], gx[u][1], M[r] * gx[u][0]));
+                        if (on[u]) gq[r] -= lam[u][r];
+                    }
+                    if (on[u]) {
+                        const Cell c = locate(G, x);
+                        cl[u] = p * ncell + cell_linear(G, c);
+                        o0[u] = offset[cl[u]];
+                        o1[u] = offset[cl[u] + 1];
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < REC_DEPTH; ++u) {
+                    const int pq = __float_as_int(rb[u].x);      // the position the solve kernel left in the record
+                    const long long slot = (long long)o0[u] + pq;
+                    if (!on[u] || pq < 0 || slot >= o1[u]) continue;
+                    rec[slot * 2] = make_float4(ra[u].x, ra[u].y, ra[u].z, lam[u][0]);
+                    rec[slot * 2 + 1] = make_float4(lam[u][1], lam[u][2], __int_as_float(cl[u]), 0.0f);
+                }
+            }
+        } else
         for (int k = g; k < nk; k += groups) {
             const long long q = (long long)k * N + n;
             float x[3], gx[3], M[9];
@@ -2133,7 +2196,8 @@ __global__ __launch_bounds__(256) void k_grad_nodes_z(GridP G, int ncell, const 
     if (valid && iz <= G.nz - 2) {
         // Cells with fewer than PIECE_MIN records hold records only (no sums): those of the 4 cells are walked side by
         // side, record j of each in one round, so that a round's loads travel together and the loop is as long as the
-        // longest of the four lists instead of their sum.  The other cells follow one by one.
+        // longest of the four lists instead of their sum (two records of each cell per round: 309 instead of 270 us, the
+        // extra registers cost two of six waves per SIMD).  The other cells follow one by one.
         int a[4], b[4];
         bool small[4];
         int rounds = 0;
