@@ -40,6 +40,7 @@ struct fs_ctx {
     int *fill;         // [P][V] arrival slot of a node inside its cell
     int *order;        // [P][V]
     int32_t *cand;     // [P][ncell][ck]
+    uint8_t *ccnt;     // [P][ncell] number of candidates of a correspondence cell
     float4 *cinit;     // [P][ncell][ck][4] initial state of every candidate (k_corr_init)
     unsigned *cursor;  // work cursor of the solve kernel
     int *gcount;       // [P*ncells + 1] per-cell lane counts, then offsets (backward)
@@ -174,7 +175,7 @@ int grid1d(long long n, int block) { return (int)((n + block - 1) / block); }
 void free_all(fs_ctx *c)
 {
     void *ptrs[] = {c->T, c->Bdev, c->Binv, c->Bok, c->GT, c->Y, c->bb_ord, c->bbox,
-                    c->cell_of, c->count, c->fill, c->order, c->cand, c->cursor, c->gcount, c->gcount_solve, c->gpos, c->grec, c->scan_sums, c->srec, c->gpart, c->voffs, c->vlist, c->cinit, c->vcnt, c->vgcell, c->vhist};
+                    c->cell_of, c->count, c->fill, c->order, c->cand, c->cursor, c->gcount, c->gcount_solve, c->gpos, c->grec, c->scan_sums, c->srec, c->gpart, c->voffs, c->vlist, c->cinit, c->vcnt, c->vgcell, c->vhist, c->ccnt};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
 }
@@ -352,7 +353,7 @@ fs_status fs_create(const fs_grid_desc *desc, const fs_params *params, void *hip
         C.ncell = C.cx * C.cy * C.cz;
         ok = dev_alloc(&c->Y, P * V * 3) && dev_alloc(&c->bb_ord, P * EXTENT_BLOCKS * 6) && dev_alloc(&c->bbox, P * 6) &&
              dev_alloc(&c->cell_of, P * V) && dev_alloc(&c->count, P * C.ncell + 1) && dev_alloc(&c->fill, P * V) &&
-             dev_alloc(&c->order, P * V) && dev_alloc(&c->cand, P * (size_t)C.ncell * C.ck) &&
+             dev_alloc(&c->order, P * V) && dev_alloc(&c->cand, P * (size_t)C.ncell * C.ck) && dev_alloc(&c->ccnt, P * (size_t)C.ncell) &&
              dev_alloc(&c->cinit, P * (size_t)C.ncell * C.ck * 4);
     }
     if (ok) {
@@ -461,7 +462,7 @@ fs_status fs_precompute(fs_ctx *ctx, const float *d_W, const float *d_B)
         k_corr_count<<<gv, 256, 0, st>>>(G, C, ctx->Y, ctx->bbox, ctx->cell_of, ctx->count, ctx->fill);
         { fs_status ss = scan_exclusive(ctx, ncp, ctx->count); if (ss != FS_OK) return ss; }
         k_corr_scatter<<<gv, 256, 0, st>>>(G, C, ctx->cell_of, ctx->count, ctx->fill, ctx->order);
-        k_corr_select<<<grid1d((long long)ncp * WAVE, 256), 256, 0, st>>>(G, C, ctx->Y, ctx->bbox, ctx->count, ctx->order, ctx->cand);
+        k_corr_select<<<grid1d((long long)ncp * WAVE, 256), 256, 0, st>>>(G, C, ctx->Y, ctx->bbox, ctx->count, ctx->order, ctx->cand, ctx->ccnt);
         k_corr_init<<<grid1d((long long)ncp * C.ck, 256), 256, 0, st>>>(G, C, ctx->T, ctx->cand, ctx->cinit);
     }
     fs_status s = launch_status(ctx, "fs_precompute");
@@ -555,6 +556,7 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     I.C = ctx->C;
     I.bbox = ctx->bbox;
     I.cand = ctx->cand;
+    I.ccnt = ctx->ccnt;
     I.cinit = ctx->cinit;
     const bool with_J = d_Jinv != nullptr || d_slot != nullptr;     // with d_slot alone J~ stays in the result records
     const size_t need = (size_t)S.total * (with_J ? 4 : 1);
@@ -584,7 +586,7 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
                 return fail(ctx, FS_E_ALLOC, "fs_solve: out of device memory for the pair list");
             ctx->vcap = (size_t)N;
         }
-        k_voxel_count<<<grid1d(N, 256), 256, 0, st>>>(ctx->G, I, N, d_xq, d_pose, ctx->voffs, ctx->vcnt, ctx->vgcell);
+        k_voxel_count<<<grid1d(N, 256), 256, sizeof(float) * 6 * ctx->G.P, st>>>(ctx->G, I, N, d_xq, d_pose, ctx->voffs, ctx->vcnt, ctx->vgcell);
         // On request (fs_set_list_order) large batches are ordered by place (pose, then column of correspondence cells)
         // with a counting sort; small ones, or correspondence grids with more columns than the sort's LDS counters hold,
         // keep the order of the points.

@@ -464,7 +464,8 @@ __global__ __launch_bounds__(256) void k_corr_scatter(GridP G, CorrP C, const in
 // greedily.
 __global__ __launch_bounds__(256) void k_corr_select(GridP G, CorrP C, const float *__restrict__ Y,
                                                      const float *__restrict__ bbox, const int *__restrict__ offset,
-                                                     const int *__restrict__ order, int32_t *__restrict__ cand)
+                                                     const int *__restrict__ order, int32_t *__restrict__ cand,
+                                                     uint8_t *__restrict__ ccnt)
 {
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int lane = threadIdx.x & 63;
@@ -512,8 +513,10 @@ __global__ __launch_bounds__(256) void k_corr_select(GridP G, CorrP C, const flo
         ++na;
         if (lane == 0) out[j] = bv;
     }
-    if (lane == 0)
+    if (lane == 0) {
         for (int j = na; j < C.ck; ++j) out[j] = -1;
+        ccnt[wave] = (uint8_t)na;            // candidates of this cell (they are packed at the front)
+    }
 }
 
 // Initial state of every candidate of the correspondence grid, once per fs_precompute instead of once per pair: a
@@ -582,6 +585,7 @@ struct InitP {
     CorrP C;
     const float *bbox;        // [P][6]
     const int32_t *cand;      // [P][ncell][ck]
+    const uint8_t *ccnt;      // [P][ncell]: number of candidates of the cell
     const float4 *cinit;      // [P][ncell][ck][4]: initial state of every candidate (k_corr_init)
 };
 
@@ -617,18 +621,31 @@ __device__ __forceinline__ void read_record_J(const float4 *__restrict__ r, floa
 // Voxel-based initial states leave most lanes without a candidate (a ray sample in empty space has
 // none).  Pre-pass for the fused solve: candidates per point, prefix sum, then the list of pairs
 // that do have one, so that the solve kernel draws only those.
+// Per pose the lower corner of the box of node images and the size of a correspondence cell are put into LDS once per
+// block (the arithmetic of cell_index), and the number of candidates of a cell is one byte written by k_corr_select:
+// with the six box entries and the three candidate slots read per point through the vector cache -- nine gathered
+// loads of four bytes -- this kernel took 77 us on the 8-pose batch.
 __global__ __launch_bounds__(256) void k_voxel_count(GridP G, InitP I, long long N, const float *__restrict__ xq,
                                                      const int32_t *__restrict__ pose, int *__restrict__ cnt,
                                                      uint8_t *__restrict__ cnt8, int *__restrict__ gcell)
 {
+    extern __shared__ float s_pose[];            // [P][6]: lower corner, cell size
+    for (int i = threadIdx.x; i < G.P * 3; i += blockDim.x) {
+        const int p = i / 3, a = i - 3 * p;
+        const float *bb = I.bbox + p * 6;
+        const int na = a == 0 ? I.C.cx : (a == 1 ? I.C.cy : I.C.cz);
+        s_pose[p * 6 + a] = bb[a];
+        s_pose[p * 6 + 3 + a] = (bb[3 + a] - bb[a]) / (float)na;
+    }
+    __syncthreads();
     const long long n = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (n >= N) return;
     const int p = pose_of(pose, n, G.P);
-    const float xp[3] = {xq[n], xq[N + n], xq[2 * N + n]};
-    const int gc = p * I.C.ncell + cell_index(I.C, I.bbox + p * 6, xp);
-    const int32_t *c = I.cand + (long long)gc * I.C.ck;
-    int m = 0;
-    for (int k = 0; k < I.C.ck; ++k) m += c[k] >= 0 ? 1 : 0;     // candidates are packed at the front
+    const float *sp = s_pose + p * 6;
+    const int ci = (cell_coord(xq[n], sp[0], sp[3], I.C.cx) * I.C.cy + cell_coord(xq[N + n], sp[1], sp[4], I.C.cy)) * I.C.cz +
+                   cell_coord(xq[2 * N + n], sp[2], sp[5], I.C.cz);
+    const int gc = p * I.C.ncell + ci;
+    const int m = I.ccnt[gc];
     cnt[n] = m;
     cnt8[n] = (uint8_t)m;
     gcell[n] = gc;
