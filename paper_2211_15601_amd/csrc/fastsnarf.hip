@@ -38,7 +38,7 @@ struct fs_ctx {
     int *cell_of;      // [P][V]
     int *count;        // [P*ncell + 1] counts, then offsets
     int *fill;         // [P][V] arrival slot of a node inside its cell
-    int *order;        // [P][V]
+    float4 *order;     // [P][V] the nodes sorted by correspondence cell: {image[3], node index}
     int32_t *cand;     // [P][ncell][ck]
     uint8_t *ccnt;     // [P][ncell] number of candidates of a correspondence cell
     float4 *cinit;     // [P][ncell][ck][4] initial state of every candidate (k_corr_init)
@@ -296,6 +296,8 @@ fs_status fs_create(const fs_grid_desc *desc, const fs_params *params, void *hip
     G.sy = desc->nz * 12;
     G.sx = desc->ny * desc->nz * 12;
     G.V = V;
+    G.mag_ny = div_magic((unsigned)desc->ny);
+    G.mag_nz = div_magic((unsigned)desc->nz);
     const int n[3] = {desc->nx, desc->ny, desc->nz};
     for (int a = 0; a < 3; ++a) {
         G.lo[a] = desc->lo[a];
@@ -461,7 +463,7 @@ fs_status fs_precompute(fs_ctx *ctx, const float *d_W, const float *d_B)
         k_corr_bbox<<<G.P, 384, 0, st>>>(eblk, ctx->bb_ord, ctx->bbox);
         k_corr_count<<<gv, 256, 0, st>>>(G, C, ctx->Y, ctx->bbox, ctx->cell_of, ctx->count, ctx->fill);
         { fs_status ss = scan_exclusive(ctx, ncp, ctx->count); if (ss != FS_OK) return ss; }
-        k_corr_scatter<<<gv, 256, 0, st>>>(G, C, ctx->cell_of, ctx->count, ctx->fill, ctx->order);
+        k_corr_scatter<<<gv, 256, 0, st>>>(G, C, ctx->Y, ctx->cell_of, ctx->count, ctx->fill, ctx->order);
         k_corr_select<<<grid1d((long long)ncp * WAVE, 256), 256, 0, st>>>(G, C, ctx->Y, ctx->bbox, ctx->count, ctx->order, ctx->cand, ctx->ccnt);
         k_corr_init<<<grid1d((long long)ncp * C.ck, 256), 256, 0, st>>>(G, C, ctx->T, ctx->cand, ctx->cinit);
     }

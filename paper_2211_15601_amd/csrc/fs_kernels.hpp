@@ -447,15 +447,20 @@ __global__ __launch_bounds__(1024) void k_scan_tiles(int n, const int *a, int *o
     if (blockIdx.x == 0 && threadIdx.x == 0) out[n] = grand;
 }
 
-__global__ __launch_bounds__(256) void k_corr_scatter(GridP G, CorrP C, const int *__restrict__ cell_of,
-                                                      const int *__restrict__ offset, const int *__restrict__ slot,
-                                                      int *__restrict__ order)
+// Every node goes to its place in its cell's list as {image[3], node index}: the selection below then reads its
+// samples as consecutive 16-byte entries.  (With a list of node indices alone every sample cost three gathered 4-byte
+// loads of its image in each of the three passes: k_corr_select 127 us on the 8-pose grid.)
+__global__ __launch_bounds__(256) void k_corr_scatter(GridP G, CorrP C, const float *__restrict__ Y,
+                                                      const int *__restrict__ cell_of, const int *__restrict__ offset,
+                                                      const int *__restrict__ slot, float4 *__restrict__ sample)
 {
     const long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     const int p = blockIdx.y;
     if (v >= G.V) return;
-    const int c = p * C.ncell + cell_of[(long long)p * G.V + v];
-    order[offset[c] + slot[(long long)p * G.V + v]] = (int)v;
+    const long long i = (long long)p * G.V + v;
+    const int c = p * C.ncell + cell_of[i];
+    const float *y = Y + i * 3;
+    sample[offset[c] + slot[i]] = make_float4(y[0], y[1], y[2], __int_as_float((int)v));
 }
 
 // One wave per cell.  Candidate j is the sample with the smallest (distance^2 of its image to the
@@ -464,11 +469,14 @@ __global__ __launch_bounds__(256) void k_corr_scatter(GridP G, CorrP C, const in
 // greedily.
 __global__ __launch_bounds__(256) void k_corr_select(GridP G, CorrP C, const float *__restrict__ Y,
                                                      const float *__restrict__ bbox, const int *__restrict__ offset,
-                                                     const int *__restrict__ order, int32_t *__restrict__ cand,
+                                                     const float4 *__restrict__ sample, int32_t *__restrict__ cand,
                                                      uint8_t *__restrict__ ccnt)
 {
+    // accepted candidates' positions, per wave: the same for all lanes and indexed by a loop counter -- in registers
+    // that indexing turns into chains of selects, from LDS it is one broadcast read per candidate
+    __shared__ float4 s_acc[4][FS_MAX_CORR_K_DEV];
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    const int lane = threadIdx.x & 63;
+    const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
     if (wave >= G.P * C.ncell) return;
     const int p = wave / C.ncell, c = wave - p * C.ncell;
     const float *bb = bbox + p * 6;
@@ -480,25 +488,25 @@ __global__ __launch_bounds__(256) void k_corr_select(GridP G, CorrP C, const flo
     const float ctr[3] = {FS_FMA((float)cix + 0.5f, cs0, bb[0]), FS_FMA((float)ciy + 0.5f, cs1, bb[1]),
                           FS_FMA((float)ciz + 0.5f, cs2, bb[2])};
     const float rs2 = 6.25f * FS_FMA(G.h[2], G.h[2], FS_FMA(G.h[1], G.h[1], G.h[0] * G.h[0]));
-    float acc[FS_MAX_CORR_K_DEV][3];
     int na = 0;
     int32_t *out = cand + (long long)wave * C.ck;
     for (int j = 0; j < C.ck; ++j) {
         float bkey = __builtin_inff();
         int bv = 0x7fffffff;
         for (int s = beg + lane; s < end; s += WAVE) {
-            const int v = order[s];
+            const float4 sm = sample[s];
+            const int v = __float_as_int(sm.w);
             float x[3];
             node_pos(G, v, x);
             bool far = true;
             for (int a = 0; a < na; ++a) {
-                const float ex = x[0] - acc[a][0], ey = x[1] - acc[a][1], ez = x[2] - acc[a][2];
+                const float4 ac = s_acc[wib][a];
+                const float ex = x[0] - ac.x, ey = x[1] - ac.y, ez = x[2] - ac.z;
                 const float d2 = FS_FMA(ez, ez, FS_FMA(ey, ey, ex * ex));
                 if (!(d2 > rs2)) far = false;
             }
             if (!far) continue;
-            const float *yp = Y + ((long long)p * G.V + v) * 3;
-            const float dx = yp[0] - ctr[0], dy = yp[1] - ctr[1], dz = yp[2] - ctr[2];
+            const float dx = sm.x - ctr[0], dy = sm.y - ctr[1], dz = sm.z - ctr[2];
             const float key = FS_FMA(dz, dz, FS_FMA(dy, dy, dx * dx));
             if (key < bkey || (key == bkey && v < bv)) { bkey = key; bv = v; }
         }
@@ -509,7 +517,11 @@ __global__ __launch_bounds__(256) void k_corr_select(GridP G, CorrP C, const flo
             if (ok < bkey || (ok == bkey && ov < bv)) { bkey = ok; bv = ov; }
         }
         if (bv == 0x7fffffff) break;     // wave-uniform
-        node_pos(G, bv, acc[na]);
+        float xa[3];
+        node_pos(G, bv, xa);
+        if (lane == 0) s_acc[wib][na] = make_float4(xa[0], xa[1], xa[2], 0.0f);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
         ++na;
         if (lane == 0) out[j] = bv;
     }
