@@ -21,26 +21,30 @@ constexpr int FS_MAX_CORR_K_DEV = 8;
 // wave-uniform addresses, i.e. through the scalar cache into SGPR operands of the multiply-adds.
 // Reads W once (96 B / node for 24 bones), writes 48 B per node and pose.
 // ------------------------------------------------------------------------------------------------
-// Every thread of a 256-thread block holds one row of NF floats (NF = 12: a 48-byte record; NF = 3: a point) of a
-// tile whose rows are contiguous in memory (row r of the tile at dst + r * NF).  Stored straight from registers, a row goes
-// out as 16-byte pieces at a 48-byte stride: partial writes of cache lines, for which the L2 first fetches the line (on
-// the 8-pose 128x128x32 grid k_precompute fetched 386 MB to read 50 MB of weights).  Through LDS the tile leaves as
-// whole, consecutive 16-byte pieces from consecutive threads.  nrows = valid rows of the tile (block-uniform); all
-// threads of the block must call.  s_tile: 256 * NF floats of LDS.
+// Every lane of a wave holds one row of NF floats (NF = 12: a 48-byte record; NF = 3: a point) of a tile whose rows are
+// contiguous in memory (row r of the wave's tile at dst + r * NF).  Stored straight from registers, a row goes out as
+// 16-byte pieces at a 48-byte stride: partial writes of cache lines, for which the L2 first fetches the line (on the
+// 8-pose 128x128x32 grid k_precompute fetched 386 MB to read 50 MB of weights).  Through LDS the tile leaves as whole,
+// consecutive 16-byte pieces from consecutive lanes.  nrows = valid rows of the wave's tile (wave-uniform; <= 0: none).
+// s_tile: 64 * NF floats of LDS that belong to this wave alone, so no barrier between waves is needed; all 64 lanes
+// must call.
 template <int NF>
-__device__ __forceinline__ void block_store_rows(float *__restrict__ dst, const float (&v)[NF], int nrows, float *s_tile)
+__device__ __forceinline__ void wave_store_rows(float *__restrict__ dst, const float (&v)[NF], int nrows, float *s_tile)
 {
-    __syncthreads();                               // s_tile may still be read from the call before
+    const int lane = threadIdx.x & 63;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");      // s_tile may still be read from the call before
+    __builtin_amdgcn_wave_barrier();
 #pragma unroll
-    for (int e = 0; e < NF; ++e) s_tile[threadIdx.x * NF + e] = v[e];
-    __syncthreads();
+    for (int e = 0; e < NF; ++e) s_tile[lane * NF + e] = v[e];
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
     const int n4 = nrows * NF / 4, tail = nrows * NF - n4 * 4;
     if ((reinterpret_cast<uintptr_t>(dst) & 15u) == 0) {
-        for (int i = threadIdx.x; i < n4; i += 256)
+        for (int i = lane; i < n4; i += 64)
             reinterpret_cast<float4 *>(dst)[i] = reinterpret_cast<const float4 *>(s_tile)[i];
-        if ((int)threadIdx.x < tail) dst[n4 * 4 + threadIdx.x] = s_tile[n4 * 4 + threadIdx.x];
+        if (lane < tail) dst[n4 * 4 + lane] = s_tile[n4 * 4 + lane];
     } else {
-        for (int i = threadIdx.x; i < nrows * NF; i += 256) dst[i] = s_tile[i];
+        for (int i = lane; i < nrows * NF; i += 64) dst[i] = s_tile[i];
     }
 }
 
@@ -63,6 +67,10 @@ __device__ __forceinline__ float ord2f(unsigned o)
 // Y (may be null; voxel-based initial states): the image y_v = T_v x_v of every node is written as well -- the
 // correspondence grid is built on those, and the transforms are in registers here anyway (a pass of its own would
 // read all of T again).
+#ifndef FS_PRE_POSES
+#define FS_PRE_POSES 4
+#endif
+constexpr int PRE_POSES = FS_PRE_POSES;     // poses that share one pass over a node's weights (8-pose grid: 2 -> 144 us, 4 -> 105, 8 -> 138)
 __global__ __launch_bounds__(256) void k_precompute(GridP G, const float *__restrict__ W,
                                                     const float *__restrict__ B, float *__restrict__ T,
                                                     float *__restrict__ Bcopy, float *__restrict__ Binv,
@@ -71,23 +79,24 @@ __global__ __launch_bounds__(256) void k_precompute(GridP G, const float *__rest
 {
     // *nonfinite = serial (the number of this call) tells the solve that this grid holds an entry that is not
     // finite: a record with weight zero may then not be skipped (0 * inf is not 0)
-    __shared__ float s_tile[256 * 12];
-    const long long v0 = (long long)blockIdx.x * blockDim.x, v = v0 + threadIdx.x;
+    __shared__ __attribute__((aligned(16))) float s_tiles[4][64 * 12];
+    float *s_tile = s_tiles[threadIdx.x >> 6];
+    const long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x, v0 = v - (threadIdx.x & 63);   // v0: the wave's first node
     for (long long i = v; i < (long long)G.P * G.nb; i += (long long)gridDim.x * blockDim.x)
         bone_inverse((int)i, B, Bcopy, Binv, Bok);
-    const bool live = v < G.V;                   // the last block: its other threads stay for the block-wide stores
-    const int nrows = (int)min(256ll, G.V - v0);
+    const bool live = v < G.V;                   // the last wave: its other lanes stay for the wave-wide stores
+    const int nrows = (int)min(64ll, G.V - v0);
     const float *w = W + (live ? v : 0) * G.nb;
     const bool vec = (G.nb & 3) == 0;        // weight rows are 16-byte aligned: read them four at a time
     float xv[3] = {0.0f, 0.0f, 0.0f};
     if (Y && live) node_pos(G, v, xv);
     // four poses share one pass over the node's weights; per pose the sum runs over the bones in order,
     // first term a product, the rest fused multiply-adds
-    for (int p0 = 0; p0 < G.P; p0 += 4) {
-        const int np = min(4, G.P - p0);
-        float acc[4][12];
+    for (int p0 = 0; p0 < G.P; p0 += PRE_POSES) {
+        const int np = min(PRE_POSES, G.P - p0);
+        float acc[PRE_POSES][12];
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
+        for (int q = 0; q < PRE_POSES; ++q)
 #pragma unroll
             for (int e = 0; e < 12; ++e) acc[q][e] = 0.0f;
         if (live) {
@@ -102,7 +111,7 @@ __global__ __launch_bounds__(256) void k_precompute(GridP G, const float *__rest
                         if (b0 + j < G.nb) wv[j] = w[b0 + j];
                 }
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
+                for (int q = 0; q < PRE_POSES; ++q) {
                     if (q < np) {
                         const float *Bp = B + (long long)(p0 + q) * G.nb * 12;
 #pragma unroll
@@ -122,19 +131,19 @@ __global__ __launch_bounds__(256) void k_precompute(GridP G, const float *__rest
             }
         }
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            if (q < np) {                        // block-uniform
+        for (int q = 0; q < PRE_POSES; ++q) {
+            if (q < np) {                        // wave-uniform
                 if (live) {
                     float big = 0.0f;
 #pragma unroll
                     for (int e = 0; e < 12; ++e) big = __builtin_fmaxf(big, __builtin_fabsf(acc[q][e]) < __builtin_inff() ? 0.0f : 1.0f);
                     if (big != 0.0f) *nonfinite = serial;
                 }
-                block_store_rows<12>(T + ((long long)(p0 + q) * G.V + v0) * 12, acc[q], nrows, s_tile);
+                wave_store_rows<12>(T + ((long long)(p0 + q) * G.V + v0) * 12, acc[q], nrows, s_tile);
                 if (Y) {
                     float y[3] = {0.0f, 0.0f, 0.0f};
                     if (live) apply12(acc[q], xv, y);
-                    block_store_rows<3>(Y + ((long long)(p0 + q) * G.V + v0) * 3, y, nrows, s_tile);
+                    wave_store_rows<3>(Y + ((long long)(p0 + q) * G.V + v0) * 3, y, nrows, s_tile);
                 }
             }
         }
@@ -2276,10 +2285,10 @@ __global__ __launch_bounds__(256) void k_grad_nodes_z(GridP G, int ncell, const 
             if (a != b) grad_cell_pair<false, true>(G, rec, a, b, ab, cx, cy, iz - 1, up, acc);
         }
     }
-    // the block's 256 records are contiguous: they leave as whole cache lines
-    __shared__ float s_tile[256 * 12];
-    const long long i0 = (long long)blockIdx.x * blockDim.x;
-    block_store_rows<12>(GT + i0 * 12, acc, (int)min(256ll, (long long)G.P * G.V - i0), s_tile);
+    // the wave's 64 records are contiguous: they leave as whole cache lines
+    __shared__ __attribute__((aligned(16))) float s_tiles[4][64 * 12];
+    const long long i0 = i - lane;
+    wave_store_rows<12>(GT + i0 * 12, acc, (int)min(64ll, (long long)G.P * G.V - i0), s_tiles[threadIdx.x >> 6]);
 }
 
 // gW[v][b] = sum_p sum_e G_T[p][v][e] B[p][b][e]: one thread per node and group of 8 bones (groups of a node
