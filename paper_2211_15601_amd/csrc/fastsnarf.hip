@@ -298,6 +298,7 @@ fs_status fs_create(const fs_grid_desc *desc, const fs_params *params, void *hip
     G.V = V;
     G.mag_ny = div_magic((unsigned)desc->ny);
     G.mag_nz = div_magic((unsigned)desc->nz);
+    G.mag_V = div_magic((unsigned)V);          // n_poses * V * 12 < 2^31
     const int n[3] = {desc->nx, desc->ny, desc->nz};
     for (int a = 0; a < 3; ++a) {
         G.lo[a] = desc->lo[a];
@@ -678,7 +679,7 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
         (void)hipEventRecord(ev1, st);
         ctx->timed->emplace_back(ev0, ev1);
     }
-    const int ub = grid1d(S.total, 256);
+    const dim3 ub(grid1d(N, 256), K);       // one thread per pair: x = point, y = initial state
     if (with_J && voxel_list)
         k_solve_unpack<true, true><<<ub, 256, 0, st>>>(N, S.total, ctx->vcnt, ctx->srec, d_xc, d_conv, d_Jinv, d_iters, d_slot);
     else if (with_J)

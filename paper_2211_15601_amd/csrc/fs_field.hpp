@@ -13,7 +13,7 @@ struct GridP {
     int sx, sy;          // float strides between x- and y-neighbours (z-neighbours are 12 apart)
     long long V;         // nodes per pose
     float lo[3], hi[3], inv_h[3], h[3], m[3];   // m = n-1 as float
-    unsigned mag_ny, mag_nz;                    // floor(2^32 / ny), floor(2^32 / nz), at most 2^32 - 1 (div_magic)
+    unsigned mag_ny, mag_nz, mag_V;             // floor(2^32 / ny), floor(2^32 / nz), floor(2^32 / V), at most 2^32 - 1 (div_magic)
 };
 
 // v / d for a divisor that is the same for the whole launch, with m = div_magic(d) = min(floor(2^32 / d), 2^32 - 1):

@@ -738,9 +738,9 @@ __global__ __launch_bounds__(256) void k_solve_unpack(long long N, long long tot
                                                       uint8_t *__restrict__ o_conv, float *__restrict__ o_J,
                                                       uint8_t *__restrict__ o_it, int32_t *__restrict__ o_slot)
 {
-    const long long pq = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (pq >= total) return;
-    const long long k = pq / N, n = pq - k * N;
+    const long long n = (long long)blockIdx.x * blockDim.x + threadIdx.x, k = blockIdx.y;      // grid: points x initial states
+    if (n >= N) return;
+    const long long pq = k * N + n;
     bool have = true;
     if (NOCAND) have = k < cand_cnt[n];
     float4 a = make_float4(0.0f, 0.0f, 0.0f, 0.0f), b = a;
@@ -2098,9 +2098,10 @@ __global__ __launch_bounds__(256) void k_grad_nodes_p(GridP G, int ncell, const 
     const long long i = t / TPN;
     const int sub = (int)(t - i * TPN);
     if (i >= (long long)G.P * G.V) return;
-    const int p = (int)(i / G.V);
-    const long long v = i - (long long)p * G.V;
-    const int iz = (int)(v % G.nz), iy = (int)((v / G.nz) % G.ny), ix = (int)(v / ((long long)G.nz * G.ny));
+    const int p = (int)div_by((unsigned)i, (unsigned)G.V, G.mag_V);          // P * V < 2^31
+    const unsigned v = (unsigned)(i - (long long)p * G.V), tz = div_by(v, (unsigned)G.nz, G.mag_nz);
+    const int iz = (int)(v - tz * (unsigned)G.nz), ix = (int)div_by(tz, (unsigned)G.ny, G.mag_ny);
+    const int iy = (int)(tz - (unsigned)ix * (unsigned)G.ny);
     float acc[12];
 #pragma unroll
     for (int e = 0; e < 12; ++e) acc[e] = 0.0f;
@@ -2222,10 +2223,10 @@ __global__ __launch_bounds__(256) void k_grad_nodes_z(GridP G, int ncell, const 
     const bool valid = i < (long long)G.P * G.V;
     int p = 0, ix = 0, iy = 0, iz = 0;
     if (valid) {
-        p = (int)(i / G.V);
-        const unsigned v = (unsigned)(i - (long long)p * G.V), t = v / (unsigned)G.nz;
+        p = (int)div_by((unsigned)i, (unsigned)G.V, G.mag_V);          // P * V < 2^31
+        const unsigned v = (unsigned)(i - (long long)p * G.V), t = div_by(v, (unsigned)G.nz, G.mag_nz);
         iz = (int)(v - t * (unsigned)G.nz);
-        ix = (int)(t / (unsigned)G.ny);
+        ix = (int)div_by(t, (unsigned)G.ny, G.mag_ny);
         iy = (int)(t - (unsigned)ix * (unsigned)G.ny);
     }
     float acc[12], up[12];
