@@ -452,7 +452,7 @@ fs_status fs_precompute(fs_ctx *ctx, const float *d_W, const float *d_B)
         const int ncp0 = G.P * ctx->C.ncell;
         k_corr_reset<<<grid1d(ncp0, 256), 256, 0, st>>>(G.P, ctx->C.ncell, ctx->count);
     }
-    k_precompute<<<grid1d(G.V, 256), 256, 0, st>>>(G, d_W, d_B, ctx->T, ctx->Bdev, ctx->Binv, ctx->Bok,
+    k_precompute<<<dim3(grid1d(G.V, 256), (G.P + PRE_POSES - 1) / PRE_POSES), 256, 0, st>>>(G, d_W, d_B, ctx->T, ctx->Bdev, ctx->Binv, ctx->Bok,
                                                    reinterpret_cast<int *>(ctx->cursor + CUR_NONFINITE), ctx->pre_serial,
                                                    voxel ? ctx->Y : nullptr);
     if (voxel) {

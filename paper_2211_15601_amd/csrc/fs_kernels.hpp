@@ -82,8 +82,9 @@ __global__ __launch_bounds__(256) void k_precompute(GridP G, const float *__rest
     __shared__ __attribute__((aligned(16))) float s_tiles[4][64 * 12];
     float *s_tile = s_tiles[threadIdx.x >> 6];
     const long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x, v0 = v - (threadIdx.x & 63);   // v0: the wave's first node
-    for (long long i = v; i < (long long)G.P * G.nb; i += (long long)gridDim.x * blockDim.x)
-        bone_inverse((int)i, B, Bcopy, Binv, Bok);
+    if (blockIdx.y == 0)
+        for (long long i = v; i < (long long)G.P * G.nb; i += (long long)gridDim.x * blockDim.x)
+            bone_inverse((int)i, B, Bcopy, Binv, Bok);
     const bool live = v < G.V;                   // the last wave: its other lanes stay for the wave-wide stores
     const int nrows = (int)min(64ll, G.V - v0);
     const float *w = W + (live ? v : 0) * G.nb;
@@ -92,7 +93,9 @@ __global__ __launch_bounds__(256) void k_precompute(GridP G, const float *__rest
     if (Y && live) node_pos(G, v, xv);
     // four poses share one pass over the node's weights; per pose the sum runs over the bones in order,
     // first term a product, the rest fused multiply-adds
-    for (int p0 = 0; p0 < G.P; p0 += PRE_POSES) {
+    // blockIdx.y = group of PRE_POSES poses: twice the waves of one block per node tile, in different phases of
+    // load, arithmetic and store at any one time
+    for (int p0 = blockIdx.y * PRE_POSES; p0 < G.P; p0 += gridDim.y * PRE_POSES) {
         const int np = min(PRE_POSES, G.P - p0);
         float acc[PRE_POSES][12];
 #pragma unroll
