@@ -173,7 +173,8 @@ class Case:
 def resolution_sweep(torch, binding, wl, dev):
     """Articulation time (fs_precompute + fs_solve, fused initial states, roots + masks only) against the
     resolution of the weight grid, 200k points of the SMPL-scale scene."""
-    for dims in ((16, 16, 4), (32, 32, 8), (64, 64, 16), (128, 128, 32)):
+    out = []
+    for dims in ((16, 16, 4), (16, 16, 8), (32, 32, 8), (64, 64, 16), (128, 128, 32)):
         w = wl.make_config(2, n_points=200000, dims=dims)
         N, K = w.N, w.K
         ctx = binding.Context(w.dims, w.n_bones, w.lo, w.hi, tol=w.tol, div_thresh=w.div_thresh, max_iters=w.max_iters)
@@ -196,11 +197,13 @@ def resolution_sweep(torch, binding, wl, dev):
         e1.record()
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / 10
-        print(json.dumps({"sweep": "grid resolution", "grid": list(dims), "grid_bytes": dims[0] * dims[1] * dims[2] * 48,
-                          "points": N, "inits": K, "articulation_ms": ms, "points_per_s": N / (ms * 1e-3),
-                          "converged_pairs": int(cv.sum().item()),
-                          "lane_iterations": int(it.to(torch.int64).sum().item()) + N * K}))
+        out.append({"sweep": "grid resolution", "grid": list(dims), "grid_bytes": dims[0] * dims[1] * dims[2] * 48,
+                    "grid_in_lds": dims[0] * dims[1] * dims[2] * 48 <= LDS_GRID_MAX,
+                    "points": N, "inits": K, "articulation_ms": ms, "points_per_s": N / (ms * 1e-3),
+                    "converged_pairs": int(cv.sum().item()),
+                    "lane_iterations": int(it.to(torch.int64).sum().item()) + N * K})
         ctx.close()
+    return out
 
 
 def cpu_baseline(case, args):
@@ -255,6 +258,7 @@ def main():
     ap.add_argument("--probe-copy-mib", type=int, default=0,
                     help="after the timed region copy this many MiB device to device once (a kernel of known "
                          "traffic, for calibrating the FETCH_SIZE / WRITE_SIZE counters under rocprofv3)")
+    ap.add_argument("--no-sweep", action="store_true", help="leave the grid-resolution sweep out of the JSON line")
     ap.add_argument("--resolution-sweep", action="store_true",
                     help="instead of the benchmark: time fs_precompute + fs_solve for 200k posed points x 24 inits on "
                          "weight grids of 16x16x4 .. 128x128x32 (the shape of the paper's grid-resolution ablation, "
@@ -282,7 +286,8 @@ def main():
     torch.cuda.set_device(0)
 
     if args.resolution_sweep:
-        resolution_sweep(torch, binding, wl, dev)
+        for r in resolution_sweep(torch, binding, wl, dev):
+            print(json.dumps(r))
         return
 
     case = Case(args.config, args, torch, binding, wl, dev)
@@ -375,6 +380,11 @@ def main():
             del c
             torch.cuda.empty_cache()
         out["per_config"] = per
+    if not args.no_sweep and not args.no_per_config:
+        # fs_precompute + fs_solve (roots, masks, iteration counts) for 200 000 points x 24 initial states against the
+        # resolution of the grid: the shape of the paper's grid-resolution ablation (Table 2)
+        out["resolution_sweep"] = [{k: r[k] for k in ("grid", "grid_bytes", "grid_in_lds", "articulation_ms", "points_per_s")}
+                                   for r in resolution_sweep(torch, binding, wl, dev)]
     print(json.dumps(out))
 
 
