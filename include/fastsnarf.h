@@ -87,7 +87,7 @@ fs_status fs_set_params(fs_ctx *ctx, const fs_params *params);
 /* Launch-shape knobs of the solve kernel; results never depend on them.  chunk = lanes a wave draws
  * from the work cursor at a time (8..4096; every draw is one atomic on a single counter, which serves about
  * 1e8 of them per second, so small chunks make the counter the bottleneck), refill_min = idle SIMD lanes that trigger a refill
- * (1..64; until it is set: 8, or 32 for a grid held in LDS),
+ * (1..64; until it is set: 8, 24 for grids of more than 32 MiB, 32 for a grid held in LDS),
  * blocks_per_cu = resident 256-thread blocks per compute unit (capped by what the occupancy
  * query reports; until it is set the library takes 2, or 3 where it solves the shorter list of
  * voxel-based candidates on a grid of at most 32 MiB, or holds the grid in LDS); for these a value of 0

@@ -540,8 +540,7 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     const bool lds = (ctx->lds_grid && grid_bytes <= FS_LDS_GRID_MAX) || lds_big;
     // Launch shape.  Grid in LDS (k_solve): latency / ALU bound, every wave the registers allow, refill at 32 idle
     // lanes.  Grid read through the caches (k_solve_ws, bound by the vector-memory path): blocks of one producer and
-    // several consumers, 2 blocks per CU (measured: more waves that compute Eq. (8) only thrash the L1); consumers
-    // refill from their queue at 8 idle lanes (4 ... 16: no difference).
+    // several consumers, 2 blocks per CU (measured: more waves that compute Eq. (8) only thrash the L1).
     const bool voxel_list = fused && ctx->prm.init_mode == FS_INIT_VOXEL;     // the solve draws from the list of pairs that have a candidate
     // fused voxel-based candidates: the producer only looks initial states up (k_corr_init computed them once per pose)
     const bool vx = !lds && voxel_list;
@@ -550,7 +549,9 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     const int want_blocks = ctx->blocks_per_cu ? (lds ? std::max(ctx->blocks_per_cu, 3) : ctx->blocks_per_cu) : auto_blocks;
     const int occ = lds ? ctx->occ_blocks_per_cu : (vx ? ctx->occ_vx_blocks_per_cu : ctx->occ_ws_blocks_per_cu);
     const int per_cu = lds_big ? 1 : std::max(1, std::min(want_blocks, occ));
-    S.refill_min = ctx->refill_min ? ctx->refill_min : (lds ? 32 : 8);
+    // consumers of k_solve_ws refill from their queue at 8 idle lanes (8 ... 24: within 1 % on grids the L2 holds; 32 and
+    // more lose 3 ... 40 %); on grids beyond it at 24 (1.34 instead of 1.37 ms on the 8-pose batch; 48: 1.38)
+    S.refill_min = ctx->refill_min ? ctx->refill_min : (lds ? 32 : (grid_bytes > (32u << 20) ? 24 : 8));
     const int blocks = (int)std::min<long long>(grid1d(chunks, wpb), (long long)per_cu * ctx->n_cus);
     InitP I;
     I.mode = ctx->prm.init_mode;
