@@ -552,6 +552,7 @@ fs_status fs_solve(fs_ctx *ctx, const float *d_xq, const int32_t *d_pose, int64_
     // consumers of k_solve_ws refill from their queue at 8 idle lanes (8 ... 24: within 1 % on grids the L2 holds; 32 and
     // more lose 3 ... 40 %); on grids beyond it at 24 (1.34 instead of 1.37 ms on the 8-pose batch; 48: 1.38)
     S.refill_min = ctx->refill_min ? ctx->refill_min : (lds ? 32 : (grid_bytes > (32u << 20) ? 24 : 8));
+    S.prefetch = grid_bytes > (32u << 20);
     const int blocks = (int)std::min<long long>(grid1d(chunks, wpb), (long long)per_cu * ctx->n_cus);
     InitP I;
     I.mode = ctx->prm.init_mode;

@@ -599,6 +599,7 @@ struct SolveP {
     int point_major;     // order in which pairs are handed out
     int spin_limit;      // producer / consumer kernel: polls of a work queue before a wave gives up
     int xcd_ranges;      // producer / consumer kernel: the list is cut into 8 ranges, one per XCD, each with its own cursor
+    int prefetch;        // producer / consumer kernel: consumers ask for the next cell's records at the end of a pass
 };
 
 // What the fused variant needs to compute initial states itself (same arithmetic as k_init_*).
@@ -1672,6 +1673,18 @@ __global__ __launch_bounds__(64 * (NCONS + 1), 2) void k_solve_ws(GridP G, Solve
                 for (int r = 0; r < 3; ++r) {
                     dx[r] = -FS_FMA(J[r * 3 + 2], g[2], FS_FMA(J[r * 3 + 1], g[1], J[r * 3] * g[0]));
                     xt[r] = x[r] + dx[r];
+                }
+                if (!SKIP && S.prefetch) {
+                    // the corner records the next pass will need are asked for now: they travel while this pass parks
+                    // its results and the next one looks for work (q is free: its records went into d above).  On the
+                    // 8-pose grid, whose records come from beyond the L2: 1.34 -> 1.32 ms; on a grid the L2 holds the
+                    // second cell lookup costs more than the head start gains (0.172 -> 0.186 ms), hence the switch
+                    const Cell cn = locate(G, xt);
+                    const long long wn = (long long)(Tp - T) + cn.base;
+                    if (wn != held) {
+                        load_cell(Tp + cn.base, G, q);
+                        held = wn;
+                    }
                 }
             }
         }
