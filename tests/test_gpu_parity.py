@@ -600,16 +600,18 @@ def test_autograd_two_forwards_then_backward(lib, mode):
             gu.assert_grad_close(name, a.cpu().numpy(), b, f"{w.name} autograd mode {mode}")
 
 
-@pytest.mark.parametrize("n_points", [4 * 40000, 70001], ids=["ten_tiles", "fewer_chunks_than_blocks"])
+@pytest.mark.parametrize("n_points", [4 * 40000, 70001, 3001], ids=["ten_tiles", "fewer_chunks_than_blocks", "too_small_to_order"])
 def test_list_order_does_not_change_results(lib, n_points):
     # voxel-based candidates, fused: on request batches of 65,536 points and more are ordered by place with a counting
     # sort before the solve; every pair's result must be the same bits as with the list in point order, every lane must be written,
     # and the backward (cell positions from the solve) must agree with the oracle in both orders
     # 160,000 points: ten sort tiles, ragged; 70,001 points: fewer chunks of pairs than the GPU takes blocks, so the
-    # number of blocks is not a multiple of the 8 ranges of order 2
+    # number of blocks is not a multiple of the 8 ranges of order 2; 3,001 points: below the size from which the list is
+    # ordered at all (the setting is then ignored)
     w = wl.make_config(5, n_points=n_points, dims=(32, 32, 16), n_poses=4)
     pose = w.pose
     run = gu.GpuRun(w)
+    assert run.ctx.set_list_order(3, check=False) != 0 and run.ctx.set_list_order(-1, check=False) != 0      # 0, 1, 2 only
     T = run.precompute()
     outs = []
     for by_place in (1, 0, 2, 1):
